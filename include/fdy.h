@@ -1,0 +1,275 @@
+/*
+ * fdy.h - C ABI of the graph-context materialization core for MI355X (gfx950).
+ *
+ * The library turns the per-graph "parameter preparation" that the paper runs on
+ * CPU worker threads at LOAD time (Section 4.2.1, "Topology-based Intra-Rank Graph
+ * Grouping") into one-GPU data transforms, and relaxes the paper's identical-layout
+ * requirement (Section 4.1.1, "Deterministic Memory Layout"): when a new instance
+ * cannot be given the capture run's base addresses, every pointer embedded in the
+ * captured kernel-argument buffers is found by interval membership against the
+ * allocation table that the deterministic allocator records, and rebased.  The scan
+ * is kernel-agnostic on purpose: argument buffers are opaque byte arrays that may
+ * hide pointers inside library-private structs (Section 2.2; Appendix B shows one
+ * such 1720-byte buffer).
+ *
+ * Conventions that hold for every entry point
+ *  - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller owns
+ *    every buffer; the library never allocates or frees device memory, copies nothing
+ *    between host and device, and keeps no global state.
+ *  - Every call that takes a stream only ENQUEUES kernels on it (hipStream_t passed as
+ *    void*; NULL = the default stream).  Outputs are valid once the caller has
+ *    synchronized that stream.  Calls on one stream may be chained without host syncs:
+ *    device scalars produced by one call (reloc count, template count) are consumed by
+ *    the next from device memory.
+ *  - Return value: FDY_OK (0) or a negative FDY_ERR_* for errors the host can see
+ *    (null or misaligned pointers, sizes out of range, workspace too small, a failed
+ *    launch).  Errors only the device can see (an index out of range inside a device
+ *    table, more relocation hits than capacity) never cause an out-of-bounds access:
+ *    the offending entry is skipped and a FDY_ST_* bit is OR-ed into *d_status
+ *    (a device uint32_t the caller zeroes beforehand and reads after synchronizing;
+ *    may be NULL).
+ *  - All arithmetic is unsigned integer, modulo 2^64.  All data is little-endian.
+ *  - All structs below are plain data with natural alignment and no padding.
+ */
+#ifndef FDY_H
+#define FDY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FDY_VERSION 100 /* major*10000 + minor*100 + patch */
+
+/* ---- return codes ------------------------------------------------------------------ */
+#define FDY_OK 0
+#define FDY_ERR_INVALID_ARG (-1) /* null/misaligned pointer, size out of range        */
+#define FDY_ERR_TABLE (-2)       /* allocation table not sorted / overlapping / empty */
+#define FDY_ERR_CAPACITY (-3)    /* reserved: reported through FDY_ST_CAPACITY         */
+#define FDY_ERR_HIP (-4)         /* a HIP call or kernel launch failed                */
+#define FDY_ERR_WORKSPACE (-5)   /* workspace pointer null, misaligned or too small   */
+#define FDY_ERR_ORDER (-6)       /* a host list is not strictly ascending by location */
+
+/* ---- device status bits (OR-ed into *d_status) ------------------------------------- */
+#define FDY_ST_CAPACITY 0x1u  /* scan: more hits than reloc_capacity; *d_count = needed  */
+#define FDY_ST_BAD_INDEX 0x2u /* an entry's word/region/node/template index was out of
+                                 range and the entry was skipped                        */
+#define FDY_ST_BAD_SIZE 0x4u  /* materialize: out_words_per_map / out_nodes_total do not
+                                 equal the sums the device computed; nothing written     */
+#define FDY_ST_SPIN 0x8u      /* scan: a bounded wait on a predecessor tile ran out      */
+
+/* ---- plain-data records ------------------------------------------------------------ */
+
+/* One allocation of the deterministic layout: the half-open byte range [base, base+size).
+ * A table is sorted by strictly ascending base, has size >= 1, base+size does not wrap
+ * and ranges do not overlap (they may touch).  Section 4.1.1 / Section 5.1: allocations
+ * are placed one after another from a fixed base, so the record of them is such a table. */
+typedef struct {
+  uint64_t base;
+  uint64_t size;
+} fdy_alloc; /* 16 B */
+
+/* One kernel node of a captured graph, reduced to the fields the fingerprint and the
+ * launch-dimension output use (Appendix B lists the full record).  kernel_id stands for
+ * the (binary content hash, function name) key of Section 4.1.2.  flags carries the node
+ * type / kernel-node attributes that Section 5.3 counts as topology (bit 0: communication
+ * node). blob_len is the byte length of the node's argument buffer, a multiple of 8. */
+typedef struct {
+  uint64_t kernel_id;
+  uint32_t grid[3];
+  uint32_t block[3];
+  uint32_t blob_len;
+  uint32_t flags;
+} fdy_node; /* 40 B */
+
+/* One relocation: 8-byte word number `word` of the scanned array holds a pointer into
+ * allocation `region`, `offset` bytes above its base. */
+typedef struct {
+  uint32_t word;
+  uint32_t region;
+  uint64_t offset;
+} fdy_reloc; /* 16 B */
+
+/* Per-graph scalar override: store the 32-bit `value` at byte offset `byte_off`
+ * (a multiple of 4) of the graph's argument blob.  Section 3: graphs of one topology
+ * differ only in per-node parameters such as a batch-size argument. */
+typedef struct {
+  uint32_t byte_off;
+  uint32_t value;
+} fdy_ovr32; /* 8 B */
+
+/* Per-graph launch-dimension override: node `node` of the graph gets grid dims `grid`. */
+typedef struct {
+  uint32_t node;
+  uint32_t grid[3];
+} fdy_grid_ovr; /* 16 B */
+
+/* Rank-dependent 64-bit patch: 8-byte word `word` (relative to the template's first word)
+ * is replaced by `value` (communication handle, {rank,nranks}, peer-buffer address).
+ * Section 4.2.2: LOAD substitutes the real handle and updates rank-specific arguments. */
+typedef struct {
+  uint32_t word;
+  uint32_t reserved; /* must be 0 */
+  uint64_t value;
+} fdy_patch; /* 16 B */
+
+/* ---- fingerprint field mask -------------------------------------------------------- */
+#define FDY_FP_KERNEL_ID 0x01u
+#define FDY_FP_GRID_X 0x02u
+#define FDY_FP_GRID_Y 0x04u
+#define FDY_FP_GRID_Z 0x08u
+#define FDY_FP_BLOCK 0x10u
+#define FDY_FP_BLOB_LEN 0x20u
+#define FDY_FP_FLAGS 0x40u
+#define FDY_FP_ALL 0x7fu
+
+/* ---- library ----------------------------------------------------------------------- */
+
+/* FDY_VERSION of the built library. */
+int fdy_version(void);
+
+/* Static, NUL-terminated description of a return code (never NULL). */
+const char* fdy_strerror(int code);
+
+/* Host-side check of an allocation table held in HOST memory against the rules stated at
+ * fdy_alloc.  Returns FDY_OK, FDY_ERR_INVALID_ARG (null pointer with n_alloc > 0) or
+ * FDY_ERR_TABLE; on FDY_ERR_TABLE *h_bad_index (may be NULL) is the first offending entry.
+ * An empty table (n_alloc == 0) is valid: nothing is a pointer. */
+int fdy_table_validate(const fdy_alloc* h_table, uint32_t n_alloc, uint32_t* h_bad_index);
+
+/* ---- (a1) pointer scan -------------------------------------------------------------
+ * Classifies every 8-byte word of d_words against the allocation table and emits the
+ * relocation table (Section 4.1.1 and Section 2.2 give the need; the paper itself avoids
+ * the scan by forcing an identical layout).  For word j with value w, let i be the last
+ * table entry with base[i] <= w; j is a hit iff such i exists and w - base[i] < size[i].
+ * Hits are written to d_relocs in ascending j as {word=j, region=i, offset=w-base[i]}.
+ *
+ *   d_words          [n_words] device, 16-byte aligned; n_words <= 2^32
+ *   d_table          [n_alloc] device, 16-byte aligned, valid per fdy_table_validate
+ *                    (the caller validates; an invalid table gives unspecified relocation
+ *                    contents but no out-of-bounds access)
+ *   d_relocs         [reloc_capacity] device, 16-byte aligned
+ *   d_count          device uint64_t: total number of hits, also when it exceeds
+ *                    reloc_capacity (then only the first reloc_capacity entries are
+ *                    written and FDY_ST_CAPACITY is raised)
+ *   d_workspace      device, 256-byte aligned, at least fdy_scan_workspace_bytes() bytes;
+ *                    contents on entry are irrelevant, contents on exit are unspecified
+ *   d_status         device uint32_t or NULL
+ */
+size_t fdy_scan_workspace_bytes(uint64_t n_words, uint32_t n_alloc);
+int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
+                      uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
+                      uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
+                      uint32_t* d_status, void* hip_stream);
+
+/* ---- (a2) relocation segmentation ---------------------------------------------------
+ * For each boundary d_word_off[s], s in [0, n_off): d_reloc_off[s] = number of entries of
+ * d_relocs[0, min(*d_count, reloc_capacity)) whose word is < d_word_off[s] (lower bound in
+ * the ascending table).  With d_word_off = the archive's per-graph word offsets [G+1] this
+ * yields each graph's slice of the relocation table. */
+int fdy_reloc_segment(const fdy_reloc* d_relocs, const uint64_t* d_count,
+                      uint64_t reloc_capacity, const uint64_t* d_word_off, uint32_t n_off,
+                      uint64_t* d_reloc_off, void* hip_stream);
+
+/* ---- (b) topology fingerprint -------------------------------------------------------
+ * Section 4.2.1 / Section 5.3: a key per graph over its structural properties; graphs
+ * with equal keys form one group served by one template.  The paper leaves the key
+ * function open; this library fixes it as follows (all mod 2^64):
+ *   mix(x): x ^= x>>30; x *= 0xbf58476d1ce4e5b9; x ^= x>>27; x *= 0x94d049bb133111eb;
+ *           x ^= x>>31                      (the SplitMix64 output function)
+ *   P = 0x9e3779b97f4a7c15
+ *   node_hash(n): fields not selected by field_mask read as 0 (FDY_FP_BLOCK selects all
+ *           three block dims), then
+ *           a = mix(kernel_id + P);            a = mix(a ^ (grid[0]  | grid[1]  << 32));
+ *           a = mix(a ^ (grid[2] | block[0] << 32)); a = mix(a ^ (block[1] | block[2] << 32));
+ *           a = mix(a ^ (blob_len | flags << 32))
+ *   key(g): H = mix(N_g); for each node in order: H = H*P + node_hash(node); key = mix(H)
+ *   template_id[g]: dense id, in order of first appearance, of g's key
+ *   tmpl_graph[t]: the first graph (lowest index) whose template_id is t
+ *
+ *   d_nodes          device, 8-byte aligned; graph g owns nodes [d_node_off[g], d_node_off[g+1])
+ *   d_node_off       [n_graphs+1] device, non-decreasing
+ *   d_keys           [n_graphs] out
+ *   d_template_id    [n_graphs] out
+ *   d_tmpl_graph     [n_graphs] out (first *d_n_templates entries meaningful) or NULL
+ *   d_n_templates    device uint32_t out
+ *   n_graphs         <= 65536
+ */
+int fdy_fingerprint(const fdy_node* d_nodes, const uint64_t* d_node_off, uint32_t n_graphs,
+                    uint32_t field_mask, uint64_t* d_keys, uint32_t* d_template_id,
+                    uint32_t* d_tmpl_graph, uint32_t* d_n_templates, void* hip_stream);
+
+/* ---- (c) template materialization ---------------------------------------------------
+ * For every base map m and every output graph g (Section 4.2.1: prepare the parameter
+ * sets of the non-template graphs; Section 4.2.2: patch rank-dependent state), in this
+ * stage order, a later stage overwriting an earlier one at the same location:
+ *   c1  out[m][g]        = copy of the argument blob of template t = graph_tmpl[g]
+ *   c2  out[m][g][k]     = new_base[m][region] + offset   for each reloc of the template,
+ *                          k = reloc.word - (first word of the template)
+ *   c3  store32(out[m][g] bytes, byte_off, value)          for each override of graph g
+ *   c4  out[m][g][word]  = value   for each patch of (t, map_rank[m]), if map_rank != NULL
+ * and, once per graph (launch dims do not depend on the map):
+ *   dims[g][n] = {grid xyz, block xyz} of the template's node n, then grid replaced for
+ *                each grid override of graph g.
+ *
+ * The template of id t is source graph s = tmpl_graph[t] of the "source archive": words
+ * [src_word_off[s], src_word_off[s+1]) of src_words, nodes [src_node_off[s], ..[s+1]) of
+ * src_nodes, relocs [src_reloc_off[s], ..[s+1]) of relocs with reloc.word indexing
+ * src_words (exactly what fdy_scan_pointers + fdy_reloc_segment produce for the archive).
+ * Each reloc / override / patch list is strictly ascending by location.
+ *
+ * Output layout: d_out_words is [n_maps][out_words_per_map], map-major; inside a map the
+ * graphs follow in order g = 0..n_graphs-1, each with the word count of its template.
+ * d_out_dims is [out_nodes_total][6] uint32 (grid xyz, block xyz), graphs in order, or
+ * NULL to skip the dims output.
+ */
+typedef struct {
+  /* host scalars */
+  uint32_t n_src_graphs; /* S: graphs in the source archive arrays                   */
+  uint32_t n_templates;  /* T                                                          */
+  uint32_t n_graphs;     /* G: output graphs per map                                   */
+  uint32_t n_maps;       /* M                                                          */
+  uint32_t n_alloc;      /* A: regions per base map                                    */
+  uint32_t n_ranks;      /* R: rank patch tables per template (0 when map_rank==NULL)  */
+  uint64_t out_words_per_map; /* sum over g of words(template(g))                      */
+  uint64_t out_nodes_total;   /* sum over g of nodes(template(g)); 0 if d_out_dims NULL */
+  /* device arrays */
+  const uint64_t* src_words;     /* 16-byte aligned                                    */
+  const uint64_t* src_word_off;  /* [S+1]                                              */
+  const fdy_node* src_nodes;     /* may be NULL when d_out_dims is NULL                */
+  const uint64_t* src_node_off;  /* [S+1]                                              */
+  const fdy_reloc* relocs;       /* 16-byte aligned                                    */
+  const uint64_t* src_reloc_off; /* [S+1]                                              */
+  const uint32_t* tmpl_graph;    /* [T] source graph of each template                  */
+  const uint32_t* graph_tmpl;    /* [G] template of each output graph                  */
+  const fdy_ovr32* ovr;          /* overrides, all graphs concatenated                 */
+  const uint64_t* ovr_off;       /* [G+1]                                              */
+  const fdy_grid_ovr* govr;      /* grid overrides, all graphs concatenated            */
+  const uint64_t* govr_off;      /* [G+1]                                              */
+  const uint64_t* new_base;      /* [M][A] row-major                                   */
+  const uint32_t* map_rank;      /* [M] rank of each map, or NULL: no patches          */
+  const fdy_patch* patch;        /* patches, index t*R+r concatenated                  */
+  const uint64_t* patch_off;     /* [T*R+1]                                            */
+} fdy_mat_desc;
+
+/* Workspace size for fdy_materialize with this descriptor (only the host scalars are
+ * read).  0 is returned for a descriptor whose scalars are out of range. */
+size_t fdy_materialize_workspace_bytes(const fdy_mat_desc* h_desc);
+
+/*   h_desc       HOST struct; read during the call only
+ *   d_out_words  device, 16-byte aligned, n_maps*out_words_per_map words
+ *   d_out_dims   device, 8-byte aligned, out_nodes_total*6 uint32, or NULL
+ *   d_workspace  device, 256-byte aligned, >= fdy_materialize_workspace_bytes(h_desc)
+ *   d_status     device uint32_t or NULL
+ * Limits: n_graphs, n_src_graphs, n_templates <= 2^20; n_maps <= 65535; every template
+ * < 2^32 words; out_words_per_map < 2^40. */
+int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words, uint32_t* d_out_dims,
+                    void* d_workspace, size_t workspace_bytes, uint32_t* d_status,
+                    void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FDY_H */
