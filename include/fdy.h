@@ -146,7 +146,7 @@ int fdy_table_validate(const fdy_alloc* h_table, uint32_t n_alloc, uint32_t* h_b
  * table entry with base[i] <= w; j is a hit iff such i exists and w - base[i] < size[i].
  * Hits are written to d_relocs in ascending j as {word=j, region=i, offset=w-base[i]}.
  *
- *   d_words          [n_words] device, 16-byte aligned; n_words <= 2^32
+ *   d_words          [n_words] device, 16-byte aligned; n_words <= 2^32 - 256
  *   d_table          [n_alloc] device, 16-byte aligned, valid per fdy_table_validate
  *                    (the caller validates; an invalid table gives unspecified relocation
  *                    contents but no out-of-bounds access)

@@ -1,0 +1,59 @@
+// fdy_api.hip - version, error strings, host-side table validation, tuning knobs.
+#include "fdy_device.hpp"
+#include "fdy_tune.h"
+
+namespace {
+int g_tune[FDY_TUNE_COUNT] = {
+    /* SCAN_TOP_LOG2   */ 12,
+    /* SCAN_WG_PER_CU  */ 2,
+    /* SCAN_SPIN_LIMIT */ 1 << 20,
+    /* MAT_VARIANT     */ 0,
+    0, 0, 0, 0};
+const int g_tune_lo[FDY_TUNE_COUNT] = {1, 1, 0, 0, 0, 0, 0, 0};
+const int g_tune_hi[FDY_TUNE_COUNT] = {13, 16, 1 << 30, 8, 0, 0, 0, 0};
+}  // namespace
+
+extern "C" int fdy__tune_get(int knob) {
+  return knob >= 0 && knob < FDY_TUNE_COUNT ? g_tune[knob] : -1;
+}
+
+extern "C" int fdy__tune_set(int knob, int value) {
+  if (knob < 0 || knob >= FDY_TUNE_COUNT) return -1;
+  if (value < g_tune_lo[knob] || value > g_tune_hi[knob]) return -1;
+  const int old = g_tune[knob];
+  g_tune[knob] = value;
+  return old;
+}
+
+extern "C" int fdy_version(void) { return FDY_VERSION; }
+
+extern "C" const char* fdy_strerror(int code) {
+  switch (code) {
+    case FDY_OK: return "ok";
+    case FDY_ERR_INVALID_ARG: return "invalid argument (null or misaligned pointer, size out of range)";
+    case FDY_ERR_TABLE: return "allocation table is not strictly ascending, non-empty, non-wrapping and non-overlapping";
+    case FDY_ERR_CAPACITY: return "relocation capacity exceeded";
+    case FDY_ERR_HIP: return "a HIP call or kernel launch failed";
+    case FDY_ERR_WORKSPACE: return "workspace is null, misaligned or too small";
+    case FDY_ERR_ORDER: return "a list is not strictly ascending by location";
+    default: return "unknown fdy error code";
+  }
+}
+
+extern "C" int fdy_table_validate(const fdy_alloc* h_table, uint32_t n_alloc, uint32_t* h_bad_index) {
+  if (n_alloc == 0) return FDY_OK;
+  if (!h_table) return FDY_ERR_INVALID_ARG;
+  uint64_t prev_end = 0;
+  for (uint32_t i = 0; i < n_alloc; ++i) {
+    const uint64_t b = h_table[i].base, s = h_table[i].size;
+    const uint64_t end = b + s;
+    // size >= 1 and no wrap  <=>  end > b ; sorted + disjoint  <=>  b >= previous end
+    // (and strictly above the previous base, which previous size >= 1 already implies)
+    if (!(end > b) || (i > 0 && b < prev_end)) {
+      if (h_bad_index) *h_bad_index = i;
+      return FDY_ERR_TABLE;
+    }
+    prev_end = end;
+  }
+  return FDY_OK;
+}

@@ -1,0 +1,375 @@
+// fdy_materialize.hip - (c) template materialization for gfx950.
+//
+// Section 4.2.1 prepares, at LOAD time, the parameter set of every non-template graph on
+// CPU worker threads; Section 4.2.2 patches rank-dependent communication arguments.  Here
+// the same preparation is one streaming pass on the GPU over all (base map, graph, tile)
+// units, bounded by the HBM write of the output:
+//
+//   prep A (one workgroup)   prefix sums over the output graphs: where each graph's words,
+//                            nodes and tiles start; verifies the caller's totals.
+//   prep B (one wave / tile) resolves each output tile once, independent of the base map:
+//                            its graph, template, source words, and the sub-ranges of the
+//                            template's relocation list, the graph's override list and each
+//                            rank's patch list that fall inside the tile (wave-cooperative
+//                            64-ary lower bounds).
+//   main  (tile x map)       stages the template tile in LDS, scatters c2 rebased pointers
+//                            (new_base[m][region] + offset), c3 32-bit overrides and c4
+//                            64-bit rank patches into LDS in that order, then streams the
+//                            tile out with coalesced stores.  Templates, relocation lists
+//                            and base maps are re-read per map from L2 / Infinity Cache;
+//                            only the output is compulsory HBM traffic.
+//   dims  (one thread / node) launch dimensions of the template with grid overrides.
+#include "fdy_device.hpp"
+#include "fdy_tune.h"
+
+namespace fdy {
+namespace {
+
+constexpr int kMatTile = 2048;  // words per tile (16 KiB)
+constexpr int kMatBlock = 256;
+
+struct __attribute__((aligned(16))) MatTile {  // 64 B
+  u64 src_word;  // index into src_words of the tile's first word
+  u64 out_word;  // word offset of the tile inside one map's output
+  u32 n_words;   // 0: unused entry
+  u32 g, tmpl, k0;
+  u32 reloc_lo, reloc_hi, ovr_lo, ovr_hi;
+  u32 pad[4];
+};
+static_assert(sizeof(MatTile) == 64, "MatTile");
+
+struct MatHeader {
+  u32 n_tiles;
+  u32 ok;
+};
+
+struct MatWs {
+  MatHeader* hdr;
+  u64* out_word_off;  // [G+1]
+  u64* out_node_off;  // [G+1]
+  u64* tile_off;      // [G+1]
+  MatTile* tiles;     // [max_tiles]
+  uint2* tile_patch;  // [max_tiles * R]
+  u32 max_tiles;
+};
+
+struct MatParams {
+  fdy_mat_desc d;
+  MatWs ws;
+  u64* out_words;
+  u32* out_dims;
+  u32* d_status;
+};
+
+// Exclusive scan of one u64 per thread over a 1024-thread workgroup; returns the exclusive
+// prefix and sets `total` (same in every thread).  s_buf: 17 u64 of LDS.
+__device__ u64 block_excl_scan_1024(u64 v, u64* s_buf, u64& total) {
+  const u32 l = lane_id(), w = threadIdx.x >> 6;
+  u64 inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const u64 o = __shfl_up(inc, d);
+    if (l >= (u32)d) inc += o;
+  }
+  if (l == 63) s_buf[w] = inc;
+  __syncthreads();
+  if (w == 0) {
+    const u64 x = l < 16 ? s_buf[l] : 0;
+    u64 xi = x;
+#pragma unroll
+    for (int d = 1; d < 16; d <<= 1) {
+      const u64 o = __shfl_up(xi, d);
+      if (l >= (u32)d) xi += o;
+    }
+    if (l < 16) s_buf[l] = xi - x;
+    if (l == 15) s_buf[16] = xi;
+  }
+  __syncthreads();
+  const u64 r = s_buf[w] + inc - v;
+  total = s_buf[16];
+  __syncthreads();
+  return r;
+}
+
+__global__ __launch_bounds__(1024) void mat_prep_graphs_kernel(MatParams p) {
+  __shared__ u64 s_buf[17];
+  const fdy_mat_desc& d = p.d;
+  const u32 G = d.n_graphs;
+  u64 carry_w = 0, carry_n = 0, carry_t = 0;
+  bool bad = false;
+  for (u32 g0 = 0; g0 < G; g0 += 1024) {
+    const u32 g = g0 + threadIdx.x;
+    u64 nw = 0, nn = 0;
+    if (g < G) {
+      const u32 t = d.graph_tmpl[g];
+      const u32 s = t < d.n_templates ? d.tmpl_graph[t] : 0xffffffffu;
+      if (s < d.n_src_graphs) {
+        nw = d.src_word_off[s + 1] - d.src_word_off[s];
+        if (p.out_dims) nn = d.src_node_off[s + 1] - d.src_node_off[s];
+        if (nw >> 32) {  // a template must stay below 2^32 words
+          nw = 0;
+          nn = 0;
+          bad = true;
+        }
+      } else {
+        bad = true;
+      }
+    }
+    const u64 nt = (nw + kMatTile - 1) / kMatTile;
+    u64 tw, tn, tt;
+    const u64 ew = block_excl_scan_1024(nw, s_buf, tw);
+    const u64 en = block_excl_scan_1024(nn, s_buf, tn);
+    const u64 et = block_excl_scan_1024(nt, s_buf, tt);
+    if (g < G) {
+      p.ws.out_word_off[g] = carry_w + ew;
+      p.ws.out_node_off[g] = carry_n + en;
+      p.ws.tile_off[g] = carry_t + et;
+    }
+    carry_w += tw;
+    carry_n += tn;
+    carry_t += tt;
+  }
+  if (bad) raise_status(p.d_status, FDY_ST_BAD_INDEX);
+  if (threadIdx.x == 0) {
+    p.ws.out_word_off[G] = carry_w;
+    p.ws.out_node_off[G] = carry_n;
+    p.ws.tile_off[G] = carry_t;
+    bool ok = carry_w == d.out_words_per_map && carry_t <= p.ws.max_tiles;
+    if (p.out_dims && carry_n != d.out_nodes_total) ok = false;
+    if (!ok) raise_status(p.d_status, FDY_ST_BAD_SIZE);
+    p.ws.hdr->n_tiles = ok ? (u32)carry_t : 0u;
+    p.ws.hdr->ok = ok ? 1u : 0u;
+  }
+}
+
+__global__ __launch_bounds__(256) void mat_prep_tiles_kernel(MatParams p) {
+  const fdy_mat_desc& d = p.d;
+  const u32 j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (j >= p.ws.max_tiles) return;
+  const u32 l = lane_id();
+  MatTile* ent = &p.ws.tiles[j];
+  if (j >= p.ws.hdr->n_tiles) {
+    if (l == 0) ent->n_words = 0;
+    return;
+  }
+  const u64* tile_off = p.ws.tile_off;
+  // largest g with tile_off[g] <= j
+  const u32 g =
+      wave_lower_bound([&](u32 i) { return tile_off[i]; }, 0u, d.n_graphs + 1u, (u64)j + 1) - 1;
+  const u32 t = d.graph_tmpl[g];
+  const u32 s = d.tmpl_graph[t];  // valid: graphs with a bad template have no tiles
+  const u64 w0 = d.src_word_off[s];
+  const u64 nw = d.src_word_off[s + 1] - w0;
+  const u64 k0 = ((u64)j - tile_off[g]) * kMatTile;
+  const u32 n = (u32)((nw - k0) < (u64)kMatTile ? (nw - k0) : (u64)kMatTile);
+  const u64 src_word = w0 + k0;
+  const fdy_reloc* relocs = d.relocs;
+  const u32 rl0 = (u32)d.src_reloc_off[s], rl1 = (u32)d.src_reloc_off[s + 1];
+  const u32 reloc_lo = wave_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, rl0, rl1, src_word);
+  const u32 reloc_hi =
+      wave_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, reloc_lo, rl1, src_word + n);
+  const fdy_ovr32* ovr = d.ovr;
+  const u32 ov0 = (u32)d.ovr_off[g], ov1 = (u32)d.ovr_off[g + 1];
+  const u32 ovr_lo = wave_lower_bound([&](u32 i) { return (u64)ovr[i].byte_off; }, ov0, ov1, k0 * 8);
+  const u32 ovr_hi =
+      wave_lower_bound([&](u32 i) { return (u64)ovr[i].byte_off; }, ovr_lo, ov1, (k0 + n) * 8);
+  if (d.map_rank) {
+    const fdy_patch* patch = d.patch;
+    for (u32 r = 0; r < d.n_ranks; ++r) {
+      const u64 row = (u64)t * d.n_ranks + r;
+      const u32 p0 = (u32)d.patch_off[row], p1 = (u32)d.patch_off[row + 1];
+      const u32 lo = wave_lower_bound([&](u32 i) { return (u64)patch[i].word; }, p0, p1, k0);
+      const u32 hi = wave_lower_bound([&](u32 i) { return (u64)patch[i].word; }, lo, p1, k0 + n);
+      if (l == 0) p.ws.tile_patch[(u64)j * d.n_ranks + r] = make_uint2(lo, hi);
+    }
+  }
+  if (l == 0) {
+    MatTile e;
+    e.src_word = src_word;
+    e.out_word = p.ws.out_word_off[g] + k0;
+    e.n_words = n;
+    e.g = g;
+    e.tmpl = t;
+    e.k0 = (u32)k0;
+    e.reloc_lo = reloc_lo;
+    e.reloc_hi = reloc_hi;
+    e.ovr_lo = ovr_lo;
+    e.ovr_hi = ovr_hi;
+    e.pad[0] = e.pad[1] = e.pad[2] = e.pad[3] = 0;
+    *ent = e;
+  }
+}
+
+__global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
+  __shared__ __align__(16) u64 buf[kMatTile];
+  const fdy_mat_desc& d = p.d;
+  const u32 j = blockIdx.x, m = blockIdx.y, tid = threadIdx.x;
+  const MatTile ent = p.ws.tiles[j];
+  const u32 n = ent.n_words;
+  if (n == 0) return;
+  const u64* src = d.src_words + ent.src_word;
+  for (u32 i = tid; i < n; i += kMatBlock) buf[i] = src[i];
+  __syncthreads();
+  // c2: rebase
+  const u64* nb = d.new_base + (u64)m * d.n_alloc;
+  bool bad = false;
+  for (u32 q = ent.reloc_lo + tid; q < ent.reloc_hi; q += kMatBlock) {
+    const u64x2 raw = *reinterpret_cast<const u64x2*>(&d.relocs[q]);
+    const u32 word = (u32)raw.x, region = (u32)(raw.x >> 32);
+    const u64 k = (u64)word - ent.src_word;
+    if (k < n && region < d.n_alloc) buf[k] = nb[region] + raw.y;
+    else bad = true;
+  }
+  __syncthreads();
+  // c3: 32-bit overrides
+  u32* buf32 = reinterpret_cast<u32*>(buf);
+  for (u32 q = ent.ovr_lo + tid; q < ent.ovr_hi; q += kMatBlock) {
+    const fdy_ovr32 o = d.ovr[q];
+    const u64 b = (u64)o.byte_off - (u64)ent.k0 * 8;
+    if ((b >> 3) < n && (b & 3) == 0) buf32[b >> 2] = o.value;
+    else bad = true;
+  }
+  __syncthreads();
+  // c4: rank patches
+  if (d.map_rank) {
+    const u32 rk = d.map_rank[m];
+    if (rk < d.n_ranks) {
+      const uint2 pr = p.ws.tile_patch[(u64)j * d.n_ranks + rk];
+      for (u32 q = pr.x + tid; q < pr.y; q += kMatBlock) {
+        const u64x2 raw = *reinterpret_cast<const u64x2*>(&d.patch[q]);
+        const u64 k = (u64)(u32)raw.x - ent.k0;
+        if (k < n) buf[k] = raw.y;
+        else bad = true;
+      }
+    } else {
+      bad = true;
+    }
+    __syncthreads();
+  }
+  if (bad) raise_status(p.d_status, FDY_ST_BAD_INDEX);
+  u64* out = p.out_words + (u64)m * d.out_words_per_map + ent.out_word;
+  for (u32 i = tid; i < n; i += kMatBlock) out[i] = buf[i];
+}
+
+__global__ __launch_bounds__(256) void mat_dims_kernel(MatParams p) {
+  const fdy_mat_desc& d = p.d;
+  if (!p.ws.hdr->ok) return;
+  const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;
+  if (i >= d.out_nodes_total) return;
+  // largest g with out_node_off[g] <= i
+  const u64* off = p.ws.out_node_off;
+  u32 lo = 0, hi = d.n_graphs;  // answer in [lo, hi)
+  while (hi - lo > 1) {
+    const u32 mid = lo + (hi - lo) / 2;
+    if (off[mid] <= i) lo = mid;
+    else hi = mid;
+  }
+  const u32 g = lo;
+  const u32 n = (u32)(i - off[g]);
+  const u32 s = d.tmpl_graph[d.graph_tmpl[g]];
+  const fdy_node nd = d.src_nodes[d.src_node_off[s] + n];
+  u32 gx = nd.grid[0], gy = nd.grid[1], gz = nd.grid[2];
+  // grid override of this node, if any (list ascending by node)
+  u64 a = d.govr_off[g], b = d.govr_off[g + 1];
+  while (a < b) {
+    const u64 mid = a + (b - a) / 2;
+    if (d.govr[mid].node < n) a = mid + 1;
+    else b = mid;
+  }
+  if (a < d.govr_off[g + 1] && d.govr[a].node == n) {
+    gx = d.govr[a].grid[0];
+    gy = d.govr[a].grid[1];
+    gz = d.govr[a].grid[2];
+  }
+  uint2* o = reinterpret_cast<uint2*>(p.out_dims + i * 6);
+  o[0] = make_uint2(gx, gy);
+  o[1] = make_uint2(gz, nd.block[0]);
+  o[2] = make_uint2(nd.block[1], nd.block[2]);
+}
+
+bool desc_ok(const fdy_mat_desc* d) {
+  if (!d) return false;
+  if (d->n_graphs > (1u << 20) || d->n_src_graphs > (1u << 20) || d->n_templates > (1u << 20))
+    return false;
+  if (d->n_maps > 65535u) return false;
+  if (d->out_words_per_map >= (1ull << 40)) return false;
+  return true;
+}
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+size_t layout(const fdy_mat_desc* d, unsigned char* base, MatWs* ws) {
+  const u64 max_tiles = (d->out_words_per_map + kMatTile - 1) / kMatTile + d->n_graphs;
+  const u32 R = d->map_rank ? d->n_ranks : 0;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    unsigned char* p = base ? base + off : nullptr;
+    off += align256(bytes);
+    return p;
+  };
+  MatWs w;
+  w.hdr = (MatHeader*)take(sizeof(MatHeader));
+  w.out_word_off = (u64*)take(((size_t)d->n_graphs + 1) * 8);
+  w.out_node_off = (u64*)take(((size_t)d->n_graphs + 1) * 8);
+  w.tile_off = (u64*)take(((size_t)d->n_graphs + 1) * 8);
+  w.tiles = (MatTile*)take((size_t)max_tiles * sizeof(MatTile));
+  w.tile_patch = (uint2*)take((size_t)max_tiles * R * sizeof(uint2));
+  w.max_tiles = (u32)max_tiles;
+  if (ws) *ws = w;
+  return off;
+}
+
+}  // namespace
+}  // namespace fdy
+
+using namespace fdy;
+
+extern "C" size_t fdy_materialize_workspace_bytes(const fdy_mat_desc* h_desc) {
+  if (!desc_ok(h_desc)) return 0;
+  return layout(h_desc, nullptr, nullptr);
+}
+
+extern "C" int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words, uint32_t* d_out_dims,
+                               void* d_workspace, size_t workspace_bytes, uint32_t* d_status,
+                               void* hip_stream) {
+  if (!desc_ok(h_desc)) return FDY_ERR_INVALID_ARG;
+  const fdy_mat_desc& d = *h_desc;
+  if (d.n_graphs == 0 || d.n_maps == 0) return FDY_OK;
+  if (!d.src_word_off || !d.src_reloc_off || !d.tmpl_graph || !d.graph_tmpl || !d.ovr_off ||
+      !d.new_base)
+    return FDY_ERR_INVALID_ARG;
+  if (d.out_words_per_map && (!d_out_words || ((uintptr_t)d_out_words & 15) || !d.src_words ||
+                              ((uintptr_t)d.src_words & 15)))
+    return FDY_ERR_INVALID_ARG;
+  if ((uintptr_t)d.relocs & 15 || (uintptr_t)d.patch & 15) return FDY_ERR_INVALID_ARG;
+  if (d.map_rank && (d.n_ranks == 0 || !d.patch_off)) return FDY_ERR_INVALID_ARG;
+  if (d_out_dims && (((uintptr_t)d_out_dims & 7) || !d.src_node_off || !d.govr_off ||
+                     (d.out_nodes_total && !d.src_nodes)))
+    return FDY_ERR_INVALID_ARG;
+  MatParams p;
+  p.d = d;
+  if (!d.map_rank) p.d.n_ranks = 0;
+  if (!d_out_dims) p.d.out_nodes_total = 0;
+  const size_t need = layout(&d, nullptr, nullptr);
+  if (!d_workspace || ((uintptr_t)d_workspace & 255) || workspace_bytes < need) return FDY_ERR_WORKSPACE;
+  layout(&d, (unsigned char*)d_workspace, &p.ws);
+  p.out_words = (u64*)d_out_words;
+  p.out_dims = d_out_dims;
+  p.d_status = d_status;
+  hipStream_t stream = (hipStream_t)hip_stream;
+
+  hipLaunchKernelGGL(mat_prep_graphs_kernel, dim3(1), dim3(1024), 0, stream, p);
+  FDY_HIP_TRY(hipGetLastError());
+  if (p.ws.max_tiles) {
+    hipLaunchKernelGGL(mat_prep_tiles_kernel, dim3((p.ws.max_tiles + 3) / 4), dim3(256), 0, stream, p);
+    FDY_HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(mat_main_kernel, dim3(p.ws.max_tiles, d.n_maps), dim3(kMatBlock), 0, stream, p);
+    FDY_HIP_TRY(hipGetLastError());
+  }
+  if (d_out_dims && d.out_nodes_total) {
+    hipLaunchKernelGGL(mat_dims_kernel, dim3((u32)((d.out_nodes_total + 255) / 256)), dim3(256), 0,
+                       stream, p);
+    FDY_HIP_TRY(hipGetLastError());
+  }
+  return FDY_OK;
+}

@@ -1,0 +1,119 @@
+"""Convenience layer over the binding for tests, the smoke check and the bench: uploads host
+arrays, allocates outputs / workspaces with torch, calls the C-ABI entry points and brings
+results back.  Marshalling only - no step of the method is computed here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2604_06664_amd as fdy
+
+RELOC = np.dtype([("word", "<u4"), ("region", "<u4"), ("offset", "<u8")])
+DEV = "cuda:0"
+
+
+def _status_tensor():
+    return torch.zeros(1, dtype=torch.int32, device=DEV)
+
+
+class ScanRun:
+    """Device-resident inputs, outputs and workspace of one fdy_scan_pointers problem."""
+
+    def __init__(self, words, table, capacity=None):
+        self.n_words = int(len(words))
+        self.n_alloc = int(len(table))
+        self.capacity = self.n_words if capacity is None else int(capacity)
+        self.d_words = words if torch.is_tensor(words) else fdy.to_device(words)
+        self.d_table = table if torch.is_tensor(table) else fdy.to_device(table)
+        self.d_relocs = fdy.device_bytes(self.capacity * 16)
+        self.d_count = torch.zeros(1, dtype=torch.int64, device=DEV)
+        self.ws_bytes = fdy.fdy_scan_workspace_bytes(self.n_words, self.n_alloc)
+        self.d_ws = fdy.device_bytes(self.ws_bytes)
+        self.d_status = _status_tensor()
+
+    def launch(self, stream=None):
+        return fdy.fdy_scan_pointers(self.d_words, self.n_words, self.d_table, self.n_alloc,
+                                     self.d_relocs, self.capacity, self.d_count, self.d_ws,
+                                     self.ws_bytes, self.d_status, stream)
+
+    def result(self):
+        torch.cuda.synchronize()
+        count = int(self.d_count.item())
+        status = int(self.d_status.item())
+        relocs = fdy.to_host(self.d_relocs, RELOC, min(count, self.capacity))
+        return relocs, count, status
+
+
+def scan(words, table, capacity=None):
+    run = ScanRun(words, table, capacity)
+    run.launch()
+    return run.result()
+
+
+def reloc_segment(d_relocs, d_count, capacity, word_off):
+    d_off = fdy.to_device(np.ascontiguousarray(word_off, np.uint64))
+    d_out = fdy.device_bytes(len(word_off) * 8, fill=0xEE)
+    fdy.fdy_reloc_segment(d_relocs, d_count, capacity, d_off, len(word_off), d_out)
+    torch.cuda.synchronize()
+    return fdy.to_host(d_out, np.uint64, len(word_off)), d_out
+
+
+def fingerprint(nodes, node_off, mask, want_tmpl_graph=True):
+    G = len(node_off) - 1
+    d_nodes = fdy.to_device(nodes)
+    d_off = fdy.to_device(np.ascontiguousarray(node_off, np.uint64))
+    d_keys = fdy.device_bytes(G * 8, fill=0xEE)
+    d_tid = fdy.device_bytes(G * 4, fill=0xEE)
+    d_tg = fdy.device_bytes(G * 4, fill=0xEE) if want_tmpl_graph else None
+    d_nt = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    fdy.fdy_fingerprint(d_nodes, d_off, G, mask, d_keys, d_tid, d_tg, d_nt)
+    torch.cuda.synchronize()
+    nt = int(d_nt.item())
+    keys = fdy.to_host(d_keys, np.uint64, G)
+    tid = fdy.to_host(d_tid, np.uint32, G)
+    tg = fdy.to_host(d_tg, np.uint32, nt) if want_tmpl_graph else None
+    return keys, tid, tg, dict(d_keys=d_keys, d_tid=d_tid, d_tg=d_tg, d_nt=d_nt)
+
+
+class MatRun:
+    """Device-resident inputs, outputs and workspace of one fdy_materialize problem.
+    `mp` is a synth.MatProblem (host arrays); `device_overrides` may replace uploaded arrays
+    by tensors that are already on the device (e.g. relocs straight from a scan)."""
+
+    def __init__(self, mp, want_dims=True, device_overrides=None, poison=True):
+        self.mp = mp
+        dev = {}
+        for name in mp.ARRAYS:
+            v = getattr(mp, name)
+            dev[name] = None if v is None else fdy.to_device(v)
+        if device_overrides:
+            dev.update(device_overrides)
+        self.dev = dev
+        self.wpm = mp.out_words_per_map()
+        self.nodes_total = mp.out_nodes_total() if want_dims else 0
+        self.desc = fdy.make_mat_desc(
+            dev, n_src_graphs=mp.S, n_templates=mp.T, n_graphs=mp.G, n_maps=mp.M, n_alloc=mp.A,
+            n_ranks=mp.n_ranks, out_words_per_map=self.wpm, out_nodes_total=self.nodes_total)
+        self.d_out = fdy.device_bytes(mp.M * self.wpm * 8, fill=0xCD if poison else None)
+        self.d_dims = (fdy.device_bytes(self.nodes_total * 24, fill=0xCD if poison else None)
+                       if want_dims else None)
+        self.ws_bytes = fdy.fdy_materialize_workspace_bytes(self.desc)
+        self.d_ws = fdy.device_bytes(self.ws_bytes)
+        self.d_status = _status_tensor()
+
+    def launch(self, stream=None, check=True):
+        return fdy.fdy_materialize(self.desc, self.d_out, self.d_dims, self.d_ws, self.ws_bytes,
+                                   self.d_status, stream, check=check)
+
+    def result(self):
+        torch.cuda.synchronize()
+        out = fdy.to_host(self.d_out, np.uint64, self.mp.M * self.wpm).reshape(self.mp.M, self.wpm)
+        dims = (fdy.to_host(self.d_dims, np.uint32, self.nodes_total * 6).reshape(-1, 6)
+                if self.d_dims is not None else None)
+        return out, dims, int(self.d_status.item())
+
+
+def materialize(mp, want_dims=True):
+    run = MatRun(mp, want_dims)
+    run.launch()
+    return run.result()

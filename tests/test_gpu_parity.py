@@ -1,0 +1,359 @@
+"""Parity of the HIP path (through the C-ABI) against the CPU oracle: bit-exact, element by
+element.  Everything here needs a real MI355X (`-m gpu`)."""
+import numpy as np
+import pytest
+
+from synth import MatProblem, make_config
+from synth import layout as L
+from tests.cases import small
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hip():
+    import torch
+
+    assert torch.cuda.is_available(), "gpu tests need a GPU"
+    import paper_2604_06664_amd as fdy
+    from paper_2604_06664_amd import session
+
+    fdy.lib()
+    return session
+
+
+def mk_table(pairs):
+    t = np.zeros(len(pairs), L.ALLOC)
+    for i, (b, s) in enumerate(pairs):
+        t[i] = (b, s)
+    return t
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------------------------ scan
+def check_scan(hip, oracle, words, table, capacity=None, tag=""):
+    say(f"[scan] {tag} W={len(words)} A={len(table)} cap={capacity}")
+    ref, rcnt = oracle.scan(words, table, capacity)
+    got, cnt, status = hip.scan(words, table, capacity)
+    assert cnt == rcnt
+    assert np.array_equal(got, ref)
+    cap = len(words) if capacity is None else capacity
+    assert status == (L.ST_CAPACITY if rcnt > cap else 0)
+    return got
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_scan_small_configs(hip, oracle, idx):
+    ar = small(idx)
+    got = check_scan(hip, oracle, ar.words, ar.table, tag=ar.name)
+    assert np.array_equal(got["word"].astype(np.int64), ar.ptr_word)  # generator ground truth
+
+
+def test_scan_edge_cases(hip, oracle):
+    ar = small(1)
+    one = mk_table([(500, 8)])
+    check_scan(hip, oracle, np.zeros(0, np.uint64), ar.table, tag="no words")
+    check_scan(hip, oracle, ar.words[:100], mk_table([]), tag="no allocations")
+    check_scan(hip, oracle, np.array([499, 500, 507, 508], np.uint64), one, tag="one allocation")
+    check_scan(hip, oracle, ar.words[:1], ar.table, tag="one word")
+    for n in (2047, 2048, 2049, 4095, 4097, 6001):  # around tile boundaries, odd tails
+        check_scan(hip, oracle, ar.words[:n], ar.table, tag="ragged")
+    # every word a hit (queue and output completely full), touching intervals, extremes
+    dense = mk_table([(0x1000 + 64 * i, 64) for i in range(300)] + [(2**64 - 0x100, 0xFF)])
+    rng = np.random.default_rng(3)
+    w = (0x1000 + rng.integers(0, 64 * 300, 5000)).astype(np.uint64)
+    w[::97] = np.uint64(2**64 - 1)
+    w[1::97] = np.uint64(2**64 - 2)
+    w[2::97] = np.uint64(0xFFF)
+    check_scan(hip, oracle, w, dense, tag="all hits")
+    # capacity smaller than the number of hits: count is the need, prefix is written
+    check_scan(hip, oracle, w, dense, capacity=1234, tag="overflow")
+    check_scan(hip, oracle, w, dense, capacity=0, tag="zero capacity")
+
+
+def test_scan_hierarchical_levels(hip, oracle):
+    """Force the sampled LDS level + in-table refinement on small tables by shrinking the
+    LDS budget, so every depth of the hierarchy is exercised at sizes the oracle likes."""
+    import paper_2604_06664_amd as fdy
+
+    ar = small(4)  # 65,536 allocations
+    old = fdy.tune_get(fdy.TUNE_SCAN_TOP_LOG2)
+    try:
+        for top_log2 in (1, 3, 8, 12, 13):
+            assert fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, top_log2) >= 0
+            check_scan(hip, oracle, ar.words[:300000], ar.table, tag=f"top_log2={top_log2}")
+            check_scan(hip, oracle, ar.words[:5000], ar.table[:1000], tag=f"A=1000 top_log2={top_log2}")
+            check_scan(hip, oracle, ar.words[:5000], ar.table[:1025], tag=f"A=1025 top_log2={top_log2}")
+    finally:
+        fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, old)
+
+
+def test_scan_bounded_wait_is_reported_not_hung(hip):
+    """Host-forced error path: with a spin limit of 0 a workgroup that finds its predecessor
+    unfinished gives up at once, raises FDY_ST_SPIN and still terminates."""
+    import paper_2604_06664_amd as fdy
+
+    ar = small(4)
+    old = fdy.tune_set(fdy.TUNE_SCAN_SPIN_LIMIT, 0)
+    try:
+        _, _, status = hip.scan(ar.words, ar.table)
+        assert status & ~(L.ST_SPIN | L.ST_CAPACITY) == 0  # terminated; only these bits possible
+    finally:
+        fdy.tune_set(fdy.TUNE_SCAN_SPIN_LIMIT, old)
+    got, cnt, status = hip.scan(ar.words, ar.table)
+    assert status == 0 and cnt == len(ar.ptr_word)
+
+
+def test_scan_argument_errors(hip):
+    import paper_2604_06664_amd as fdy
+    import torch
+
+    ar = small(1)
+    run = hip.ScanRun(ar.words, ar.table)
+    bad = fdy.fdy_scan_pointers(run.d_words.data_ptr() + 8, run.n_words - 1, run.d_table, run.n_alloc,
+                                run.d_relocs, run.capacity, run.d_count, run.d_ws, run.ws_bytes,
+                                run.d_status, check=False)
+    assert bad == fdy.FDY_ERR_INVALID_ARG
+    assert fdy.fdy_scan_pointers(run.d_words, run.n_words, run.d_table, run.n_alloc, run.d_relocs,
+                                 run.capacity, run.d_count, run.d_ws, run.ws_bytes - 1, run.d_status,
+                                 check=False) == fdy.FDY_ERR_WORKSPACE
+    assert fdy.fdy_scan_pointers(run.d_words, 1 << 32, run.d_table, run.n_alloc, run.d_relocs,
+                                 run.capacity, run.d_count, run.d_ws, run.ws_bytes, run.d_status,
+                                 check=False) == fdy.FDY_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+
+
+def test_reloc_segment(hip, oracle):
+    ar = small(2)
+    run = hip.ScanRun(ar.words, ar.table)
+    run.launch()
+    relocs, cnt, _ = run.result()
+    for bounds in (ar.word_off, np.array([0], np.uint64), np.array([5, 5, 10**9], np.uint64)):
+        got, _ = hip.reloc_segment(run.d_relocs, run.d_count, run.capacity, bounds)
+        assert np.array_equal(got, oracle.reloc_segment(relocs, bounds))
+    # an empty relocation table
+    run0 = hip.ScanRun(ar.words[:50], mk_table([(1, 1)]))
+    run0.launch()
+    got, _ = hip.reloc_segment(run0.d_relocs, run0.d_count, run0.capacity, ar.word_off[:3])
+    assert got.tolist() == [0, 0, 0]
+
+
+# ----------------------------------------------------------------------------- fingerprint
+@pytest.mark.parametrize("idx", [1, 2, 3, 5])
+def test_fingerprint_small_configs(hip, oracle, idx):
+    ar = small(idx)
+    for mask in (ar.fp_mask, L.FP_ALL, L.FP_KERNEL_ID | L.FP_BLOB_LEN, L.FP_GRID_Y | L.FP_BLOCK, 0):
+        say(f"[fingerprint] {ar.name} mask={mask:#x}")
+        keys, tid, tg = oracle.fingerprint(ar.nodes, ar.node_off, mask)
+        gk, gt, gg, _ = hip.fingerprint(ar.nodes, ar.node_off, mask)
+        assert np.array_equal(gk, keys)
+        assert np.array_equal(gt, tid)
+        assert np.array_equal(gg, tg)
+
+
+def test_fingerprint_edge_cases(hip, oracle):
+    nodes = small(1).nodes
+    # empty graphs, one-node graphs, a graph longer than a workgroup, duplicates out of order
+    off = np.array([0, 0, 1, 3, 3, 4, 4 + 300, 4 + 300, 4 + 301], np.uint64)
+    nd = np.concatenate([nodes[:4], nodes[:300], nodes[:1]])
+    keys, tid, tg = oracle.fingerprint(nd, off, L.FP_ALL)
+    gk, gt, gg, _ = hip.fingerprint(nd, off, L.FP_ALL)
+    assert np.array_equal(gk, keys) and np.array_equal(gt, tid) and np.array_equal(gg, tg)
+    assert tid[0] == tid[3] == tid[6] and tid[1] == tid[7]
+    # no graphs at all
+    gk, gt, gg, _ = hip.fingerprint(nodes[:0], np.zeros(1, np.uint64), L.FP_ALL)
+    assert len(gk) == 0 and len(gg) == 0
+    # many graphs (several chunks of the grouping workgroup), few distinct keys
+    rng = np.random.default_rng(5)
+    pick = rng.integers(0, 7, 2500)
+    lens = np.array([3, 1, 4, 1, 5, 9, 2])
+    starts = np.concatenate([[0], np.cumsum(lens)])
+    nd = np.concatenate([nodes[starts[p]:starts[p] + lens[p]] for p in pick])
+    off = np.concatenate([[0], np.cumsum(lens[pick])]).astype(np.uint64)
+    keys, tid, tg = oracle.fingerprint(nd, off, L.FP_ALL)
+    gk, gt, gg, _ = hip.fingerprint(nd, off, L.FP_ALL, want_tmpl_graph=False)
+    assert np.array_equal(gk, keys) and np.array_equal(gt, tid) and gg is None
+    _, _, gg, _ = hip.fingerprint(nd, off, L.FP_ALL)
+    assert np.array_equal(gg, tg)
+
+
+# ----------------------------------------------------------------------------- materialize
+def problem(oracle, ar, **kw):
+    relocs, _ = oracle.scan(ar.words, ar.table)
+    return MatProblem.from_archive(ar, relocs, oracle.reloc_segment(relocs, ar.word_off), **kw)
+
+
+def check_mat(hip, oracle, mp, tag="", want_dims=True):
+    say(f"[materialize] {tag} G={mp.G} M={mp.M} T={mp.T} words/map={mp.out_words_per_map()}")
+    ref, rdims = oracle.materialize(mp, want_dims)
+    out, dims, status = hip.materialize(mp, want_dims)
+    assert status == 0
+    assert np.array_equal(out, ref)
+    if want_dims:
+        assert np.array_equal(dims, rdims)
+    return out
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_materialize_small_configs(hip, oracle, idx):
+    ar = small(idx)
+    mp = problem(oracle, ar)
+    check_mat(hip, oracle, mp, tag=ar.name)
+    check_mat(hip, oracle, mp, tag=ar.name + " no dims", want_dims=False)
+
+
+def test_materialize_identity_on_gpu(hip, oracle):
+    ar = small(2)
+    mp = problem(oracle, ar)
+    kw = {n: getattr(mp, n) for n in MatProblem.ARRAYS}
+    kw["new_base"] = ar.table["base"][None, :].copy()
+    out, dims, status = hip.materialize(MatProblem(n_ranks=0, **kw))
+    assert status == 0 and np.array_equal(out[0], ar.words)
+    assert np.array_equal(dims[:, :3], ar.nodes["grid"])
+
+
+def test_materialize_stage_precedence_and_wrap(hip, oracle):
+    words = np.array([11, 0x1000 + 5, 0x1000 + 9, 44], np.uint64)
+    table = mk_table([(0x1000, 0x100)])
+    relocs, _ = oracle.scan(words, table)
+    ovr = np.zeros(3, L.OVR32)
+    ovr[0], ovr[1], ovr[2] = (8, 0xAAAA), (20, 0xBBBB), (28, 0xCCCC)
+    patch = np.zeros(1, L.PATCH)
+    patch[0] = (2, 0, 0xDEADBEEF00000001)
+    mp = MatProblem(
+        src_words=words, src_word_off=[0, 4], src_nodes=np.zeros(0, L.NODE), src_node_off=[0, 0],
+        relocs=relocs, src_reloc_off=[0, 2], tmpl_graph=[0], graph_tmpl=[0, 0], ovr=ovr,
+        ovr_off=[0, 0, 3], govr=np.zeros(0, L.GRID_OVR), govr_off=[0, 0, 0],
+        new_base=np.array([[0x500000], [2**64 - 3]], np.uint64), map_rank=[1, 0], n_ranks=2,
+        patch=patch, patch_off=[0, 0, 1])
+    out = check_mat(hip, oracle, mp, tag="precedence", want_dims=False)
+    assert out[0, 6] == 0xDEADBEEF00000001 and out[1, 1] == 2  # (2^64-3)+5 wraps to 2
+
+
+def test_materialize_tile_boundaries_and_empty_graphs(hip, oracle):
+    """Templates of 0, 1, 2047, 2048, 2049 and 5000 words; overrides and patches placed on
+    the first / last word of tiles; outputs referencing templates in scrambled order."""
+    rng = np.random.default_rng(11)
+    table = small(1).table
+    lens = [0, 1, 2047, 2048, 2049, 5000]
+    from synth.archive import fill_words
+
+    words, *_ = fill_words(rng, sum(lens), table, 0.3, 0.05, "mix")
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint64)
+    relocs, _ = oracle.scan(words, table)
+    roff = oracle.reloc_segment(relocs, off)
+    graph_tmpl = np.array([5, 0, 3, 3, 1, 4, 2, 0, 5], np.uint32)
+    ovr_l, ovr_off, patch_l, patch_off = [], [0], [], [0]
+    for g, t in enumerate(graph_tmpl):
+        n = lens[t]
+        spots = sorted({b for b in (0, 4, 8 * 2047, 8 * 2047 + 4, 8 * 2048, 8 * 2048 + 4, 8 * n - 4) if 0 <= b < 8 * n})
+        o = np.zeros(len(spots), L.OVR32)
+        o["byte_off"], o["value"] = spots, rng.integers(0, 2**32, len(spots))
+        ovr_l.append(o)
+        ovr_off.append(ovr_off[-1] + len(o))
+    R = 3
+    for t in range(len(lens)):
+        for r in range(R):
+            n = lens[t]
+            spots = sorted({k for k in (0, 2047, 2048, 4095, 4096, n - 1) if 0 <= k < n}) if r != 1 else []
+            q = np.zeros(len(spots), L.PATCH)
+            q["word"], q["value"] = spots, rng.integers(0, 2**63, len(spots))
+            patch_l.append(q)
+            patch_off.append(patch_off[-1] + len(q))
+    G = len(graph_tmpl)
+    mp = MatProblem(
+        src_words=words, src_word_off=off, src_nodes=np.zeros(0, L.NODE), src_node_off=np.zeros(len(lens) + 1),
+        relocs=relocs, src_reloc_off=roff, tmpl_graph=np.arange(len(lens)), graph_tmpl=graph_tmpl,
+        ovr=np.concatenate(ovr_l), ovr_off=ovr_off, govr=np.zeros(0, L.GRID_OVR), govr_off=np.zeros(G + 1),
+        new_base=small(1).new_base.repeat(4, axis=0) + np.arange(4, dtype=np.uint64)[:, None] * np.uint64(1 << 30),
+        map_rank=[2, 0, 1, 2], n_ranks=R, patch=np.concatenate(patch_l), patch_off=patch_off)
+    check_mat(hip, oracle, mp, tag="tile boundaries", want_dims=False)
+
+
+def test_materialize_bad_inputs_are_flagged_not_faulting(hip, oracle):
+    import paper_2604_06664_amd as fdy
+
+    ar = small(1)
+    mp = problem(oracle, ar)
+    # region out of range in one reloc: entry skipped, status bit raised, rest as the oracle
+    bad = mp.relocs.copy()
+    bad["region"][7] = ar.n_alloc + 5
+    kw = {n: getattr(mp, n) for n in MatProblem.ARRAYS}
+    kw["relocs"] = bad
+    out, _, status = hip.materialize(MatProblem(n_ranks=0, **kw), want_dims=False)
+    assert status == L.ST_BAD_INDEX
+    ref, _ = oracle.materialize(mp, want_dims=False)
+    k = int(bad["word"][7])
+    assert out[0, k] == ar.words[k]  # the skipped entry leaves the template word
+    ref[0, k] = ar.words[k]
+    assert np.array_equal(out, ref)
+    # wrong total from the caller: nothing is written
+    run = hip.MatRun(mp, want_dims=False)
+    run.desc.out_words_per_map = run.wpm - 1
+    run.launch()
+    out, _, status = run.result()
+    assert status & L.ST_BAD_SIZE and np.all(out.view(np.uint8) == 0xCD)
+    # template index out of range
+    kw["relocs"] = mp.relocs
+    run = hip.MatRun(mp, want_dims=False)
+    run.dev["graph_tmpl"] = fdy.to_device(np.array([9], np.uint32))
+    run.desc = fdy.make_mat_desc(run.dev, n_src_graphs=mp.S, n_templates=mp.T, n_graphs=mp.G, n_maps=mp.M,
+                                 n_alloc=mp.A, n_ranks=0, out_words_per_map=run.wpm, out_nodes_total=0)
+    run.launch()
+    out, _, status = run.result()
+    assert status & L.ST_BAD_INDEX and np.all(out.view(np.uint8) == 0xCD)
+    # host-visible errors
+    run = hip.MatRun(mp, want_dims=False)
+    assert fdy.fdy_materialize(run.desc, run.d_out, None, run.d_ws, run.ws_bytes - 1, run.d_status,
+                               check=False) == fdy.FDY_ERR_WORKSPACE
+    assert fdy.fdy_materialize(run.desc, run.d_out.data_ptr() + 8, None, run.d_ws, run.ws_bytes,
+                               run.d_status, check=False) == fdy.FDY_ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------- whole path, full sizes
+@pytest.mark.parametrize("idx", [1, 2, 3, 5, 4])
+def test_full_config_whole_path(hip, oracle, idx):
+    """scan -> segment -> fingerprint -> materialize chained on the device (no host round
+    trip between the calls), at the full size of each configuration, every output compared
+    with the oracle element by element."""
+    import paper_2604_06664_amd as fdy
+    import torch
+
+    say(f"[full] config {idx}: generating")
+    ar = make_config(idx)
+    say(f"[full] config {idx}: oracle")
+    relocs, cnt = oracle.scan(ar.words, ar.table)
+    roff = oracle.reloc_segment(relocs, ar.word_off)
+    keys, tid, tg = oracle.fingerprint(ar.nodes, ar.node_off, ar.fp_mask)
+    assert np.array_equal(tid, ar.graph_tmpl) and np.array_equal(tg, ar.tmpl_graph)
+    mp = MatProblem.from_archive(ar, relocs, roff, graph_tmpl=tid, tmpl_graph=tg)
+    say(f"[full] config {idx}: gpu W={len(ar.words)} A={ar.n_alloc} G={ar.n_graphs} M={ar.n_maps}")
+    srun = hip.ScanRun(ar.words, ar.table, capacity=cnt + 16)
+    srun.launch()
+    G = ar.n_graphs
+    d_word_off = fdy.to_device(ar.word_off)
+    d_roff = fdy.device_bytes((G + 1) * 8, fill=0xEE)
+    fdy.fdy_reloc_segment(srun.d_relocs, srun.d_count, srun.capacity, d_word_off, G + 1, d_roff)
+    gk, gt, gg, fp = hip.fingerprint(ar.nodes, ar.node_off, ar.fp_mask)
+    mrun = hip.MatRun(mp, want_dims=len(ar.nodes) > 0, device_overrides=dict(
+        src_words=srun.d_words, relocs=srun.d_relocs, src_reloc_off=d_roff,
+        graph_tmpl=fp["d_tid"], tmpl_graph=fp["d_tg"]))
+    mrun.launch()
+    got_relocs, got_cnt, st = srun.result()
+    say(f"[full] config {idx}: comparing")
+    assert st == 0 and got_cnt == cnt == len(ar.ptr_word)
+    assert np.array_equal(got_relocs, relocs)
+    assert np.array_equal(fdy.to_host(d_roff, np.uint64, G + 1), roff)
+    assert np.array_equal(gk, keys) and np.array_equal(gt, tid) and np.array_equal(gg, tg)
+    del got_relocs
+    ref, rdims = oracle.materialize(mp, want_dims=len(ar.nodes) > 0)
+    out, dims, st = mrun.result()
+    assert st == 0
+    assert np.array_equal(out, ref)
+    if rdims is not None:
+        assert np.array_equal(dims, rdims)
+    del mrun, srun
+    torch.cuda.empty_cache()
