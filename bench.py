@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""bench.py - one-GPU throughput of the whole hot path (scan -> reloc segmentation ->
+fingerprint -> materialize) on the synthetic capture archives, with the roofline fraction of
+the dominant kernel and the CPU oracle timed beside it.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 4] [--no-others]
+
+Prints ONE JSON line.  `value` is param-blob GB/s for scan+materialize on the main workload
+(config 4, the largest single-GPU configuration): (input blob bytes + output blob bytes) per
+step time, inputs resident in HBM.  A step is one pass of the whole path over the archive.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(ar, n_relocs_total, n_relocs_tmpl):
+    """Compulsory HBM bytes per launch of the two streaming kernels: every distinct input
+    byte once plus every output byte once (re-reads of templates per map are not counted)."""
+    W, A, M = len(ar.words), ar.n_alloc, ar.n_maps
+    import numpy as np
+
+    nw = np.diff(ar.word_off.astype(np.int64))
+    tmpl_words = int(nw[ar.tmpl_graph].sum())
+    out_words = int(nw[ar.tmpl_graph[ar.graph_tmpl]].sum()) * M
+    scan = W * 8 + n_relocs_total * 16 + A * 16
+    mat = (tmpl_words * 8 + n_relocs_tmpl * 16 + M * A * 8 + ar.ovr.nbytes + ar.patch.nbytes
+           + out_words * 8)
+    return dict(scan=scan, mat=mat, in_blob=W * 8, out_blob=out_words * 8, out_words=out_words)
+
+
+def run_workload(idx, steps, warmup, prof=True, cpu_sample_words=0):
+    import numpy as np
+    import torch
+
+    import paper_2604_06664_amd as fdy
+    from paper_2604_06664_amd import session
+    from synth import CONFIG_NAMES, make_config
+
+    t0 = time.time()
+    ar = make_config(idx)
+    log(f"config {idx} ({CONFIG_NAMES[idx]}): generated in {time.time() - t0:.1f}s "
+        f"W={len(ar.words)} A={ar.n_alloc} G={ar.n_graphs} M={ar.n_maps}")
+    n_ptr = len(ar.ptr_word)
+    run = session.PathRun(ar, reloc_capacity=n_ptr + 1024)
+    stream = torch.cuda.current_stream()
+    for _ in range(max(warmup, 1)):
+        run.step(stream)
+    st = run.status()
+    cnt = int(run.scan.d_count.item())
+    assert st == 0 and cnt == n_ptr, f"status={st} count={cnt} planted={n_ptr}"
+    if prof:
+        fdy.prof_enable(steps)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(steps):
+        run.step(stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    dev_ms = ev0.elapsed_time(ev1)
+    kernels = fdy.prof_read() if prof else {}
+    if prof:
+        fdy.prof_enable(0)
+    assert run.status() == 0
+    # relocs belonging to template graphs (what materialize reads)
+    roff = fdy.to_host(run.d_reloc_off, np.uint64, ar.n_graphs + 1).astype(np.int64)
+    n_rel_tmpl = int((roff[1:] - roff[:-1])[ar.tmpl_graph].sum())
+    ab = algorithmic_bytes(ar, cnt, n_rel_tmpl)
+    ms = wall_ms / steps
+    res = dict(
+        workload=f"config {idx}: {CONFIG_NAMES[idx]}", ms_per_step=ms, device_ms_per_step=dev_ms / steps,
+        blob_gbs=(ab["in_blob"] + ab["out_blob"]) / ms / 1e6,
+        graphs_per_s=ar.n_graphs * ar.n_maps / (ms / 1e3),
+        words=len(ar.words), allocations=ar.n_alloc, graphs=ar.n_graphs, maps=ar.n_maps,
+        templates=ar.n_templates, relocs=cnt, out_bytes=ab["out_blob"], kernels={})
+    for name, k in kernels.items():
+        e = dict(avg_ms=round(k["avg_ms"], 5), min_ms=round(k["min_ms"], 5), n=k["n"])
+        alg = ab["scan"] if name == "scan_kernel" else ab["mat"] if name == "mat_main_kernel" else None
+        if alg is not None:
+            e["algorithmic_bytes"] = alg
+            e["achieved_gbs"] = round(alg / k["avg_ms"] / 1e6, 1)
+            e["frac_hbm_peak"] = round(alg / k["avg_ms"] / 1e6 / HBM_PEAK_GBS, 4)
+        res["kernels"][name] = e
+    if res["kernels"].get("mat_main_kernel"):
+        res["materialize_graphs_per_s"] = ar.n_graphs * ar.n_maps / (
+            res["kernels"]["mat_main_kernel"]["avg_ms"] / 1e3)
+    cpu = None
+    if cpu_sample_words:
+        cpu = cpu_baseline(ar, run, min(cpu_sample_words, len(ar.words)))
+    del run
+    torch.cuda.empty_cache()
+    return res, cpu
+
+
+def cpu_baseline(ar, run, n):
+    """The oracle as it stands, single thread, on the first n words of the same workload:
+    scan + segmentation + materialize (one map).  Also checks the GPU relocation table of
+    that prefix against the oracle's."""
+    import numpy as np
+
+    import oracle
+    import paper_2604_06664_amd as fdy
+    from synth import MatProblem
+
+    oracle.build()
+    words = ar.words[:n]
+    t0 = time.perf_counter()
+    relocs, cnt = oracle.scan(words, ar.table)
+    t_scan = time.perf_counter() - t0
+    woff = np.array([0, n], np.uint64)
+    t0 = time.perf_counter()
+    roff = oracle.reloc_segment(relocs, woff)
+    mp = MatProblem(
+        src_words=words, src_word_off=woff, src_nodes=ar.nodes[:0], src_node_off=[0, 0], relocs=relocs,
+        src_reloc_off=roff, tmpl_graph=[0], graph_tmpl=[0], ovr=ar.ovr[:0], ovr_off=[0, 0],
+        govr=ar.govr[:0], govr_off=[0, 0], new_base=ar.new_base[:1], map_rank=None, n_ranks=0,
+        patch=ar.patch[:0], patch_off=[0])
+    out, _ = oracle.materialize(mp, want_dims=False)
+    t_mat = time.perf_counter() - t0
+    got = fdy.to_host(run.scan.d_relocs, session_reloc_dtype(), cnt)
+    parity = bool(np.array_equal(got, relocs))
+    got_out = fdy.to_host(run.mat.d_out, np.uint64, n)
+    parity = parity and bool(np.array_equal(got_out, out[0]))
+    secs = t_scan + t_mat
+    return dict(value=round(2 * n * 8 / secs / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
+                sample=f"first {n} words ({n * 8 / 2**20:.0f} MiB) of the workload against the full "
+                       f"allocation table: scan {t_scan:.2f}s + segment+materialize {t_mat:.2f}s, "
+                       f"single thread",
+                scan_gbs=round(n * 8 / t_scan / 1e9, 4), materialize_gbs=round(n * 8 / t_mat / 1e9, 4),
+                gpu_matches_oracle_on_sample=parity)
+
+
+def session_reloc_dtype():
+    from paper_2604_06664_amd import session
+
+    return session.RELOC
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--cpu-sample-words", type=int, default=1 << 26)
+    ap.add_argument("--no-others", action="store_true", help="skip the secondary configurations")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (the hot path shards without "
+              "communication; see DESIGN.md) - run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    import paper_2604_06664_amd as fdy
+
+    fdy.lib()
+    main_res, cpu = run_workload(args.workload, args.steps, args.warmup, prof=True,
+                                 cpu_sample_words=args.cpu_sample_words)
+    k = main_res["kernels"]
+    dom = max((n for n in k if "algorithmic_bytes" in k[n]), key=lambda n: k[n]["avg_ms"])
+    roofline = dict(bound="hbm", kernel=dom, achieved=k[dom]["achieved_gbs"], peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=k[dom]["frac_hbm_peak"], traffic=None,
+                    algorithmic_bytes_per_launch=k[dom]["algorithmic_bytes"],
+                    avg_launch_ms=k[dom]["avg_ms"])
+    others = {}
+    if not args.no_others:
+        for idx in (5, 3, 2, 1):
+            if idx == args.workload:
+                continue
+            r, _ = run_workload(idx, max(5, min(args.steps, 20)), 2, prof=True)
+            others[f"config{idx}"] = r
+    out = {
+        "metric": "param-blob GB/s (scan+materialize)",
+        "value": round(main_res["blob_gbs"], 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(main_res["ms_per_step"], 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u64",
+        "data": "synthetic",
+        "config": {"workload": main_res["workload"], "words": main_res["words"],
+                   "allocations": main_res["allocations"], "graphs": main_res["graphs"],
+                   "maps": main_res["maps"], "relocs": main_res["relocs"],
+                   "step": "fdy_scan_pointers + fdy_reloc_segment + fdy_fingerprint + fdy_materialize"},
+        "graphs_materialized_per_s": round(main_res["graphs_per_s"], 1),
+        "frac_hbm_peak_step": round(
+            (k["scan_kernel"]["algorithmic_bytes"] + k["mat_main_kernel"]["algorithmic_bytes"])
+            / main_res["ms_per_step"] / 1e6 / HBM_PEAK_GBS, 4),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": k,
+        "other_workloads": others,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -76,6 +76,12 @@ def lib():
         L.fdy__tune_get.argtypes = [C.c_int]
         L.fdy__tune_set.restype = C.c_int
         L.fdy__tune_set.argtypes = [C.c_int, C.c_int]
+        L.fdy__prof_enable.restype = C.c_int
+        L.fdy__prof_enable.argtypes = [C.c_int]
+        L.fdy__prof_read.restype = C.c_int
+        L.fdy__prof_read.argtypes = [C.c_int, C.POINTER(C.c_int)] + [C.POINTER(C.c_float)] * 3
+        L.fdy__prof_name.restype = C.c_char_p
+        L.fdy__prof_name.argtypes = [C.c_int]
         _lib = L
     return _lib
 
@@ -169,6 +175,29 @@ def tune_get(knob):
 
 def tune_set(knob, value):
     return lib().fdy__tune_set(knob, value)
+
+
+PROF_SLOTS = 9
+
+
+def prof_enable(n_records):
+    """Bracket each kernel launch of the library with HIP events on the caller's stream
+    (bench support; 0 switches it off)."""
+    return lib().fdy__prof_enable(int(n_records))
+
+
+def prof_read():
+    """-> {kernel name: dict(n, total_ms, avg_ms, min_ms, max_ms)} and resets the records."""
+    out = {}
+    for slot in range(PROF_SLOTS):
+        n, tot, mn, mx = C.c_int(0), C.c_float(0), C.c_float(0), C.c_float(0)
+        if lib().fdy__prof_read(slot, C.byref(n), C.byref(tot), C.byref(mn), C.byref(mx)) != 0:
+            raise FdyError(FDY_ERR_HIP, "fdy__prof_read")
+        if n.value:
+            out[lib().fdy__prof_name(slot).decode()] = dict(
+                n=n.value, total_ms=tot.value, avg_ms=tot.value / n.value, min_ms=mn.value,
+                max_ms=mx.value)
+    return out
 
 
 # ---- marshalling helpers -------------------------------------------------------------------

@@ -57,3 +57,78 @@ extern "C" int fdy_table_validate(const fdy_alloc* h_table, uint32_t n_alloc, ui
   }
   return FDY_OK;
 }
+
+// ---- per-kernel event timing (bench support) -------------------------------------------
+#include <vector>
+namespace {
+struct ProfSlot {
+  std::vector<hipEvent_t> a, b;
+  int used = 0;
+};
+ProfSlot g_prof[FDY_PROF_SLOTS];
+int g_prof_n = 0;
+}  // namespace
+
+void fdy::prof_begin(int slot, void* stream) {
+  if (!g_prof_n) return;
+  ProfSlot& s = g_prof[slot];
+  if (s.used >= g_prof_n) return;
+  (void)hipEventRecord(s.a[s.used], (hipStream_t)stream);
+}
+
+void fdy::prof_end(int slot, void* stream) {
+  if (!g_prof_n) return;
+  ProfSlot& s = g_prof[slot];
+  if (s.used >= g_prof_n) return;
+  (void)hipEventRecord(s.b[s.used], (hipStream_t)stream);
+  ++s.used;
+}
+
+extern "C" int fdy__prof_enable(int n_records) {
+  for (auto& s : g_prof) {
+    for (auto e : s.a) (void)hipEventDestroy(e);
+    for (auto e : s.b) (void)hipEventDestroy(e);
+    s.a.clear();
+    s.b.clear();
+    s.used = 0;
+  }
+  g_prof_n = 0;
+  if (n_records <= 0) return 0;
+  if (n_records > 4096) n_records = 4096;
+  for (auto& s : g_prof) {
+    s.a.resize(n_records);
+    s.b.resize(n_records);
+    for (int i = 0; i < n_records; ++i) {
+      if (hipEventCreate(&s.a[i]) != hipSuccess || hipEventCreate(&s.b[i]) != hipSuccess) return -1;
+    }
+  }
+  g_prof_n = n_records;
+  return n_records;
+}
+
+extern "C" int fdy__prof_read(int slot, int* n_records, float* total_ms, float* min_ms, float* max_ms) {
+  if (slot < 0 || slot >= FDY_PROF_SLOTS) return -1;
+  ProfSlot& s = g_prof[slot];
+  float tot = 0.f, mn = 1e30f, mx = 0.f;
+  for (int i = 0; i < s.used; ++i) {
+    if (hipEventSynchronize(s.b[i]) != hipSuccess) return -1;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, s.a[i], s.b[i]) != hipSuccess) return -1;
+    tot += ms;
+    mn = ms < mn ? ms : mn;
+    mx = ms > mx ? ms : mx;
+  }
+  if (n_records) *n_records = s.used;
+  if (total_ms) *total_ms = tot;
+  if (min_ms) *min_ms = s.used ? mn : 0.f;
+  if (max_ms) *max_ms = mx;
+  s.used = 0;
+  return 0;
+}
+
+extern "C" const char* fdy__prof_name(int slot) {
+  static const char* names[FDY_PROF_SLOTS] = {
+      "scan_kernel", "scan_init_kernel", "reloc_segment_kernel", "fp_key_kernel", "fp_group_kernel",
+      "mat_prep_graphs_kernel", "mat_prep_tiles_kernel", "mat_main_kernel", "mat_dims_kernel"};
+  return slot >= 0 && slot < FDY_PROF_SLOTS ? names[slot] : "?";
+}

@@ -10,6 +10,7 @@
 // the sequential 64-bit result.  A second, single-workgroup kernel turns keys into dense
 // template ids in order of first appearance.
 #include "fdy_device.hpp"
+#include "fdy_tune.h"
 
 namespace fdy {
 namespace {
@@ -159,13 +160,18 @@ extern "C" int fdy_fingerprint(const fdy_node* d_nodes, const uint64_t* d_node_o
   if (n_graphs && (!d_node_off || !d_keys || !d_template_id)) return FDY_ERR_INVALID_ARG;
   if ((uintptr_t)d_nodes & 7) return FDY_ERR_INVALID_ARG;
   hipStream_t stream = (hipStream_t)hip_stream;
+  (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
   if (n_graphs) {
+    prof_begin(FDY_PROF_FP_KEYS, stream);
     hipLaunchKernelGGL(fp_key_kernel, dim3(n_graphs), dim3(kFpBlock), 0, stream, d_nodes,
                        (const u64*)d_node_off, field_mask, (u64*)d_keys);
+    prof_end(FDY_PROF_FP_KEYS, stream);
     FDY_HIP_TRY(hipGetLastError());
   }
+  prof_begin(FDY_PROF_FP_GROUP, stream);
   hipLaunchKernelGGL(fp_group_kernel, dim3(1), dim3(1024), 0, stream, (const u64*)d_keys, n_graphs,
                      d_template_id, d_tmpl_graph, d_n_templates);
+  prof_end(FDY_PROF_FP_GROUP, stream);
   FDY_HIP_TRY(hipGetLastError());
   return FDY_OK;
 }

@@ -357,18 +357,27 @@ extern "C" int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words
   p.out_dims = d_out_dims;
   p.d_status = d_status;
   hipStream_t stream = (hipStream_t)hip_stream;
+  (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
 
+  prof_begin(FDY_PROF_MAT_PREP_GRAPHS, stream);
   hipLaunchKernelGGL(mat_prep_graphs_kernel, dim3(1), dim3(1024), 0, stream, p);
+  prof_end(FDY_PROF_MAT_PREP_GRAPHS, stream);
   FDY_HIP_TRY(hipGetLastError());
   if (p.ws.max_tiles) {
+    prof_begin(FDY_PROF_MAT_PREP_TILES, stream);
     hipLaunchKernelGGL(mat_prep_tiles_kernel, dim3((p.ws.max_tiles + 3) / 4), dim3(256), 0, stream, p);
+    prof_end(FDY_PROF_MAT_PREP_TILES, stream);
     FDY_HIP_TRY(hipGetLastError());
+    prof_begin(FDY_PROF_MAT_MAIN, stream);
     hipLaunchKernelGGL(mat_main_kernel, dim3(p.ws.max_tiles, d.n_maps), dim3(kMatBlock), 0, stream, p);
+    prof_end(FDY_PROF_MAT_MAIN, stream);
     FDY_HIP_TRY(hipGetLastError());
   }
   if (d_out_dims && d.out_nodes_total) {
+    prof_begin(FDY_PROF_MAT_DIMS, stream);
     hipLaunchKernelGGL(mat_dims_kernel, dim3((u32)((d.out_nodes_total + 255) / 256)), dim3(256), 0,
                        stream, p);
+    prof_end(FDY_PROF_MAT_DIMS, stream);
     FDY_HIP_TRY(hipGetLastError());
   }
   return FDY_OK;

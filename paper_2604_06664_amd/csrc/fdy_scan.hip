@@ -343,15 +343,18 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   if (!d_workspace || ((uintptr_t)d_workspace & 255) || workspace_bytes < pl.total)
     return FDY_ERR_WORKSPACE;
   hipStream_t stream = (hipStream_t)hip_stream;
+  (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
   unsigned char* ws = (unsigned char*)d_workspace;
   u32* ticket = (u32*)ws;
   u64* top = (u64*)(ws + pl.off_top);
   u64* state = (u64*)(ws + pl.off_state);
 
   const u32 n_init = pl.top_n > pl.n_tiles ? pl.top_n : pl.n_tiles;
+  prof_begin(FDY_PROF_SCAN_INIT, stream);
   hipLaunchKernelGGL(scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream,
                      d_table, n_alloc, top, pl.top_n, pl.seg_log2, state, pl.n_tiles, ticket,
                      (u64*)d_count);
+  prof_end(FDY_PROF_SCAN_INIT, stream);
   FDY_HIP_TRY(hipGetLastError());
   if (pl.n_tiles == 0 || n_alloc == 0) return FDY_OK;  // nothing can be a pointer
 
@@ -382,7 +385,9 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   const u32 per_cu = (u32)fdy__tune_get(FDY_TUNE_SCAN_WG_PER_CU);
   u32 grid = (u32)n_cu * per_cu;
   if (grid > pl.n_tiles) grid = pl.n_tiles;
+  prof_begin(FDY_PROF_SCAN_MAIN, stream);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), lds, stream, p);
+  prof_end(FDY_PROF_SCAN_MAIN, stream);
   FDY_HIP_TRY(hipGetLastError());
   return FDY_OK;
 }
@@ -393,9 +398,12 @@ extern "C" int fdy_reloc_segment(const fdy_reloc* d_relocs, const uint64_t* d_co
   if (n_off == 0) return FDY_OK;
   if (!d_count || !d_word_off || !d_reloc_off) return FDY_ERR_INVALID_ARG;
   if (reloc_capacity && !d_relocs) return FDY_ERR_INVALID_ARG;
+  (void)hipGetLastError();
+  prof_begin(FDY_PROF_SEGMENT, hip_stream);
   hipLaunchKernelGGL(reloc_segment_kernel, dim3((n_off + 3) / 4), dim3(256), 0,
                      (hipStream_t)hip_stream, d_relocs, (const u64*)d_count, reloc_capacity,
                      (const u64*)d_word_off, n_off, (u64*)d_reloc_off);
+  prof_end(FDY_PROF_SEGMENT, hip_stream);
   FDY_HIP_TRY(hipGetLastError());
   return FDY_OK;
 }

@@ -20,7 +20,34 @@ int fdy__tune_get(int knob);
 /* returns the previous value, or -1 for an unknown knob / value out of range */
 int fdy__tune_set(int knob, int value);
 
+/* Per-kernel timing for the bench: when enabled with a record count n > 0, each launch of
+ * an instrumented kernel is bracketed by a hipEvent pair on the caller's stream (at most n
+ * launches per slot are recorded, later ones are not).  fdy__prof_read synchronizes the
+ * recorded events and returns, per slot, the number of records and their total elapsed
+ * milliseconds; fdy__prof_enable(0) destroys the events.  Not thread-safe; off by default. */
+enum {
+  FDY_PROF_SCAN_MAIN = 0,
+  FDY_PROF_SCAN_INIT = 1,
+  FDY_PROF_SEGMENT = 2,
+  FDY_PROF_FP_KEYS = 3,
+  FDY_PROF_FP_GROUP = 4,
+  FDY_PROF_MAT_PREP_GRAPHS = 5,
+  FDY_PROF_MAT_PREP_TILES = 6,
+  FDY_PROF_MAT_MAIN = 7,
+  FDY_PROF_MAT_DIMS = 8,
+  FDY_PROF_SLOTS = 9
+};
+int fdy__prof_enable(int n_records);
+int fdy__prof_read(int slot, int* n_records, float* total_ms, float* min_ms, float* max_ms);
+const char* fdy__prof_name(int slot);
+
 #ifdef __cplusplus
 }
+
+namespace fdy {
+/* internal: bracket one launch; no-ops unless profiling is enabled */
+void prof_begin(int slot, void* stream);
+void prof_end(int slot, void* stream);
+}  // namespace fdy
 #endif
 #endif

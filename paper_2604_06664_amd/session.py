@@ -82,12 +82,11 @@ class MatRun:
 
     def __init__(self, mp, want_dims=True, device_overrides=None, poison=True):
         self.mp = mp
-        dev = {}
+        dev = dict(device_overrides or {})
         for name in mp.ARRAYS:
-            v = getattr(mp, name)
-            dev[name] = None if v is None else fdy.to_device(v)
-        if device_overrides:
-            dev.update(device_overrides)
+            if name not in dev:
+                v = getattr(mp, name)
+                dev[name] = None if v is None else fdy.to_device(v)
         self.dev = dev
         self.wpm = mp.out_words_per_map()
         self.nodes_total = mp.out_nodes_total() if want_dims else 0
@@ -117,3 +116,48 @@ def materialize(mp, want_dims=True):
     run = MatRun(mp, want_dims)
     run.launch()
     return run.result()
+
+
+class PathRun:
+    """The whole hot path for one capture archive, device-resident and chained on one stream
+    without host round trips: scan -> reloc segmentation -> fingerprint -> materialize.
+    `ar` is a synth.Archive; `reloc_capacity` bounds the relocation table (host knowledge:
+    at most one entry per word)."""
+
+    def __init__(self, ar, reloc_capacity=None, want_dims=True, maps=None):
+        from synth import MatProblem
+
+        self.ar = ar
+        G = ar.n_graphs
+        self.G = G
+        cap = len(ar.words) if reloc_capacity is None else int(reloc_capacity)
+        self.scan = ScanRun(ar.words, ar.table, cap)
+        self.d_word_off = fdy.to_device(ar.word_off)
+        self.d_reloc_off = fdy.device_bytes((G + 1) * 8, fill=0xEE)
+        self.d_nodes = fdy.to_device(ar.nodes)
+        self.d_node_off = fdy.to_device(ar.node_off)
+        self.d_keys = fdy.device_bytes(G * 8, fill=0xEE)
+        self.d_tid = fdy.device_bytes(G * 4, fill=0xEE)
+        self.d_tg = fdy.device_bytes(G * 4, fill=0xEE)
+        self.d_nt = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+        # host-side manifest knowledge (template of each graph) sizes the output; the device
+        # arrays the kernels consume are the ones fdy_fingerprint writes
+        empty_rel = np.zeros(0, RELOC)
+        mp = MatProblem.from_archive(ar, empty_rel, np.zeros(G + 1, np.uint64), maps=maps)
+        self.mat = MatRun(mp, want_dims=want_dims and len(ar.nodes) > 0, device_overrides=dict(
+            src_words=self.scan.d_words, relocs=self.scan.d_relocs, src_reloc_off=self.d_reloc_off,
+            src_nodes=self.d_nodes, src_node_off=self.d_node_off, graph_tmpl=self.d_tid,
+            tmpl_graph=self.d_tg))
+
+    def step(self, stream=None):
+        ar = self.ar
+        self.scan.launch(stream)
+        fdy.fdy_reloc_segment(self.scan.d_relocs, self.scan.d_count, self.scan.capacity,
+                              self.d_word_off, self.G + 1, self.d_reloc_off, stream)
+        fdy.fdy_fingerprint(self.d_nodes, self.d_node_off, self.G, ar.fp_mask, self.d_keys,
+                            self.d_tid, self.d_tg, self.d_nt, stream)
+        self.mat.launch(stream)
+
+    def status(self):
+        torch.cuda.synchronize()
+        return int(self.scan.d_status.item()) | int(self.mat.d_status.item())
