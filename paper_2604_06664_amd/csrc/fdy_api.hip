@@ -4,13 +4,13 @@
 
 namespace {
 int g_tune[FDY_TUNE_COUNT] = {
-    /* SCAN_TOP_LOG2   */ 12,
+    /* SCAN_TOP_LOG2   */ 14,
     /* SCAN_WG_PER_CU  */ 2,
     /* SCAN_SPIN_LIMIT */ 1 << 20,
     /* MAT_VARIANT     */ 0,
     0, 0, 0, 0};
 const int g_tune_lo[FDY_TUNE_COUNT] = {1, 1, 0, 0, 0, 0, 0, 0};
-const int g_tune_hi[FDY_TUNE_COUNT] = {13, 16, 1 << 30, 8, 0, 0, 0, 0};
+const int g_tune_hi[FDY_TUNE_COUNT] = {14, 16, 1 << 30, 8, 7, 0, 0, 0};
 }  // namespace
 
 extern "C" int fdy__tune_get(int knob) {

@@ -3,30 +3,67 @@
 // The scan classifies every 8-byte word of the captured argument blobs against the sorted
 // allocation table (the relaxation of Section 4.1.1's identical-layout requirement: find
 // every embedded pointer kernel-agnostically, because argument buffers are opaque -
-// Section 2.2, Appendix B).  It is a streaming pass bounded by HBM bandwidth:
+// Section 2.2, Appendix B).  It is one streaming pass over the words; what bounds it is HBM
+// bandwidth for the words plus the rate at which the memory system serves divergent lookups
+// into the table (measured on MI355X: ~2.5e11 per-lane loads/s when the target stays in L2,
+// ~8e10/s when it comes from the Infinity Cache), so table traffic per candidate is kept to
+// one 64-byte node per packed level plus one 128-byte line of the table.
 //
-//   * each workgroup draws tiles of TILE consecutive words from an atomic ticket, loads them
-//     with 16-byte coalesced loads and rejects every word outside the table's span with one
-//     subtract-and-compare;
-//   * the surviving candidates are compacted (wave ballot + popcount ranks, one wave scans
-//     the per-wave totals) into an LDS queue, so that the interval search runs on dense
-//     lanes only;
-//   * the search is hierarchical: a sampled level of the table (every 2^seg_log2-th base)
-//     is staged in LDS once per workgroup and binary-searched there; the remaining steps run
-//     on the table itself out of L2;
-//   * hits are compacted a second time in word order; the tile's global output position
-//     comes from a decoupled look-back over per-tile state words (flag and value packed in
-//     one 64-bit word, agent-scope relaxed atomics), so the input is read exactly once and
-//     the relocation table is written exactly once, in ascending word order.
+// Work decomposition.  A persistent workgroup of 8 waves stages the top level of the table
+// hierarchy in LDS once.  Work is handed out by an atomic ticket, but not per sub-tile
+// (same-address atomics complete at under 1e8/s on this chip, which alone would cap a
+// 1 GiB scan near 1.3 TB/s): a workgroup draws a chunk of 32 sub-tiles (512 words each)
+// per ticket and deals them to its waves in rows, sub-tile = base + row*8 + wave.  Per row a
+// wave
+//   1. loads 8 words per lane with 16-byte coalesced loads (the next row's loads are already
+//      in flight) and rejects every word outside the table's span with one
+//      subtract-and-compare;
+//   2. compacts the surviving candidates, in word order, into its private LDS queue (wave
+//      ballot + popcount ranks), so that the interval search runs on dense lanes only;
+//   3. searches the hierarchy, up to three candidates per lane interleaved so that their
+//      dependent steps overlap:
+//        level 0  sampled bases (every S-th, S = 8^k) as 31-bit keys (base - span_lo) >> sh
+//                 in LDS, binary search; a key equal to the candidate's is ambiguous and is
+//                 settled against the exact base in the table (rare);
+//        level j  k-1 packed arrays "every 8^j-th base" in global memory, small enough to
+//                 stay in L2: one 64-byte node of 8 keys per level;
+//        leaf     8 consecutive {base,size} entries of the table itself = one 128-byte line;
+//      results (region, offset, local word index) stay in registers;
+//   4. counts its hits into LDS.
+// One workgroup barrier per chunk makes the counts and the next ticket visible.  The output
+// position of the chunk comes from a decoupled look-back over per-CHUNK state words (flag and
+// value packed in one 64-bit word, agent-scope relaxed atomics), walked by one wave per
+// workgroup: a few hundred chunks are in flight at any time, so the walk is a handful of
+// 64-wide steps (a look-back over per-sub-tile states would walk thousands of entries).
+// The waves then write their relocation entries from registers in ascending word order.
+// The input is read exactly once and the relocation table written exactly once.
 //
-// Tickets are handed out in increasing order and a workgroup only ever waits for tiles
-// with smaller tickets, which are already running or finished; the wait is bounded by a
+// A sub-tile with more than 192 candidates (over a third of its words inside the table's
+// span - never the case for argument blobs, but legal) is handled in windows of queue size,
+// searched twice (count, then write); slower, same result.
+//
+// Tickets are handed out in increasing order and a wave only ever waits for chunks with
+// smaller numbers, which are already owned by resident workgroups; the wait is bounded by a
 // spin limit after which FDY_ST_SPIN is raised and the kernel still terminates.
 #include "fdy_device.hpp"
 #include "fdy_tune.h"
 
 namespace fdy {
 namespace {
+
+constexpr u64 kMaxWords = (1ull << 32) - 256;  // word and reloc indices are 32-bit
+constexpr int kWaves = 8;                      // waves per workgroup
+constexpr int kBlock = kWaves * 64;
+constexpr int kLoads = 4;                      // 16-byte loads per lane per sub-tile
+constexpr int kWpl = 2 * kLoads;               // words per lane per sub-tile
+constexpr int kSub = 64 * kWpl;                // words per sub-tile (512)
+constexpr int kRound = 4;                      // sub-tiles per wave per ticket round
+constexpr int kChunk = kWaves * kRound;        // sub-tiles a workgroup draws per ticket
+static_assert(kSub <= 65536 && kChunk <= 64, "one wave-wide load reads a chunk's sub-tile states");
+constexpr int kQcap = 192;                     // queue entries per wave
+constexpr int kRegRounds = 3;                  // rounds of 64 candidates a row keeps in registers
+constexpr int kMaxMid = 6;                     // packed levels in global memory
+constexpr u32 kMiss = 0xffffffffu;
 
 struct ScanParams {
   const u64* words;
@@ -37,13 +74,15 @@ struct ScanParams {
   u64 capacity;
   u64* d_count;
   u32* ticket;
-  const u64* top;  // [top_n] sampled bases, padded with ~0
-  u64* state;      // [n_tiles]
-  u32 n_tiles;
-  u32 top_n;     // power of two
-  u32 seg_log2;  // table entries per sampled base = 1 << seg_log2
+  const u32* top;  // [top_n] level-0 keys, padded with 0xffffffff
+  const u64* mid[kMaxMid];  // mid[j-1] = every 8^j-th base, padded with ~0
+  u64* cstate;     // [n_chunks] per-chunk totals / inclusive prefixes
+  u32 n_sub;       // sub-tiles
+  u32 top_n;       // power of two
+  u32 levels;      // k: S = 8^k table entries per level-0 key
   u32* d_status;
   u32 spin_limit;
+  u32 debug;  // timing experiments only (results are then wrong): 1 skip chunk walk, 4 skip loads
 };
 
 constexpr u64 kFlagAgg = 1ull << 62;
@@ -57,223 +96,457 @@ __device__ __forceinline__ void st_state(u64* p, u64 v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__device__ __forceinline__ u32 wave_incl_scan_u32(u32 v) {
-  const u32 l = lane_id();
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const u32 o = __shfl_up(v, d);
-    if (l >= (u32)d) v += o;
-  }
-  return v;
-}
-
 __device__ __forceinline__ u64 wave_sum_u64(u64 v) {
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
   return v;
 }
 
-// Decoupled look-back, executed by one whole wave.  Returns the number of hits in all tiles
-// before `tile` and publishes this tile's inclusive prefix.
-__device__ u64 lookback(u64* state, u32 tile, u64 total, u32 spin_limit, u32* d_status) {
-  const u32 l = lane_id();
-  if (tile == 0) {
-    if (l == 0) st_state(&state[0], kFlagInc | total);
-    return 0;
+// LDS traffic between lanes of one wave needs no hardware barrier (a wave's LDS operations
+// execute in order); this only stops the compiler from moving accesses across the point.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// Chunk states carry a 2-bit flag and a value in one 64-bit word (agent-scope relaxed
+// atomics; no fences needed because the payload travels in the same word as the flag): first
+// the chunk's hit total (flag AGG), later the inclusive prefix up to the chunk's end (flag
+// INC).  A chunk's exclusive prefix is found by walking the states backwards, 64 chunks per
+// step, summing totals until an inclusive prefix is met.  Waits are for chunks that are
+// already being processed, and they are bounded by the spin limit.
+__device__ __forceinline__ bool spin_once(u32& spins, u32 spin_limit, u32* d_status) {
+  if (++spins > spin_limit) {  // give up, flag it, let everybody proceed
+    if (lane_id() == 0) raise_status(d_status, FDY_ST_SPIN);
+    return false;
   }
-  if (l == 0) st_state(&state[tile], kFlagAgg | total);
+  __builtin_amdgcn_s_sleep(1);
+  return true;
+}
+
+// Number of hits in all chunks before `chunk`.
+__device__ __forceinline__ u64 chunk_exclusive_prefix(const u64* cstate, u32 chunk, u32 spin_limit,
+                                                      u32* d_status) {
+  const u32 l = lane_id();
+  if (chunk == 0) return 0;
   u64 excl = 0;
-  long long pos = (long long)tile - 1;
+  int pos = (int)chunk - 1;
   u32 spins = 0;
   for (;;) {
-    const long long idx = pos - (long long)l;
-    const u64 v = idx >= 0 ? ld_state(&state[idx]) : kFlagInc;  // before tile 0: prefix 0
+    const int idx = pos - (int)l;
+    const u64 v = idx >= 0 ? ld_state(&cstate[idx]) : kFlagInc;  // before chunk 0: prefix 0
     const u32 flag = (u32)(v >> 62);
     const u64 inc_mask = ballot(flag == 2);
     const u64 empty_mask = ballot(flag == 0);
     const u32 first_inc = inc_mask ? (u32)__ffsll((long long)inc_mask) - 1 : 64;
     const u64 need = first_inc >= 63 ? ~0ull : ((2ull << first_inc) - 1);  // lanes 0..first_inc
     if (empty_mask & need) {
-      if (++spins > spin_limit) {  // bounded wait: give up, flag it, let successors proceed
-        if (l == 0) raise_status(d_status, FDY_ST_SPIN);
-        break;
-      }
-      __builtin_amdgcn_s_sleep(2);
+      if (!spin_once(spins, spin_limit, d_status)) break;
       continue;
     }
     excl += wave_sum_u64(((need >> l) & 1) ? (v & kValMask) : 0);
     if (first_inc < 64) break;
     pos -= 64;
   }
-  if (l == 0) st_state(&state[tile], kFlagInc | ((excl + total) & kValMask));
   return excl;
 }
 
-template <int BLOCK, int L>
-__global__ __launch_bounds__(BLOCK) void scan_kernel(ScanParams p) {
-  constexpr int NW = BLOCK / 64;
-  constexpr int R = 2 * L;  // words per thread
-  constexpr int TILE = BLOCK * R;
-  static_assert(R * NW <= 64, "one wave scans the per-wave totals");
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  u64* top = reinterpret_cast<u64*>(smem_raw);  // [top_n]
-  u64* qw = top + p.top_n;                      // [TILE] candidate values
-  u32* qi = reinterpret_cast<u32*>(qw + TILE);  // [TILE] candidate local word index
-  __shared__ u32 s_tile, s_Q;
-  __shared__ u32 s_wtot[64], s_htot[64];
-  __shared__ u64 s_prefix;
-
-  const u32 tid = threadIdx.x;
-  const u32 lane = tid & 63;
-  const u32 wave = tid >> 6;
-  const u64 lt = lanemask_lt();
-
-  for (u32 i = tid; i < p.top_n; i += BLOCK) top[i] = p.top[i];
-  const u64 span_lo = p.table[0].base;
-  const u64 span_len = p.table[p.n_alloc - 1].base + p.table[p.n_alloc - 1].size - span_lo;
-  const u32 seg = 1u << p.seg_log2;
-
-  for (;;) {
-    if (tid == 0) s_tile = atomicAdd(p.ticket, 1u);
-    __syncthreads();  // also orders the top[] fill before its first use
-    const u32 tile = s_tile;
-    if (tile >= p.n_tiles) break;
-    const u64 wbase = (u64)tile * TILE;
-
-    // ---- load + span pre-filter + candidate ranks
-    u64 w[R];
-    bool c[R];
-    u32 crank[R];
-    const bool full = wbase + TILE <= p.n_words;
+__device__ __forceinline__ u64 wave_incl_scan_u64(u64 v) {
+  const u32 l = lane_id();
 #pragma unroll
-    for (int k = 0; k < L; ++k) {
-      const u64 idx = wbase + ((u64)k * BLOCK + tid) * 2;
-      if (full) {
-        const u64x2 v = *reinterpret_cast<const u64x2*>(p.words + idx);
-        w[2 * k] = v.x;
-        w[2 * k + 1] = v.y;
-        c[2 * k] = (v.x - span_lo) < span_len;
-        c[2 * k + 1] = (v.y - span_lo) < span_len;
-      } else {
-        const bool v0 = idx < p.n_words, v1 = idx + 1 < p.n_words;
-        w[2 * k] = v0 ? p.words[idx] : 0;
-        w[2 * k + 1] = v1 ? p.words[idx + 1] : 0;
-        c[2 * k] = v0 && (w[2 * k] - span_lo) < span_len;
-        c[2 * k + 1] = v1 && (w[2 * k + 1] - span_lo) < span_len;
-      }
-      const u64 b0 = ballot(c[2 * k]), b1 = ballot(c[2 * k + 1]);
-      const u32 pre = __popcll(b0 & lt) + __popcll(b1 & lt);
-      crank[2 * k] = pre;
-      crank[2 * k + 1] = pre + (c[2 * k] ? 1u : 0u);
-      if (lane == 0) s_wtot[k * NW + wave] = __popcll(b0) + __popcll(b1);
-    }
-    __syncthreads();
-    if (wave == 0) {
-      const u32 v = lane < L * NW ? s_wtot[lane] : 0;
-      const u32 inc = wave_incl_scan_u32(v);
-      if (lane < L * NW) s_wtot[lane] = inc - v;
-      if (lane == 63) s_Q = inc;
-    }
-    __syncthreads();
-    const u32 Q = s_Q;
-#pragma unroll
-    for (int k = 0; k < L; ++k) {
-      const u32 base = s_wtot[k * NW + wave];
-      const u32 li = (k * BLOCK + tid) * 2;
-      if (c[2 * k]) {
-        qw[base + crank[2 * k]] = w[2 * k];
-        qi[base + crank[2 * k]] = li;
-      }
-      if (c[2 * k + 1]) {
-        qw[base + crank[2 * k + 1]] = w[2 * k + 1];
-        qi[base + crank[2 * k + 1]] = li + 1;
-      }
-    }
-    __syncthreads();
+  for (int d = 1; d < 64; d <<= 1) {
+    const u64 o = __shfl_up(v, d);
+    if (l >= (u32)d) v += o;
+  }
+  return v;
+}
 
-    // ---- interval search on the dense candidate queue
-    bool hit[R];
-    u32 hreg[R], hidx[R], hrank[R];
-    u64 hoff[R];
+// Level-0 keys are (base - span_lo) >> shift with the smallest shift that makes every key of
+// the span fit 31 bits (0xffffffff pads).  What the truncation leaves ambiguous is settled on
+// the exact bases, so the shift affects speed only.
+__device__ __forceinline__ u32 key_shift_for(u64 span_len) {
+  const u64 m = span_len - 1;
+  const u32 bits = m ? 64u - (u32)__clzll((long long)m) : 0u;
+  return bits > 31u ? bits - 31u : 0u;
+}
+
+struct Found {
+  bool hit;
+  u32 region;
+  u64 offset;
+};
+
+// Interval search for N candidates per lane at once (each w lies inside the table's span).
+// The N chains are independent; writing every step for all of them lets their LDS and
+// global round trips overlap, which is what the dependent steps of one chain cannot do.
+template <int N>
+__device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 span_lo, u32 key_shift,
+                                       const u64 (&w)[N], Found (&f)[N]) {
+  u32 kw[N], i[N];
+  u64 n[N];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      hit[r] = false;
-      hreg[r] = 0;
-      hidx[r] = 0;
-      hoff[r] = 0;
-      hrank[r] = 0;
-      if ((u32)r * BLOCK < Q) {  // uniform over the workgroup
-        const u32 q = r * BLOCK + tid;
-        if (q < Q) {
-          const u64 wv = qw[q];
-          u32 i = 0;
-          for (u32 step = p.top_n >> 1; step; step >>= 1)
-            if (top[i + step] <= wv) i += step;
-          u64 j = (u64)i << p.seg_log2;
-          for (u32 step = seg >> 1; step; step >>= 1) {
-            const u64 jj = j + step;
-            if (jj < p.n_alloc && p.table[jj].base <= wv) j = jj;
-          }
-          const u64x2 e = *reinterpret_cast<const u64x2*>(&p.table[j]);
-          hoff[r] = wv - e.x;
-          hreg[r] = (u32)j;
-          hidx[r] = qi[q];
-          hit[r] = hoff[r] < e.y;
+  for (int c = 0; c < N; ++c) {
+    kw[c] = (u32)((w[c] - span_lo) >> key_shift);
+    i[c] = 0;
+  }
+  for (u32 step = p.top_n >> 1; step; step >>= 1) {
+#pragma unroll
+    for (int c = 0; c < N; ++c)
+      if (top[i[c] + step] <= kw[c]) i[c] += step;
+  }
+#pragma unroll
+  for (int c = 0; c < N; ++c) {
+    n[c] = i[c];  // node index at level `levels`: covers table entries [n * 8^levels, ...)
+    if (top[i[c]] == kw[c]) {
+      // equal keys: the sampled base may still lie above w; settle it on exact bases
+      const u32 sh = 3 * p.levels;
+      while (n[c] > 0 && p.table[n[c] << sh].base > w[c]) --n[c];
+    }
+  }
+  for (int j = (int)p.levels - 1; j >= 1; --j) {
+    const u64* m = p.mid[j - 1];
+#pragma unroll
+    for (int c = 0; c < N; ++c) n[c] *= 8;
+#pragma unroll
+    for (u32 step = 4; step; step >>= 1) {
+#pragma unroll
+      for (int c = 0; c < N; ++c)
+        if (m[n[c] + step] <= w[c]) n[c] += step;
+    }
+  }
+  u64x2 e[N];
+  if (p.levels == 0) {
+#pragma unroll
+    for (int c = 0; c < N; ++c) e[c] = *reinterpret_cast<const u64x2*>(&p.table[n[c]]);
+  } else {
+#pragma unroll
+    for (int c = 0; c < N; ++c) {
+      n[c] *= 8;
+      e[c] = *reinterpret_cast<const u64x2*>(&p.table[n[c]]);
+    }
+#pragma unroll
+    for (u32 step = 4; step; step >>= 1) {
+      u64x2 q[N];
+      bool in[N];
+#pragma unroll
+      for (int c = 0; c < N; ++c) {
+        in[c] = n[c] + step < p.n_alloc;
+        if (in[c]) q[c] = *reinterpret_cast<const u64x2*>(&p.table[n[c] + step]);
+      }
+#pragma unroll
+      for (int c = 0; c < N; ++c)
+        if (in[c] && q[c].x <= w[c]) {
+          n[c] += step;
+          e[c] = q[c];
         }
-        const u64 b = ballot(hit[r]);
-        hrank[r] = __popcll(b & lt);
-        if (lane == 0) s_htot[r * NW + wave] = __popcll(b);
-      } else if (lane == 0) {
-        s_htot[r * NW + wave] = 0;
-      }
     }
-    __syncthreads();
-    if (wave == 0) {
-      const u32 v = lane < R * NW ? s_htot[lane] : 0;
-      const u32 inc = wave_incl_scan_u32(v);
-      if (lane < R * NW) s_htot[lane] = inc - v;
-      const u32 H = __shfl(inc, 63);
-      const u64 excl = lookback(p.state, tile, H, p.spin_limit, p.d_status);
-      if (lane == 0) {
-        s_prefix = excl;
-        if (tile == p.n_tiles - 1) {
-          *p.d_count = excl + H;
-          if (excl + H > p.capacity) raise_status(p.d_status, FDY_ST_CAPACITY);
-        }
-      }
-    }
-    __syncthreads();
-    const u64 prefix = s_prefix;
+  }
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      if (hit[r]) {
-        const u64 pos = prefix + s_htot[r * NW + wave] + hrank[r];
-        if (pos < p.capacity) {
-          fdy_reloc o;
-          o.word = (u32)(wbase + hidx[r]);
-          o.region = hreg[r];
-          o.offset = hoff[r];
-          *reinterpret_cast<uint4*>(&p.relocs[pos]) = *reinterpret_cast<const uint4*>(&o);
-        }
-      }
-    }
-    // the barrier at the top of the next iteration separates these reads of s_htot /
-    // s_prefix and the queue from the next tile's writes
+  for (int c = 0; c < N; ++c) {
+    f[c].offset = w[c] - e[c].x;
+    f[c].region = (u32)n[c];
+    f[c].hit = f[c].offset < e[c].y;
   }
 }
 
-// Builds the sampled top level, clears the tile states and the ticket.
-__global__ void scan_init_kernel(const fdy_alloc* table, u32 n_alloc, u64* top, u32 top_n,
-                                 u32 seg_log2, u64* state, u32 n_tiles, u32* ticket, u64* d_count) {
-  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < top_n) {
-    const u64 j = i << seg_log2;
-    top[i] = j < n_alloc ? table[j].base : ~0ull;
+// One sub-tile's words as a wave holds them: 8 per lane, with the span pre-filter outcome and
+// each candidate's rank in word order (load k, lane, half).
+struct SubTile {
+  u64 w[kWpl];
+  bool c[kWpl];
+  u32 crank[kWpl];
+  u32 Q;
+};
+
+__device__ __forceinline__ void load_words(const ScanParams& p, u32 sub, u64 span_lo, u64 (&w)[kWpl]) {
+  const u32 lane = lane_id();
+  const u64 wbase = (u64)sub * kSub;
+  if (p.debug & 4) {
+#pragma unroll
+    for (int k = 0; k < kWpl; ++k) w[k] = span_lo - 1;
+  } else if (wbase + kSub <= p.n_words) {
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const u64x2 v = *reinterpret_cast<const u64x2*>(p.words + wbase + (k * 64 + lane) * 2);
+      w[2 * k] = v.x;
+      w[2 * k + 1] = v.y;
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const u64 idx = wbase + (k * 64 + lane) * 2;
+      w[2 * k] = idx < p.n_words ? p.words[idx] : span_lo - 1;  // outside the span
+      w[2 * k + 1] = idx + 1 < p.n_words ? p.words[idx + 1] : span_lo - 1;
+    }
   }
-  if (i < n_tiles) state[i] = 0;
+}
+
+__device__ __forceinline__ void filter_words(SubTile& t, u64 span_lo, u64 span_len) {
+  const u64 lt = lanemask_lt();
+  t.Q = 0;
+#pragma unroll
+  for (int k = 0; k < kLoads; ++k) {
+    t.c[2 * k] = (t.w[2 * k] - span_lo) < span_len;
+    t.c[2 * k + 1] = (t.w[2 * k + 1] - span_lo) < span_len;
+    const u64 b0 = ballot(t.c[2 * k]), b1 = ballot(t.c[2 * k + 1]);
+    const u32 pre = t.Q + __popcll(b0 & lt) + __popcll(b1 & lt);
+    t.crank[2 * k] = pre;
+    t.crank[2 * k + 1] = pre + (t.c[2 * k] ? 1u : 0u);
+    t.Q += __popcll(b0) + __popcll(b1);
+  }
+}
+
+// Candidates with rank in [win, win + wn) go to queue slots [0, wn).
+__device__ __forceinline__ void enqueue(const SubTile& t, u32 win, u32 wn, u64* qw, unsigned short* qi) {
+  const u32 lane = lane_id();
+  wave_lds_fence();
+#pragma unroll
+  for (int r = 0; r < kWpl; ++r)
+    if (t.c[r] && t.crank[r] - win < wn) {  // unsigned: also false below the window
+      qw[t.crank[r] - win] = t.w[r];
+      qi[t.crank[r] - win] = (unsigned short)(((r >> 1) * 64 + lane) * 2 + (r & 1));
+    }
+  wave_lds_fence();
+}
+
+__device__ __forceinline__ void store_reloc(const ScanParams& p, u64 at, u32 word, u32 region, u64 offset) {
+  if (at < p.capacity) {
+    fdy_reloc o;
+    o.word = word;
+    o.region = region;
+    o.offset = offset;
+    *reinterpret_cast<uint4*>(&p.relocs[at]) = *reinterpret_cast<const uint4*>(&o);
+  }
+}
+
+// Dense sub-tile (more candidates than the register-resident path holds): windows of queue
+// size; counts when `write` is false, writes from position `pos` otherwise.  Returns hits.
+__device__ u64 dense_pass(const ScanParams& p, const SubTile& t, const u32* top, u64 span_lo,
+                          u32 key_shift, u64* qw, unsigned short* qi, u64 wbase, bool write, u64 pos) {
+  const u32 lane = lane_id();
+  const u64 lt = lanemask_lt();
+  u64 H = 0;
+  for (u32 win = 0; win < t.Q; win += kQcap) {
+    const u32 wn = t.Q - win < (u32)kQcap ? t.Q - win : (u32)kQcap;
+    enqueue(t, win, wn, qw, qi);
+    for (u32 q0 = 0; q0 < wn; q0 += 64) {
+      const u32 q = q0 + lane;
+      const bool valid = q < wn;
+      const u64 wv[1] = {valid ? qw[q] : span_lo};
+      Found f[1];
+      search<1>(p, top, span_lo, key_shift, wv, f);
+      const bool hit = valid && f[0].hit;
+      const u64 b = ballot(hit);
+      if (write && hit)
+        store_reloc(p, pos + H + __popcll(b & lt), (u32)(wbase + qi[q]), f[0].region, f[0].offset);
+      H += __popcll(b);
+    }
+  }
+  return H;
+}
+
+// Searches queue rounds [R0, R0 + N) (64 entries each), N per lane in flight at once; results
+// stay in the caller's registers (region = kMiss for "no hit").
+template <int N, int R0>
+__device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, u64 span_lo, u32 key_shift,
+                                           const u64* qw, const unsigned short* qi, u32 Q,
+                                           u32 (&reg)[kRegRounds],
+                                           u64 (&off)[kRegRounds], u32 (&idx)[kRegRounds], u64& H) {
+  const u32 lane = lane_id();
+  u64 wv[N];
+  Found f[N];
+  bool valid[N];
+#pragma unroll
+  for (int r = 0; r < N; ++r) {
+    valid[r] = (R0 + r) * 64 + lane < Q;
+    wv[r] = valid[r] ? qw[(R0 + r) * 64 + lane] : span_lo;
+  }
+  search<N>(p, top, span_lo, key_shift, wv, f);
+#pragma unroll
+  for (int r = 0; r < N; ++r) {
+    const bool hit = valid[r] && f[r].hit;
+    reg[R0 + r] = hit ? f[r].region : kMiss;
+    off[R0 + r] = f[r].offset;
+    idx[R0 + r] = valid[r] ? qi[(R0 + r) * 64 + lane] : 0;
+    H += __popcll(ballot(hit));
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  __shared__ u32 s_next[2];           // next chunk's first sub-tile, per round parity
+  __shared__ u32 s_cnt[2][kChunk];    // hit counts of the chunk's sub-tiles
+  __shared__ u64 s_excl[2];           // chunk's exclusive prefix, from the closer wave
+  __shared__ u32 s_ready[2];          // round tag: s_excl[parity] is valid for round tag-1
+  u32* top = reinterpret_cast<u32*>(smem_raw);  // [top_n]
+  unsigned char* qbase = smem_raw + (size_t)p.top_n * 4;
+  const u32 tid = threadIdx.x;
+  const u32 lane = tid & 63;
+  const u32 wave = tid >> 6;
+  u64* qw = reinterpret_cast<u64*>(qbase) + wave * kQcap;                              // value
+  unsigned short* qi =
+      reinterpret_cast<unsigned short*>(qbase + (size_t)kWaves * kQcap * 8) + wave * kQcap;  // local word
+  const u64 lt = lanemask_lt();
+  const bool closer = wave == kWaves - 1;  // one wave per workgroup speaks for the chunk
+
+  for (u32 i = tid; i < p.top_n; i += kBlock) top[i] = p.top[i];
+  if (tid == 0) {
+    s_ready[0] = 0;
+    s_ready[1] = 0;
+    s_next[1] = atomicAdd(p.ticket, (u32)kChunk);  // round 0 reads parity (0 - 1) & 1
+  }
+  __syncthreads();
+
+  const u64 span_lo = p.table[0].base;
+  const u64 span_len = p.table[p.n_alloc - 1].base + p.table[p.n_alloc - 1].size - span_lo;
+  const u32 key_shift = key_shift_for(span_len);
+
+  SubTile t;
+  u32 base = s_next[1];
+  if (base + wave < p.n_sub) load_words(p, base + wave, span_lo, t.w);
+
+  for (u32 round = 0; base < p.n_sub; ++round) {
+    const u32 b = round & 1;
+    u32 next = 0;
+    if (tid == 0) next = atomicAdd(p.ticket, (u32)kChunk);  // published at this round's barrier
+
+    // Results of the rows, register-resident: per row up to kRegRounds rounds of 64 candidates.
+    u32 r_reg[kRound][kRegRounds];
+    u32 r_idx[kRound][kRegRounds];
+    u64 r_off[kRound][kRegRounds];
+    u32 r_Q[kRound];
+    u32 r_H[kRound];
+
+    // ---- phase 1: search and count every row of the chunk
+#pragma unroll
+    for (int j = 0; j < kRound; ++j) {
+      const u32 sub = base + j * kWaves + wave;
+      r_Q[j] = 0;
+      r_H[j] = 0;
+#pragma unroll
+      for (int r = 0; r < kRegRounds; ++r) r_reg[j][r] = kMiss;
+      if (sub < p.n_sub) {
+        filter_words(t, span_lo, span_len);
+        u64 nw[kWpl];
+        const bool more = j + 1 < kRound && sub + kWaves < p.n_sub;
+        if (more) load_words(p, sub + kWaves, span_lo, nw);  // next row's words, in flight
+        u64 H = 0;
+        if (t.Q <= (u32)(kRegRounds * 64)) {
+          enqueue(t, 0, t.Q, qw, qi);
+          // all rounds of the row in flight together (up to three chains per lane)
+#define FDY_RUN(N, R0) run_rounds<N, R0>(p, top, span_lo, key_shift, qw, qi, t.Q, r_reg[j], r_off[j], r_idx[j], H)
+          const u32 nr = (t.Q + 63) >> 6;
+          if (nr == 1) FDY_RUN(1, 0);
+          else if (nr == 2) FDY_RUN(2, 0);
+          else if (nr == 3) FDY_RUN(3, 0);
+#undef FDY_RUN
+        } else {
+          H = dense_pass(p, t, top, span_lo, key_shift, qw, qi, (u64)sub * kSub, false, 0);
+        }
+        r_Q[j] = t.Q;
+        r_H[j] = (u32)H;
+        if (more) {
+#pragma unroll
+          for (int k = 0; k < kWpl; ++k) t.w[k] = nw[k];
+        }
+      }
+      if (lane == 0) s_cnt[b][j * kWaves + wave] = r_H[j];
+    }
+    if (tid == 0) s_next[b] = next;
+    __syncthreads();  // the one barrier per round: counts and the next ticket are visible
+
+    // next round's first row: issue its loads before waiting for the prefix
+    const u32 nbase = s_next[b];
+    if (nbase + wave < p.n_sub) load_words(p, nbase + wave, span_lo, t.w);
+
+    // ---- phase 2: output positions, ordered writes
+    const u32 chunk = base / kChunk;
+    const u64 cnt = lane < (u32)kChunk ? s_cnt[b][lane] : 0;
+    const u64 cnt_incl = wave_incl_scan_u64(cnt);  // lane l: hits of sub-tiles base..base+l
+    u64 chunk_excl = 0;
+    if (closer) {
+      const u64 total = __shfl(cnt_incl, 63);
+      if (lane == 0) st_state(&p.cstate[chunk], (chunk == 0 ? kFlagInc : kFlagAgg) | total);
+      chunk_excl = (p.debug & 1) ? 0 : chunk_exclusive_prefix(p.cstate, chunk, p.spin_limit, p.d_status);
+      if (lane == 0) {
+        if (chunk != 0) st_state(&p.cstate[chunk], kFlagInc | ((chunk_excl + total) & kValMask));
+        if (base + kChunk >= p.n_sub) {  // the last chunk
+          *p.d_count = chunk_excl + total;
+          if (chunk_excl + total > p.capacity) raise_status(p.d_status, FDY_ST_CAPACITY);
+        }
+        s_excl[b] = chunk_excl;
+        __hip_atomic_store(&s_ready[b], round + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
+    } else {
+      u32 spins = 0;
+      while (__hip_atomic_load(&s_ready[b], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) != round + 1)
+        if (!spin_once(spins, p.spin_limit, p.d_status)) break;
+      chunk_excl = s_excl[b];
+    }
+#pragma unroll
+    for (int j = 0; j < kRound; ++j) {
+      const u32 sub = base + j * kWaves + wave;
+      if (sub < p.n_sub) {
+        const u64 wbase = (u64)sub * kSub;
+        const u32 in_chunk = j * kWaves + wave;
+        const u64 excl = chunk_excl + __shfl(cnt_incl, in_chunk) - r_H[j];
+        if (r_Q[j] <= (u32)(kRegRounds * 64)) {
+          u64 pos = excl;
+#pragma unroll
+          for (int r = 0; r < kRegRounds; ++r) {
+            const bool hit = r_reg[j][r] != kMiss;
+            const u64 bl = ballot(hit);
+            if (hit) store_reloc(p, pos + __popcll(bl & lt), (u32)(wbase + r_idx[j][r]), r_reg[j][r], r_off[j][r]);
+            pos += __popcll(bl);
+          }
+        } else {
+          SubTile d;
+          load_words(p, sub, span_lo, d.w);
+          filter_words(d, span_lo, span_len);
+          dense_pass(p, d, top, span_lo, key_shift, qw, qi, wbase, true, excl);
+        }
+      }
+    }
+    base = nbase;
+  }
+}
+
+struct ScanInit {
+  const fdy_alloc* table;
+  u32 n_alloc;
+  u32* top;
+  u32 top_n;
+  u32 levels;
+  u64* mid[kMaxMid];
+  u32 mid_len[kMaxMid];
+  u32 n_sub;
+  u64* cstate;
+  u32 n_chunks;
+  u32* ticket;
+  u64* d_count;
+};
+
+// Builds the level-0 keys and the packed mid levels, clears the sub-tile states and ticket.
+__global__ void scan_init_kernel(ScanInit a) {
+  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  const u64 span_lo = a.n_alloc ? a.table[0].base : 0;
+  const u64 span_len =
+      a.n_alloc ? a.table[a.n_alloc - 1].base + a.table[a.n_alloc - 1].size - span_lo : 1;
+  const u32 key_shift = key_shift_for(span_len);
+  if (i < a.top_n) {
+    const u64 j = i << (3 * a.levels);
+    a.top[i] = j < a.n_alloc ? (u32)((a.table[j].base - span_lo) >> key_shift) : 0xffffffffu;
+  }
+  for (u32 lv = 1; lv < a.levels; ++lv) {
+    if (i < a.mid_len[lv - 1]) {
+      const u64 j = i << (3 * lv);
+      a.mid[lv - 1][i] = j < a.n_alloc ? a.table[j].base : ~0ull;
+    }
+  }
+  if (i < a.n_chunks) a.cstate[i] = 0;
   if (i == 0) {
-    *ticket = 0;
-    if (n_tiles == 0 || n_alloc == 0) *d_count = 0;
+    *a.ticket = 0;
+    if (a.n_sub == 0 || a.n_alloc == 0) *a.d_count = 0;
   }
 }
 
@@ -289,35 +562,49 @@ __global__ void reloc_segment_kernel(const fdy_reloc* relocs, const u64* d_count
   if (lane_id() == 0) reloc_off[s] = r;
 }
 
-constexpr u64 kMaxWords = (1ull << 32) - 256;  // word and reloc indices are 32-bit
-constexpr int kBlock = 512;
-constexpr int kL = 2;
-constexpr int kTile = kBlock * kL * 2;
-
 u32 pow2_ceil(u32 v) {
   u32 p = 1;
   while (p < v) p <<= 1;
   return p;
 }
 
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
 struct ScanPlan {
-  u32 top_n, seg_log2, n_tiles;
-  size_t off_top, off_state, total;
+  u32 top_n, levels, n_sub;
+  u32 mid_len[kMaxMid];
+  u32 n_chunks;
+  size_t off_top, off_mid[kMaxMid], off_cstate, total;
 };
 
-ScanPlan make_plan(u64 n_words, u32 n_alloc) {
-  ScanPlan pl;
+bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
   const u32 top_cap = 1u << fdy__tune_get(FDY_TUNE_SCAN_TOP_LOG2);
-  u32 seg_log2 = 0;
-  while ((((u64)n_alloc + (1ull << seg_log2) - 1) >> seg_log2) > top_cap) ++seg_log2;
-  const u32 sampled = (u32)(((u64)n_alloc + (1ull << seg_log2) - 1) >> seg_log2);
-  pl.top_n = pow2_ceil(sampled < 2 ? 2 : sampled);
-  pl.seg_log2 = seg_log2;
-  pl.n_tiles = (u32)((n_words + kTile - 1) / kTile);
-  pl.off_top = 256;
-  pl.off_state = pl.off_top + (((size_t)pl.top_n * 8 + 255) & ~(size_t)255);
-  pl.total = pl.off_state + (((size_t)pl.n_tiles * 8 + 255) & ~(size_t)255);
-  return pl;
+  u32 levels = 0;
+  while ((((u64)n_alloc + (1ull << (3 * levels)) - 1) >> (3 * levels)) > top_cap) ++levels;
+  if (levels > (u32)kMaxMid) return false;
+  const u32 sampled = (u32)(((u64)n_alloc + (1ull << (3 * levels)) - 1) >> (3 * levels));
+  pl->top_n = pow2_ceil(sampled < 2 ? 2 : sampled);
+  pl->levels = levels;
+  pl->n_sub = (u32)((n_words + kSub - 1) / kSub);
+  size_t off = 256;
+  pl->off_top = off;
+  off += align256((size_t)pl->top_n * 4);
+  for (int j = 0; j < kMaxMid; ++j) {
+    pl->mid_len[j] = 0;
+    pl->off_mid[j] = off;
+  }
+  for (u32 lv = 1; lv < levels; ++lv) {
+    // level lv holds every 8^lv-th base; its parent has ceil(A / 8^(lv+1)) nodes of 8 keys
+    const u64 parents = ((u64)n_alloc + (1ull << (3 * (lv + 1))) - 1) >> (3 * (lv + 1));
+    pl->mid_len[lv - 1] = (u32)(parents * 8);
+    pl->off_mid[lv - 1] = off;
+    off += align256((size_t)pl->mid_len[lv - 1] * 8);
+  }
+  pl->n_chunks = (pl->n_sub + kChunk - 1) / kChunk;
+  pl->off_cstate = off;
+  off += align256((size_t)pl->n_chunks * 8);
+  pl->total = off;
+  return true;
 }
 
 }  // namespace
@@ -327,7 +614,9 @@ using namespace fdy;
 
 extern "C" size_t fdy_scan_workspace_bytes(uint64_t n_words, uint32_t n_alloc) {
   if (n_words > kMaxWords) return 0;
-  return make_plan(n_words, n_alloc).total;
+  ScanPlan pl;
+  if (!make_plan(n_words, n_alloc, &pl)) return 0;
+  return pl.total;
 }
 
 extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
@@ -339,24 +628,36 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   if (n_words && (!d_words || ((uintptr_t)d_words & 15))) return FDY_ERR_INVALID_ARG;
   if (n_alloc && (!d_table || ((uintptr_t)d_table & 15))) return FDY_ERR_INVALID_ARG;
   if (reloc_capacity && (!d_relocs || ((uintptr_t)d_relocs & 15))) return FDY_ERR_INVALID_ARG;
-  const ScanPlan pl = make_plan(n_words, n_alloc);
+  ScanPlan pl;
+  if (!make_plan(n_words, n_alloc, &pl)) return FDY_ERR_INVALID_ARG;
   if (!d_workspace || ((uintptr_t)d_workspace & 255) || workspace_bytes < pl.total)
     return FDY_ERR_WORKSPACE;
   hipStream_t stream = (hipStream_t)hip_stream;
   (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
   unsigned char* ws = (unsigned char*)d_workspace;
-  u32* ticket = (u32*)ws;
-  u64* top = (u64*)(ws + pl.off_top);
-  u64* state = (u64*)(ws + pl.off_state);
-
-  const u32 n_init = pl.top_n > pl.n_tiles ? pl.top_n : pl.n_tiles;
+  ScanInit a;
+  a.table = d_table;
+  a.n_alloc = n_alloc;
+  a.top = (u32*)(ws + pl.off_top);
+  a.top_n = pl.top_n;
+  a.levels = pl.levels;
+  for (int j = 0; j < kMaxMid; ++j) {
+    a.mid[j] = (u64*)(ws + pl.off_mid[j]);
+    a.mid_len[j] = pl.mid_len[j];
+  }
+  a.n_sub = pl.n_sub;
+  a.cstate = (u64*)(ws + pl.off_cstate);
+  a.n_chunks = pl.n_chunks;
+  a.ticket = (u32*)ws;
+  a.d_count = (u64*)d_count;
+  u32 n_init = pl.top_n > pl.n_chunks ? pl.top_n : pl.n_chunks;
+  for (int j = 0; j < kMaxMid; ++j)
+    if (pl.mid_len[j] > n_init) n_init = pl.mid_len[j];
   prof_begin(FDY_PROF_SCAN_INIT, stream);
-  hipLaunchKernelGGL(scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream,
-                     d_table, n_alloc, top, pl.top_n, pl.seg_log2, state, pl.n_tiles, ticket,
-                     (u64*)d_count);
+  hipLaunchKernelGGL(scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream, a);
   prof_end(FDY_PROF_SCAN_INIT, stream);
   FDY_HIP_TRY(hipGetLastError());
-  if (pl.n_tiles == 0 || n_alloc == 0) return FDY_OK;  // nothing can be a pointer
+  if (pl.n_sub == 0 || n_alloc == 0) return FDY_OK;  // nothing can be a pointer
 
   ScanParams p;
   p.words = (const u64*)d_words;
@@ -366,27 +667,29 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   p.relocs = d_relocs;
   p.capacity = reloc_capacity;
   p.d_count = (u64*)d_count;
-  p.ticket = ticket;
-  p.top = top;
-  p.state = state;
-  p.n_tiles = pl.n_tiles;
+  p.ticket = a.ticket;
+  p.top = a.top;
+  for (int j = 0; j < kMaxMid; ++j) p.mid[j] = a.mid[j];
+  p.cstate = a.cstate;
+  p.n_sub = pl.n_sub;
   p.top_n = pl.top_n;
-  p.seg_log2 = pl.seg_log2;
+  p.levels = pl.levels;
   p.d_status = d_status;
   p.spin_limit = (u32)fdy__tune_get(FDY_TUNE_SCAN_SPIN_LIMIT);
+  p.debug = (u32)fdy__tune_get(FDY_TUNE_SCAN_DEBUG);
 
-  const size_t lds = (size_t)pl.top_n * 8 + (size_t)kTile * 12;
+  const size_t lds = (size_t)pl.top_n * 4 + (size_t)kWaves * kQcap * 10;
   int dev = 0, n_cu = 256;
   FDY_HIP_TRY(hipGetDevice(&dev));
   FDY_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-  auto kern = scan_kernel<kBlock, kL>;
-  FDY_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+  FDY_HIP_TRY(hipFuncSetAttribute((const void*)scan_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)lds));
   const u32 per_cu = (u32)fdy__tune_get(FDY_TUNE_SCAN_WG_PER_CU);
   u32 grid = (u32)n_cu * per_cu;
-  if (grid > pl.n_tiles) grid = pl.n_tiles;
+  const u32 useful = pl.n_chunks;
+  if (grid > useful) grid = useful;
   prof_begin(FDY_PROF_SCAN_MAIN, stream);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), lds, stream, p);
+  hipLaunchKernelGGL(scan_kernel, dim3(grid), dim3(kBlock), lds, stream, p);
   prof_end(FDY_PROF_SCAN_MAIN, stream);
   FDY_HIP_TRY(hipGetLastError());
   return FDY_OK;

@@ -82,11 +82,43 @@ def test_scan_hierarchical_levels(hip, oracle):
     ar = small(4)  # 65,536 allocations
     old = fdy.tune_get(fdy.TUNE_SCAN_TOP_LOG2)
     try:
-        for top_log2 in (1, 3, 8, 12, 13):
+        for top_log2 in (1, 3, 8, 12, 14):
             assert fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, top_log2) >= 0
             check_scan(hip, oracle, ar.words[:300000], ar.table, tag=f"top_log2={top_log2}")
             check_scan(hip, oracle, ar.words[:5000], ar.table[:1000], tag=f"A=1000 top_log2={top_log2}")
             check_scan(hip, oracle, ar.words[:5000], ar.table[:1025], tag=f"A=1025 top_log2={top_log2}")
+    finally:
+        fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, old)
+
+
+def test_scan_truncated_key_ambiguity(hip, oracle):
+    """The LDS level holds truncated keys; candidates whose key equals a sampled base's key
+    must be settled on exact bases.  Unaligned bases in a very wide span, words placed just
+    below / at / above bases inside the same truncation granule, and a cluster of tiny
+    allocations that all share one key."""
+    import paper_2604_06664_amd as fdy
+
+    rng = np.random.default_rng(21)
+    A = 40000
+    base = (np.uint64(0x1000_0000_0005) + np.arange(A, dtype=np.uint64) * np.uint64(1 << 33)
+            + rng.integers(0, 4096, A).astype(np.uint64) * np.uint64(8))
+    size = np.full(A, 100, np.uint64)
+    # a cluster of 3000 16-byte allocations, 16 bytes apart, inside one key granule
+    cb = base[100] + np.uint64(1 << 20) + np.arange(3000, dtype=np.uint64) * np.uint64(16)
+    allb = np.concatenate([base, cb])
+    alls = np.concatenate([size, np.full(3000, 16, np.uint64)])
+    order = np.argsort(allb)
+    table = np.zeros(len(allb), L.ALLOC)
+    table["base"], table["size"] = allb[order], alls[order]
+    assert oracle.table_validate(table)[0] == 0
+    pick = rng.integers(0, len(table), 60000)
+    delta = rng.choice(np.array([-9, -1, 0, 1, 15, 16, 99, 100, 101, 5000], np.int64), 60000)
+    words = (table["base"][pick].astype(np.int64) + delta).astype(np.uint64)
+    old = fdy.tune_get(fdy.TUNE_SCAN_TOP_LOG2)
+    try:
+        for top_log2 in (14, 9, 4):
+            fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, top_log2)
+            check_scan(hip, oracle, words, table, tag=f"ambiguous keys top_log2={top_log2}")
     finally:
         fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, old)
 
