@@ -7,11 +7,13 @@
 //
 //   prep A (one workgroup)   prefix sums over the output graphs: where each graph's words,
 //                            nodes and tiles start; verifies the caller's totals.
-//   prep B (one wave / tile) resolves each output tile once, independent of the base map:
+//   prep B (one thread/tile) resolves each output tile once, independent of the base map:
 //                            its graph, template, source words, and the sub-ranges of the
-//                            template's relocation list, the graph's override list and each
-//                            rank's patch list that fall inside the tile (wave-cooperative
-//                            64-ary lower bounds).
+//                            template's relocation list and the graph's override list that
+//                            fall inside the tile; prep C (one thread per tile and rank) does
+//                            the same for each rank's patch list.  Plain per-lane binary
+//                            searches: tens of thousands of them run side by side, and one
+//                            request per halving is what the memory system serves best.
 //   main  (tile x map)       stages the template tile in LDS, scatters c2 rebased pointers
 //                            (new_base[m][region] + offset), c3 32-bit overrides and c4
 //                            64-bit rank patches into LDS in that order, then streams the
@@ -142,20 +144,32 @@ __global__ __launch_bounds__(1024) void mat_prep_graphs_kernel(MatParams p) {
   }
 }
 
+// Per-lane lower bound: first index in [lo, hi) whose key is not below target (hi if none).
+// One dependent load per halving; used where thousands of independent searches run side by
+// side (one per lane), so that the memory system sees few requests per search.
+template <typename KeyFn>
+__device__ __forceinline__ u32 lane_lower_bound(KeyFn key, u32 lo, u32 hi, u64 target) {
+  while (lo < hi) {
+    const u32 mid = lo + ((hi - lo) >> 1);
+    if (key(mid) < target) lo = mid + 1;
+    else hi = mid;
+  }
+  return lo;
+}
+
+// One thread per output tile (independent of the base map).
 __global__ __launch_bounds__(256) void mat_prep_tiles_kernel(MatParams p) {
   const fdy_mat_desc& d = p.d;
-  const u32 j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const u32 j = blockIdx.x * 256 + threadIdx.x;
   if (j >= p.ws.max_tiles) return;
-  const u32 l = lane_id();
   MatTile* ent = &p.ws.tiles[j];
   if (j >= p.ws.hdr->n_tiles) {
-    if (l == 0) ent->n_words = 0;
+    ent->n_words = 0;
     return;
   }
   const u64* tile_off = p.ws.tile_off;
   // largest g with tile_off[g] <= j
-  const u32 g =
-      wave_lower_bound([&](u32 i) { return tile_off[i]; }, 0u, d.n_graphs + 1u, (u64)j + 1) - 1;
+  const u32 g = lane_lower_bound([&](u32 i) { return tile_off[i]; }, 0u, d.n_graphs + 1u, (u64)j + 1) - 1;
   const u32 t = d.graph_tmpl[g];
   const u32 s = d.tmpl_graph[t];  // valid: graphs with a bad template have no tiles
   const u64 w0 = d.src_word_off[s];
@@ -165,39 +179,46 @@ __global__ __launch_bounds__(256) void mat_prep_tiles_kernel(MatParams p) {
   const u64 src_word = w0 + k0;
   const fdy_reloc* relocs = d.relocs;
   const u32 rl0 = (u32)d.src_reloc_off[s], rl1 = (u32)d.src_reloc_off[s + 1];
-  const u32 reloc_lo = wave_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, rl0, rl1, src_word);
+  const u32 reloc_lo = lane_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, rl0, rl1, src_word);
+  // the list is strictly ascending by word: at most n entries fall inside the tile
+  const u32 cap = rl1 - reloc_lo < n ? rl1 : reloc_lo + n;
   const u32 reloc_hi =
-      wave_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, reloc_lo, rl1, src_word + n);
+      lane_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, reloc_lo, cap, src_word + n);
   const fdy_ovr32* ovr = d.ovr;
   const u32 ov0 = (u32)d.ovr_off[g], ov1 = (u32)d.ovr_off[g + 1];
-  const u32 ovr_lo = wave_lower_bound([&](u32 i) { return (u64)ovr[i].byte_off; }, ov0, ov1, k0 * 8);
+  const u32 ovr_lo = lane_lower_bound([&](u32 i) { return (u64)ovr[i].byte_off; }, ov0, ov1, k0 * 8);
   const u32 ovr_hi =
-      wave_lower_bound([&](u32 i) { return (u64)ovr[i].byte_off; }, ovr_lo, ov1, (k0 + n) * 8);
-  if (d.map_rank) {
-    const fdy_patch* patch = d.patch;
-    for (u32 r = 0; r < d.n_ranks; ++r) {
-      const u64 row = (u64)t * d.n_ranks + r;
-      const u32 p0 = (u32)d.patch_off[row], p1 = (u32)d.patch_off[row + 1];
-      const u32 lo = wave_lower_bound([&](u32 i) { return (u64)patch[i].word; }, p0, p1, k0);
-      const u32 hi = wave_lower_bound([&](u32 i) { return (u64)patch[i].word; }, lo, p1, k0 + n);
-      if (l == 0) p.ws.tile_patch[(u64)j * d.n_ranks + r] = make_uint2(lo, hi);
-    }
-  }
-  if (l == 0) {
-    MatTile e;
-    e.src_word = src_word;
-    e.out_word = p.ws.out_word_off[g] + k0;
-    e.n_words = n;
-    e.g = g;
-    e.tmpl = t;
-    e.k0 = (u32)k0;
-    e.reloc_lo = reloc_lo;
-    e.reloc_hi = reloc_hi;
-    e.ovr_lo = ovr_lo;
-    e.ovr_hi = ovr_hi;
-    e.pad[0] = e.pad[1] = e.pad[2] = e.pad[3] = 0;
-    *ent = e;
-  }
+      lane_lower_bound([&](u32 i) { return (u64)ovr[i].byte_off; }, ovr_lo, ov1, (k0 + n) * 8);
+  MatTile e;
+  e.src_word = src_word;
+  e.out_word = p.ws.out_word_off[g] + k0;
+  e.n_words = n;
+  e.g = g;
+  e.tmpl = t;
+  e.k0 = (u32)k0;
+  e.reloc_lo = reloc_lo;
+  e.reloc_hi = reloc_hi;
+  e.ovr_lo = ovr_lo;
+  e.ovr_hi = ovr_hi;
+  e.pad[0] = e.pad[1] = e.pad[2] = e.pad[3] = 0;
+  *ent = e;
+}
+
+// One thread per (output tile, rank): the slice of the rank's patch list inside the tile.
+__global__ __launch_bounds__(256) void mat_prep_patch_kernel(MatParams p) {
+  const fdy_mat_desc& d = p.d;
+  const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;
+  const u32 R = d.n_ranks;
+  if (i >= (u64)p.ws.hdr->n_tiles * R) return;
+  const u32 j = (u32)(i / R), r = (u32)(i % R);
+  const MatTile& e = p.ws.tiles[j];
+  const fdy_patch* patch = d.patch;
+  const u64 row = (u64)e.tmpl * R + r;
+  const u32 p0 = (u32)d.patch_off[row], p1 = (u32)d.patch_off[row + 1];
+  const u32 lo = lane_lower_bound([&](u32 q) { return (u64)patch[q].word; }, p0, p1, (u64)e.k0);
+  const u32 hi =
+      lane_lower_bound([&](u32 q) { return (u64)patch[q].word; }, lo, p1, (u64)e.k0 + e.n_words);
+  p.ws.tile_patch[i] = make_uint2(lo, hi);
 }
 
 __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
@@ -207,8 +228,19 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
   const MatTile ent = p.ws.tiles[j];
   const u32 n = ent.n_words;
   if (n == 0) return;
+  // c1: stage the template tile in LDS; 16-byte global loads from the first even word on
   const u64* src = d.src_words + ent.src_word;
-  for (u32 i = tid; i < n; i += kMatBlock) buf[i] = src[i];
+  {
+    const u32 head = (u32)(ent.src_word & 1) & (n ? 1u : 0u);  // words before 16-byte alignment
+    const u32 pairs = (n - head) >> 1;
+    if (tid == 0 && head) buf[0] = src[0];
+    for (u32 i = tid; i < pairs; i += kMatBlock) {
+      const u64x2 v = *reinterpret_cast<const u64x2*>(src + head + 2 * i);
+      buf[head + 2 * i] = v.x;
+      buf[head + 2 * i + 1] = v.y;
+    }
+    if (tid == 0 && head + 2 * pairs < n) buf[n - 1] = src[n - 1];
+  }
   __syncthreads();
   // c2: rebase
   const u64* nb = d.new_base + (u64)m * d.n_alloc;
@@ -247,8 +279,23 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
     __syncthreads();
   }
   if (bad) raise_status(p.d_status, FDY_ST_BAD_INDEX);
-  u64* out = p.out_words + (u64)m * d.out_words_per_map + ent.out_word;
-  for (u32 i = tid; i < n; i += kMatBlock) out[i] = buf[i];
+  // stream the tile out: 16-byte non-temporal stores (the output is written once and not
+  // read again here; keeping it out of L2 leaves the templates, lists and base maps there)
+  const u64 out_at = (u64)m * d.out_words_per_map + ent.out_word;
+  u64* out = p.out_words + out_at;
+  {
+    const u32 head = (u32)(out_at & 1) & (n ? 1u : 0u);
+    const u32 pairs = (n - head) >> 1;
+    if (tid == 0 && head) __builtin_nontemporal_store(buf[0], out);
+    for (u32 i = tid; i < pairs; i += kMatBlock) {
+      typedef u64 v2u64 __attribute__((ext_vector_type(2)));
+      v2u64 v;
+      v.x = buf[head + 2 * i];
+      v.y = buf[head + 2 * i + 1];
+      __builtin_nontemporal_store(v, reinterpret_cast<v2u64*>(out + head + 2 * i));
+    }
+    if (tid == 0 && head + 2 * pairs < n) __builtin_nontemporal_store(buf[n - 1], out + n - 1);
+  }
 }
 
 __global__ __launch_bounds__(256) void mat_dims_kernel(MatParams p) {
@@ -365,7 +412,11 @@ extern "C" int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words
   FDY_HIP_TRY(hipGetLastError());
   if (p.ws.max_tiles) {
     prof_begin(FDY_PROF_MAT_PREP_TILES, stream);
-    hipLaunchKernelGGL(mat_prep_tiles_kernel, dim3((p.ws.max_tiles + 3) / 4), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(mat_prep_tiles_kernel, dim3((p.ws.max_tiles + 255) / 256), dim3(256), 0, stream, p);
+    if (p.d.map_rank) {
+      const u64 n_pairs = (u64)p.ws.max_tiles * p.d.n_ranks;
+      hipLaunchKernelGGL(mat_prep_patch_kernel, dim3((u32)((n_pairs + 255) / 256)), dim3(256), 0, stream, p);
+    }
     prof_end(FDY_PROF_MAT_PREP_TILES, stream);
     FDY_HIP_TRY(hipGetLastError());
     prof_begin(FDY_PROF_MAT_MAIN, stream);
