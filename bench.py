@@ -158,6 +158,9 @@ def main():
     ap.add_argument("--workload", type=int, default=4, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--cpu-sample-words", type=int, default=1 << 26)
     ap.add_argument("--no-others", action="store_true", help="skip the secondary configurations")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, "
+                         "used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (the hot path shards without "
@@ -171,6 +174,12 @@ def main():
     import paper_2604_06664_amd as fdy
 
     fdy.lib()
+    if args.calibrate_copy:
+        a = torch.zeros(1 << 27, dtype=torch.int64, device="cuda:0")
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     main_res, cpu = run_workload(args.workload, args.steps, args.warmup, prof=True,
                                  cpu_sample_words=args.cpu_sample_words)
     k = main_res["kernels"]

@@ -31,7 +31,23 @@ def build_lib(verbose=False):
     return LIB
 
 
+TOY_SRC = os.path.join(ROOT, "tests", "toy_graph", "toy_graph.hip")
+TOY_LIB = os.path.join(ROOT, "tests", "toy_graph", "libtoy_graph.so")
+
+
+def build_toy(verbose=False):
+    """The toy hipGraph end-to-end check (a test program; links against libfdy.so)."""
+    cmd = [hipcc()] + FLAGS + ["-I", os.path.join(ROOT, "include"), TOY_SRC, "-L", PKG, "-lfdy",
+                               "-Wl,-rpath,$ORIGIN/../../paper_2604_06664_amd", "-o", TOY_LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return TOY_LIB
+
+
 if __name__ == "__main__":
     build_lib(verbose=True)
     print("built", LIB)
+    build_toy(verbose=True)
+    print("built", TOY_LIB)
     sys.exit(0)
