@@ -12,7 +12,7 @@
 // Work decomposition.  A persistent workgroup of 8 waves stages the top level of the table
 // hierarchy in LDS once.  Work is handed out by an atomic ticket, but not per sub-tile
 // (same-address atomics complete at under 1e8/s on this chip, which alone would cap a
-// 1 GiB scan near 1.3 TB/s): a workgroup draws a chunk of 32 sub-tiles (512 words each)
+// 1 GiB scan near 1.3 TB/s): a workgroup draws a chunk of 24 sub-tiles (512 words each)
 // per ticket and deals them to its waves in rows, sub-tile = base + row*8 + wave.  Per row a
 // wave
 //   1. loads 8 words per lane with 16-byte coalesced loads (the next row's loads are already
@@ -35,7 +35,10 @@
 // value packed in one 64-bit word, agent-scope relaxed atomics), walked by one wave per
 // workgroup: a few hundred chunks are in flight at any time, so the walk is a handful of
 // 64-wide steps (a look-back over per-sub-tile states would walk thousands of entries).
-// The waves then write their relocation entries from registers in ascending word order.
+// The look-back runs one round late: a chunk's results wait in registers while the next
+// chunk is searched, and by then the chunks before it have published their totals, so no
+// workgroup stalls on another one.  The waves then write their relocation entries from
+// registers in ascending word order.
 // The input is read exactly once and the relocation table written exactly once.
 //
 // A sub-tile with more than 192 candidates (over a third of its words inside the table's
@@ -57,7 +60,7 @@ constexpr int kBlock = kWaves * 64;
 constexpr int kLoads = 4;                      // 16-byte loads per lane per sub-tile
 constexpr int kWpl = 2 * kLoads;               // words per lane per sub-tile
 constexpr int kSub = 64 * kWpl;                // words per sub-tile (512)
-constexpr int kRound = 4;                      // sub-tiles per wave per ticket round
+constexpr int kRound = 3;                      // sub-tiles per wave per ticket round
 constexpr int kChunk = kWaves * kRound;        // sub-tiles a workgroup draws per ticket
 static_assert(kSub <= 65536 && kChunk <= 64, "one wave-wide load reads a chunk's sub-tile states");
 constexpr int kQcap = 192;                     // queue entries per wave
@@ -267,7 +270,10 @@ __device__ __forceinline__ void load_words(const ScanParams& p, u32 sub, u64 spa
   } else if (wbase + kSub <= p.n_words) {
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
-      const u64x2 v = *reinterpret_cast<const u64x2*>(p.words + wbase + (k * 64 + lane) * 2);
+      // streamed once: non-temporal, so that the table levels keep their place in L2
+      typedef u64 v2u64 __attribute__((ext_vector_type(2)));
+      const v2u64 v =
+          __builtin_nontemporal_load(reinterpret_cast<const v2u64*>(p.words + wbase + (k * 64 + lane) * 2));
       w[2 * k] = v.x;
       w[2 * k + 1] = v.y;
     }
@@ -372,34 +378,80 @@ __device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, 
   }
 }
 
+// Results of one round (kRound rows of one wave), register-resident: per row up to kRegRounds
+// rounds of 64 candidates.
+struct RoundResults {
+  u32 reg[kRound][kRegRounds];  // region, kMiss for "no hit"
+  u32 idx[kRound][kRegRounds];  // word index inside the sub-tile
+  u64 off[kRound][kRegRounds];  // offset inside the region
+  u32 Q[kRound];                // candidates of the row (dense path if above the register limit)
+  u32 H[kRound];                // hits of the row
+  u64 cnt_incl;                 // lane l: hits of the chunk's sub-tiles 0..l
+  u32 base;                     // first sub-tile of the chunk
+};
+
+// Ordered write of one round's hits, given the chunk's exclusive prefix.
+__device__ __forceinline__ void write_round(const ScanParams& p, const RoundResults& r, u64 chunk_excl,
+                                            const u32* top, u64 span_lo, u64 span_len, u32 key_shift,
+                                            u64* qw, unsigned short* qi) {
+  const u32 wave = threadIdx.x >> 6;
+  const u64 lt = lanemask_lt();
+#pragma unroll
+  for (int j = 0; j < kRound; ++j) {
+    const u32 sub = r.base + j * kWaves + wave;
+    if (sub < p.n_sub) {
+      const u64 wbase = (u64)sub * kSub;
+      const u64 excl = chunk_excl + __shfl(r.cnt_incl, j * kWaves + wave) - r.H[j];
+      if (r.Q[j] <= (u32)(kRegRounds * 64)) {
+        u64 pos = excl;
+#pragma unroll
+        for (int k = 0; k < kRegRounds; ++k) {
+          const bool hit = r.reg[j][k] != kMiss;
+          const u64 bl = ballot(hit);
+          if (hit) store_reloc(p, pos + __popcll(bl & lt), (u32)(wbase + r.idx[j][k]), r.reg[j][k], r.off[j][k]);
+          pos += __popcll(bl);
+        }
+      } else {
+        SubTile d;
+        load_words(p, sub, span_lo, d.w);
+        filter_words(d, span_lo, span_len);
+        dense_pass(p, d, top, span_lo, key_shift, qw, qi, wbase, true, excl);
+      }
+    }
+  }
+}
+
 __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  __shared__ u32 s_next[2];           // next chunk's first sub-tile, per round parity
-  __shared__ u32 s_cnt[2][kChunk];    // hit counts of the chunk's sub-tiles
-  __shared__ u64 s_excl[2];           // chunk's exclusive prefix, from the closer wave
-  __shared__ u32 s_ready[2];          // round tag: s_excl[parity] is valid for round tag-1
+  __shared__ u32 s_next[2];         // next chunk's first sub-tile, per round parity
+  __shared__ u32 s_cnt[2][kChunk];  // hit counts of the chunk's sub-tiles
+  __shared__ u64 s_excl[2];         // previous chunk's exclusive prefix, from the closer wave
   u32* top = reinterpret_cast<u32*>(smem_raw);  // [top_n]
   unsigned char* qbase = smem_raw + (size_t)p.top_n * 4;
   const u32 tid = threadIdx.x;
   const u32 lane = tid & 63;
   const u32 wave = tid >> 6;
-  u64* qw = reinterpret_cast<u64*>(qbase) + wave * kQcap;                              // value
+  u64* qw = reinterpret_cast<u64*>(qbase) + wave * kQcap;  // candidate values
   unsigned short* qi =
       reinterpret_cast<unsigned short*>(qbase + (size_t)kWaves * kQcap * 8) + wave * kQcap;  // local word
-  const u64 lt = lanemask_lt();
   const bool closer = wave == kWaves - 1;  // one wave per workgroup speaks for the chunk
 
   for (u32 i = tid; i < p.top_n; i += kBlock) top[i] = p.top[i];
-  if (tid == 0) {
-    s_ready[0] = 0;
-    s_ready[1] = 0;
-    s_next[1] = atomicAdd(p.ticket, (u32)kChunk);  // round 0 reads parity (0 - 1) & 1
-  }
+  if (tid == 0) s_next[1] = atomicAdd(p.ticket, (u32)kChunk);  // round 0 reads parity (0 - 1) & 1
   __syncthreads();
 
   const u64 span_lo = p.table[0].base;
   const u64 span_len = p.table[p.n_alloc - 1].base + p.table[p.n_alloc - 1].size - span_lo;
   const u32 key_shift = key_shift_for(span_len);
+
+  // The output position of a chunk is looked up one round late: while this round's rows are
+  // searched, the previous round's results wait in registers; by the time its prefix is
+  // needed the chunks before it have long published their totals, so the look-back does not
+  // stall on other workgroups.
+  RoundResults prev, cur;
+  bool have_prev = false;
+  prev.base = 0;
+  prev.cnt_incl = 0;
 
   SubTile t;
   u32 base = s_next[1];
@@ -409,22 +461,16 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
     const u32 b = round & 1;
     u32 next = 0;
     if (tid == 0) next = atomicAdd(p.ticket, (u32)kChunk);  // published at this round's barrier
+    cur.base = base;
 
-    // Results of the rows, register-resident: per row up to kRegRounds rounds of 64 candidates.
-    u32 r_reg[kRound][kRegRounds];
-    u32 r_idx[kRound][kRegRounds];
-    u64 r_off[kRound][kRegRounds];
-    u32 r_Q[kRound];
-    u32 r_H[kRound];
-
-    // ---- phase 1: search and count every row of the chunk
+    // ---- search and count every row of this chunk
 #pragma unroll
     for (int j = 0; j < kRound; ++j) {
       const u32 sub = base + j * kWaves + wave;
-      r_Q[j] = 0;
-      r_H[j] = 0;
+      cur.Q[j] = 0;
+      cur.H[j] = 0;
 #pragma unroll
-      for (int r = 0; r < kRegRounds; ++r) r_reg[j][r] = kMiss;
+      for (int r = 0; r < kRegRounds; ++r) cur.reg[j][r] = kMiss;
       if (sub < p.n_sub) {
         filter_words(t, span_lo, span_len);
         u64 nw[kWpl];
@@ -434,7 +480,8 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
         if (t.Q <= (u32)(kRegRounds * 64)) {
           enqueue(t, 0, t.Q, qw, qi);
           // all rounds of the row in flight together (up to three chains per lane)
-#define FDY_RUN(N, R0) run_rounds<N, R0>(p, top, span_lo, key_shift, qw, qi, t.Q, r_reg[j], r_off[j], r_idx[j], H)
+#define FDY_RUN(N, R0) \
+  run_rounds<N, R0>(p, top, span_lo, key_shift, qw, qi, t.Q, cur.reg[j], cur.off[j], cur.idx[j], H)
           const u32 nr = (t.Q + 63) >> 6;
           if (nr == 1) FDY_RUN(1, 0);
           else if (nr == 2) FDY_RUN(2, 0);
@@ -443,71 +490,67 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
         } else {
           H = dense_pass(p, t, top, span_lo, key_shift, qw, qi, (u64)sub * kSub, false, 0);
         }
-        r_Q[j] = t.Q;
-        r_H[j] = (u32)H;
+        cur.Q[j] = t.Q;
+        cur.H[j] = (u32)H;
         if (more) {
 #pragma unroll
           for (int k = 0; k < kWpl; ++k) t.w[k] = nw[k];
         }
       }
-      if (lane == 0) s_cnt[b][j * kWaves + wave] = r_H[j];
+      if (lane == 0) s_cnt[b][j * kWaves + wave] = cur.H[j];
+    }
+
+    // ---- the previous chunk's exclusive prefix (closer wave), then the round's one barrier
+    if (closer && have_prev) {
+      const u32 pchunk = prev.base / kChunk;
+      const u64 total = __shfl(prev.cnt_incl, 63);
+      const u64 excl = (p.debug & 1) ? 0 : chunk_exclusive_prefix(p.cstate, pchunk, p.spin_limit, p.d_status);
+      if (lane == 0) {
+        if (pchunk != 0) st_state(&p.cstate[pchunk], kFlagInc | ((excl + total) & kValMask));
+        if (prev.base + kChunk >= p.n_sub) {  // the last chunk: the grand total
+          *p.d_count = excl + total;
+          if (excl + total > p.capacity) raise_status(p.d_status, FDY_ST_CAPACITY);
+        }
+        s_excl[b] = excl;
+      }
     }
     if (tid == 0) s_next[b] = next;
-    __syncthreads();  // the one barrier per round: counts and the next ticket are visible
+    __syncthreads();  // counts, next ticket and the previous chunk's prefix are visible
 
-    // next round's first row: issue its loads before waiting for the prefix
+    // next round's first row: loads in flight while the previous round is written out
     const u32 nbase = s_next[b];
     if (nbase + wave < p.n_sub) load_words(p, nbase + wave, span_lo, t.w);
 
-    // ---- phase 2: output positions, ordered writes
-    const u32 chunk = base / kChunk;
     const u64 cnt = lane < (u32)kChunk ? s_cnt[b][lane] : 0;
-    const u64 cnt_incl = wave_incl_scan_u64(cnt);  // lane l: hits of sub-tiles base..base+l
-    u64 chunk_excl = 0;
-    if (closer) {
-      const u64 total = __shfl(cnt_incl, 63);
-      if (lane == 0) st_state(&p.cstate[chunk], (chunk == 0 ? kFlagInc : kFlagAgg) | total);
-      chunk_excl = (p.debug & 1) ? 0 : chunk_exclusive_prefix(p.cstate, chunk, p.spin_limit, p.d_status);
-      if (lane == 0) {
-        if (chunk != 0) st_state(&p.cstate[chunk], kFlagInc | ((chunk_excl + total) & kValMask));
-        if (base + kChunk >= p.n_sub) {  // the last chunk
-          *p.d_count = chunk_excl + total;
-          if (chunk_excl + total > p.capacity) raise_status(p.d_status, FDY_ST_CAPACITY);
-        }
-        s_excl[b] = chunk_excl;
-        __hip_atomic_store(&s_ready[b], round + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-      }
-    } else {
-      u32 spins = 0;
-      while (__hip_atomic_load(&s_ready[b], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) != round + 1)
-        if (!spin_once(spins, p.spin_limit, p.d_status)) break;
-      chunk_excl = s_excl[b];
+    cur.cnt_incl = wave_incl_scan_u64(cnt);  // lane l: hits of sub-tiles base..base+l
+    {
+      const u32 chunk = base / kChunk;
+      const u64 total = __shfl(cur.cnt_incl, 63);  // all lanes take part in the shuffle
+      if (closer && lane == 0) st_state(&p.cstate[chunk], (chunk == 0 ? kFlagInc : kFlagAgg) | total);
     }
-#pragma unroll
-    for (int j = 0; j < kRound; ++j) {
-      const u32 sub = base + j * kWaves + wave;
-      if (sub < p.n_sub) {
-        const u64 wbase = (u64)sub * kSub;
-        const u32 in_chunk = j * kWaves + wave;
-        const u64 excl = chunk_excl + __shfl(cnt_incl, in_chunk) - r_H[j];
-        if (r_Q[j] <= (u32)(kRegRounds * 64)) {
-          u64 pos = excl;
-#pragma unroll
-          for (int r = 0; r < kRegRounds; ++r) {
-            const bool hit = r_reg[j][r] != kMiss;
-            const u64 bl = ballot(hit);
-            if (hit) store_reloc(p, pos + __popcll(bl & lt), (u32)(wbase + r_idx[j][r]), r_reg[j][r], r_off[j][r]);
-            pos += __popcll(bl);
-          }
-        } else {
-          SubTile d;
-          load_words(p, sub, span_lo, d.w);
-          filter_words(d, span_lo, span_len);
-          dense_pass(p, d, top, span_lo, key_shift, qw, qi, wbase, true, excl);
-        }
-      }
-    }
+    if (have_prev) write_round(p, prev, s_excl[b], top, span_lo, span_len, key_shift, qw, qi);
+    prev = cur;
+    have_prev = true;
     base = nbase;
+  }
+
+  // ---- drain: the last chunk this workgroup searched
+  if (have_prev) {
+    if (closer) {
+      const u32 pchunk = prev.base / kChunk;
+      const u64 total = __shfl(prev.cnt_incl, 63);
+      const u64 excl = (p.debug & 1) ? 0 : chunk_exclusive_prefix(p.cstate, pchunk, p.spin_limit, p.d_status);
+      if (lane == 0) {
+        if (pchunk != 0) st_state(&p.cstate[pchunk], kFlagInc | ((excl + total) & kValMask));
+        if (prev.base + kChunk >= p.n_sub) {  // the last chunk: the grand total
+          *p.d_count = excl + total;
+          if (excl + total > p.capacity) raise_status(p.d_status, FDY_ST_CAPACITY);
+        }
+        s_excl[0] = excl;
+      }
+    }
+    __syncthreads();
+    write_round(p, prev, s_excl[0], top, span_lo, span_len, key_shift, qw, qi);
   }
 }
 
@@ -692,6 +735,7 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   hipLaunchKernelGGL(scan_kernel, dim3(grid), dim3(kBlock), lds, stream, p);
   prof_end(FDY_PROF_SCAN_MAIN, stream);
   FDY_HIP_TRY(hipGetLastError());
+
   return FDY_OK;
 }
 
