@@ -78,6 +78,8 @@ def lib():
         L.fdy__tune_set.argtypes = [C.c_int, C.c_int]
         L.fdy__prof_enable.restype = C.c_int
         L.fdy__prof_enable.argtypes = [C.c_int]
+        L.fdy__prof_mask.restype = None
+        L.fdy__prof_mask.argtypes = [C.c_uint]
         L.fdy__prof_read.restype = C.c_int
         L.fdy__prof_read.argtypes = [C.c_int, C.POINTER(C.c_int)] + [C.POINTER(C.c_float)] * 3
         L.fdy__prof_name.restype = C.c_char_p
@@ -180,9 +182,14 @@ def tune_set(knob, value):
 PROF_SLOTS = 9
 
 
-def prof_enable(n_records):
-    """Bracket each kernel launch of the library with HIP events on the caller's stream
-    (bench support; 0 switches it off)."""
+PROF_SCAN_MAIN, PROF_MAT_MAIN = 0, 7
+
+
+def prof_enable(n_records, slots=None):
+    """Bracket kernel launches of the library with HIP events on the caller's stream (bench
+    support; 0 switches it off).  `slots`: iterable of slot numbers to record, default all."""
+    mask = 0xFFFFFFFF if slots is None else sum(1 << s for s in slots)
+    lib().fdy__prof_mask(mask)
     return lib().fdy__prof_enable(int(n_records))
 
 

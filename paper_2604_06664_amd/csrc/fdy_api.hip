@@ -10,7 +10,7 @@ int g_tune[FDY_TUNE_COUNT] = {
     /* MAT_VARIANT     */ 0,
     0, 0, 0, 0};
 const int g_tune_lo[FDY_TUNE_COUNT] = {1, 1, 0, 0, 0, 0, 0, 0};
-const int g_tune_hi[FDY_TUNE_COUNT] = {14, 16, 1 << 30, 8, 7, 0, 0, 0};
+const int g_tune_hi[FDY_TUNE_COUNT] = {15, 16, 1 << 30, 8, 63, 0, 0, 0};
 }  // namespace
 
 extern "C" int fdy__tune_get(int knob) {
@@ -67,17 +67,18 @@ struct ProfSlot {
 };
 ProfSlot g_prof[FDY_PROF_SLOTS];
 int g_prof_n = 0;
+unsigned g_prof_mask = ~0u;
 }  // namespace
 
 void fdy::prof_begin(int slot, void* stream) {
-  if (!g_prof_n) return;
+  if (!g_prof_n || !((g_prof_mask >> slot) & 1u)) return;
   ProfSlot& s = g_prof[slot];
   if (s.used >= g_prof_n) return;
   (void)hipEventRecord(s.a[s.used], (hipStream_t)stream);
 }
 
 void fdy::prof_end(int slot, void* stream) {
-  if (!g_prof_n) return;
+  if (!g_prof_n || !((g_prof_mask >> slot) & 1u)) return;
   ProfSlot& s = g_prof[slot];
   if (s.used >= g_prof_n) return;
   (void)hipEventRecord(s.b[s.used], (hipStream_t)stream);
@@ -105,6 +106,8 @@ extern "C" int fdy__prof_enable(int n_records) {
   g_prof_n = n_records;
   return n_records;
 }
+
+extern "C" void fdy__prof_mask(unsigned mask) { g_prof_mask = mask; }
 
 extern "C" int fdy__prof_read(int slot, int* n_records, float* total_ms, float* min_ms, float* max_ms) {
   if (slot < 0 || slot >= FDY_PROF_SLOTS) return -1;

@@ -60,9 +60,10 @@ constexpr int kBlock = kWaves * 64;
 constexpr int kLoads = 4;                      // 16-byte loads per lane per sub-tile
 constexpr int kWpl = 2 * kLoads;               // words per lane per sub-tile
 constexpr int kSub = 64 * kWpl;                // words per sub-tile (512)
-constexpr int kRound = 3;                      // sub-tiles per wave per ticket round
-constexpr int kChunk = kWaves * kRound;        // sub-tiles a workgroup draws per ticket
-static_assert(kSub <= 65536 && kChunk <= 64, "one wave-wide load reads a chunk's sub-tile states");
+constexpr int kRoundBig = 3;                   // rows (sub-tiles per wave) per ticket, large inputs
+constexpr int kRoundSmall = 1;                 // ... small inputs: more, smaller chunks fill the chip
+constexpr u32 kSmallSubTiles = 256 * kWaves * kRoundBig * 2;  // below this many sub-tiles: small
+static_assert(kSub <= 65536 && kWaves * kRoundBig <= 64, "a chunk's counts fit one wave");
 constexpr int kQcap = 192;                     // queue entries per wave
 constexpr int kRegRounds = 3;                  // rounds of 64 candidates a row keeps in registers
 constexpr int kMaxMid = 6;                     // packed levels in global memory
@@ -82,7 +83,8 @@ struct ScanParams {
   u64* cstate;     // [n_chunks] per-chunk totals / inclusive prefixes
   u32 n_sub;       // sub-tiles
   u32 top_n;       // power of two
-  u32 levels;      // k: S = 8^k table entries per level-0 key
+  u32 levels;      // k: 8-ary levels below level 0, the table line included
+  u32 f0_log2;     // level 0 samples every (2^f0_log2 * 8^k)-th base
   u32* d_status;
   u32 spin_limit;
   u32 debug;  // timing experiments only (results are then wrong): 1 skip chunk walk, 4 skip loads
@@ -202,14 +204,26 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
     n[c] = i[c];  // node index at level `levels`: covers table entries [n * 8^levels, ...)
     if (top[i[c]] == kw[c]) {
       // equal keys: the sampled base may still lie above w; settle it on exact bases
-      const u32 sh = 3 * p.levels;
+      const u32 sh = 3 * p.levels + p.f0_log2;
       while (n[c] > 0 && p.table[n[c] << sh].base > w[c]) --n[c];
+    }
+  }
+  if (p.f0_log2) {
+    // a level-0 key spans 2^f0_log2 nodes of the first packed level: 1-2 binary steps there
+    const u64* m = p.mid[p.levels - 1];
+#pragma unroll
+    for (int c = 0; c < N; ++c) n[c] <<= p.f0_log2;
+    for (u32 step = 1u << (p.f0_log2 - 1); step; step >>= 1) {
+#pragma unroll
+      for (int c = 0; c < N; ++c)
+        if (m[n[c] + step] <= w[c]) n[c] += step;
     }
   }
   for (int j = (int)p.levels - 1; j >= 1; --j) {
     const u64* m = p.mid[j - 1];
 #pragma unroll
     for (int c = 0; c < N; ++c) n[c] *= 8;
+    if (p.debug & 8) continue;  // timing experiment: skip this level's probes
 #pragma unroll
     for (u32 step = 4; step; step >>= 1) {
 #pragma unroll
@@ -229,6 +243,7 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
     }
 #pragma unroll
     for (u32 step = 4; step; step >>= 1) {
+      if (p.debug & 16) break;  // timing experiment: skip the probes inside the table line
       u64x2 q[N];
       bool in[N];
 #pragma unroll
@@ -380,6 +395,7 @@ __device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, 
 
 // Results of one round (kRound rows of one wave), register-resident: per row up to kRegRounds
 // rounds of 64 candidates.
+template <int kRound>
 struct RoundResults {
   u32 reg[kRound][kRegRounds];  // region, kMiss for "no hit"
   u32 idx[kRound][kRegRounds];  // word index inside the sub-tile
@@ -391,7 +407,8 @@ struct RoundResults {
 };
 
 // Ordered write of one round's hits, given the chunk's exclusive prefix.
-__device__ __forceinline__ void write_round(const ScanParams& p, const RoundResults& r, u64 chunk_excl,
+template <int kRound>
+__device__ __forceinline__ void write_round(const ScanParams& p, const RoundResults<kRound>& r, u64 chunk_excl,
                                             const u32* top, u64 span_lo, u64 span_len, u32 key_shift,
                                             u64* qw, unsigned short* qi) {
   const u32 wave = threadIdx.x >> 6;
@@ -421,7 +438,9 @@ __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResu
   }
 }
 
+template <int kRound>
 __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
+  constexpr int kChunk = kWaves * kRound;  // sub-tiles a workgroup draws per ticket
   extern __shared__ __align__(16) unsigned char smem_raw[];
   __shared__ u32 s_next[2];         // next chunk's first sub-tile, per round parity
   __shared__ u32 s_cnt[2][kChunk];  // hit counts of the chunk's sub-tiles
@@ -448,7 +467,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   // searched, the previous round's results wait in registers; by the time its prefix is
   // needed the chunks before it have long published their totals, so the look-back does not
   // stall on other workgroups.
-  RoundResults prev, cur;
+  RoundResults<kRound> prev, cur;
   bool have_prev = false;
   prev.base = 0;
   prev.cnt_incl = 0;
@@ -560,6 +579,7 @@ struct ScanInit {
   u32* top;
   u32 top_n;
   u32 levels;
+  u32 f0_log2;
   u64* mid[kMaxMid];
   u32 mid_len[kMaxMid];
   u32 n_sub;
@@ -577,10 +597,10 @@ __global__ void scan_init_kernel(ScanInit a) {
       a.n_alloc ? a.table[a.n_alloc - 1].base + a.table[a.n_alloc - 1].size - span_lo : 1;
   const u32 key_shift = key_shift_for(span_len);
   if (i < a.top_n) {
-    const u64 j = i << (3 * a.levels);
+    const u64 j = i << (3 * a.levels + a.f0_log2);
     a.top[i] = j < a.n_alloc ? (u32)((a.table[j].base - span_lo) >> key_shift) : 0xffffffffu;
   }
-  for (u32 lv = 1; lv < a.levels; ++lv) {
+  for (u32 lv = 1; lv <= a.levels; ++lv) {
     if (i < a.mid_len[lv - 1]) {
       const u64 j = i << (3 * lv);
       a.mid[lv - 1][i] = j < a.n_alloc ? a.table[j].base : ~0ull;
@@ -614,7 +634,7 @@ u32 pow2_ceil(u32 v) {
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct ScanPlan {
-  u32 top_n, levels, n_sub;
+  u32 top_n, levels, f0_log2, n_sub, round;
   u32 mid_len[kMaxMid];
   u32 n_chunks;
   size_t off_top, off_mid[kMaxMid], off_cstate, total;
@@ -622,12 +642,24 @@ struct ScanPlan {
 
 bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
   const u32 top_cap = 1u << fdy__tune_get(FDY_TUNE_SCAN_TOP_LOG2);
-  u32 levels = 0;
-  while ((((u64)n_alloc + (1ull << (3 * levels)) - 1) >> (3 * levels)) > top_cap) ++levels;
+  // smallest sampling stride 2^f0_log2 * 8^levels (levels >= 1 unless the whole table fits)
+  // for which the sampled bases fit the LDS level
+  u32 levels = 0, f0_log2 = 0;
+  auto sampled_at = [&](u32 lv, u32 f) { return (u32)(((u64)n_alloc + (1ull << (3 * lv + f)) - 1) >> (3 * lv + f)); };
+  if (n_alloc > top_cap) {
+    levels = 1;
+    while (sampled_at(levels, f0_log2) > top_cap) {
+      if (++f0_log2 == 3) {
+        f0_log2 = 0;
+        ++levels;
+      }
+    }
+  }
   if (levels > (u32)kMaxMid) return false;
-  const u32 sampled = (u32)(((u64)n_alloc + (1ull << (3 * levels)) - 1) >> (3 * levels));
+  const u32 sampled = sampled_at(levels, f0_log2);
   pl->top_n = pow2_ceil(sampled < 2 ? 2 : sampled);
   pl->levels = levels;
+  pl->f0_log2 = f0_log2;
   pl->n_sub = (u32)((n_words + kSub - 1) / kSub);
   size_t off = 256;
   pl->off_top = off;
@@ -636,14 +668,21 @@ bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
     pl->mid_len[j] = 0;
     pl->off_mid[j] = off;
   }
-  for (u32 lv = 1; lv < levels; ++lv) {
-    // level lv holds every 8^lv-th base; its parent has ceil(A / 8^(lv+1)) nodes of 8 keys
-    const u64 parents = ((u64)n_alloc + (1ull << (3 * (lv + 1))) - 1) >> (3 * (lv + 1));
-    pl->mid_len[lv - 1] = (u32)(parents * 8);
+  // packed level lv holds every 8^lv-th base.  Below the top it is read in nodes of 8 keys
+  // (one per parent); the level right under level 0 exists only when a level-0 key spans
+  // several of its entries (f0_log2 > 0) and is read in runs of 2^f0_log2 keys.
+  const u32 top_lv = f0_log2 ? levels : (levels ? levels - 1 : 0);
+  for (u32 lv = 1; lv <= top_lv; ++lv) {
+    u64 len;
+    if (lv == levels) len = (u64)sampled << f0_log2;
+    else len = (((u64)n_alloc + (1ull << (3 * (lv + 1))) - 1) >> (3 * (lv + 1))) * 8;
+    pl->mid_len[lv - 1] = (u32)len;
     pl->off_mid[lv - 1] = off;
-    off += align256((size_t)pl->mid_len[lv - 1] * 8);
+    off += align256((size_t)len * 8);
   }
-  pl->n_chunks = (pl->n_sub + kChunk - 1) / kChunk;
+  pl->round = pl->n_sub < kSmallSubTiles ? kRoundSmall : kRoundBig;
+  const u32 chunk = kWaves * pl->round;
+  pl->n_chunks = (pl->n_sub + chunk - 1) / chunk;
   pl->off_cstate = off;
   off += align256((size_t)pl->n_chunks * 8);
   pl->total = off;
@@ -684,6 +723,7 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   a.top = (u32*)(ws + pl.off_top);
   a.top_n = pl.top_n;
   a.levels = pl.levels;
+  a.f0_log2 = pl.f0_log2;
   for (int j = 0; j < kMaxMid; ++j) {
     a.mid[j] = (u64*)(ws + pl.off_mid[j]);
     a.mid_len[j] = pl.mid_len[j];
@@ -717,6 +757,7 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   p.n_sub = pl.n_sub;
   p.top_n = pl.top_n;
   p.levels = pl.levels;
+  p.f0_log2 = pl.f0_log2;
   p.d_status = d_status;
   p.spin_limit = (u32)fdy__tune_get(FDY_TUNE_SCAN_SPIN_LIMIT);
   p.debug = (u32)fdy__tune_get(FDY_TUNE_SCAN_DEBUG);
@@ -725,17 +766,15 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   int dev = 0, n_cu = 256;
   FDY_HIP_TRY(hipGetDevice(&dev));
   FDY_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-  FDY_HIP_TRY(hipFuncSetAttribute((const void*)scan_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)lds));
   const u32 per_cu = (u32)fdy__tune_get(FDY_TUNE_SCAN_WG_PER_CU);
   u32 grid = (u32)n_cu * per_cu;
-  const u32 useful = pl.n_chunks;
-  if (grid > useful) grid = useful;
+  if (grid > pl.n_chunks) grid = pl.n_chunks;
+  auto kern = pl.round == kRoundSmall ? scan_kernel<kRoundSmall> : scan_kernel<kRoundBig>;
+  FDY_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   prof_begin(FDY_PROF_SCAN_MAIN, stream);
-  hipLaunchKernelGGL(scan_kernel, dim3(grid), dim3(kBlock), lds, stream, p);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), lds, stream, p);
   prof_end(FDY_PROF_SCAN_MAIN, stream);
   FDY_HIP_TRY(hipGetLastError());
-
   return FDY_OK;
 }
 

@@ -39,6 +39,7 @@ enum {
   FDY_PROF_SLOTS = 9
 };
 int fdy__prof_enable(int n_records);
+void fdy__prof_mask(unsigned slot_mask); /* which slots record; default all */
 int fdy__prof_read(int slot, int* n_records, float* total_ms, float* min_ms, float* max_ms);
 const char* fdy__prof_name(int slot);
 
