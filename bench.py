@@ -20,6 +20,17 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 
+# Memory-side traffic per launch in bytes, (workload, kernel) -> read + write, from rocprofv3
+# FETCH_SIZE and WRITE_SIZE (two separate counter runs of this script), each scaled by the
+# reading of a plain 1 GiB device copy in the same run (fetch x2.000, write x1.000).  A
+# counter run cannot happen inside this process; the figures are those of the committed
+# summary profiles/whole_path_config4_hbm_traffic_pmc.txt and are reported only for the
+# workload and kernels they were collected on.
+PMC_TRAFFIC_BYTES = {
+    (4, "scan_kernel"): 3_385_815_245 + 216_020_890,
+    (4, "mat_main_kernel"): 2_605_006_438 + 1_073_779_098,
+}
+
 
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
@@ -194,7 +205,8 @@ def main():
     k = main_res["kernels"]
     dom = max((n for n in k if "algorithmic_bytes" in k[n]), key=lambda n: k[n]["avg_ms"])
     roofline = dict(bound="hbm", kernel=dom, achieved=k[dom]["achieved_gbs"], peak=HBM_PEAK_GBS,
-                    unit="GB/s", frac=k[dom]["frac_hbm_peak"], traffic=None,
+                    unit="GB/s", frac=k[dom]["frac_hbm_peak"],
+                    traffic=PMC_TRAFFIC_BYTES.get((args.workload, dom)),
                     algorithmic_bytes_per_launch=k[dom]["algorithmic_bytes"],
                     avg_launch_ms=k[dom]["avg_ms"])
     others = {}
