@@ -176,7 +176,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=4, choices=[1, 2, 3, 4, 5])
-    ap.add_argument("--cpu-sample-words", type=int, default=1 << 26)
+    ap.add_argument("--cpu-sample-words", type=int, default=1 << 27)
     ap.add_argument("--no-others", action="store_true", help="skip the secondary configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, "

@@ -7,10 +7,10 @@ int g_tune[FDY_TUNE_COUNT] = {
     /* SCAN_TOP_LOG2   */ 14,
     /* SCAN_WG_PER_CU  */ 2,
     /* SCAN_SPIN_LIMIT */ 1 << 20,
-    /* MAT_VARIANT     */ 0,
+    /* MAT_MAP_GROUP     */ 0,
     0, 0, 0, 0};
 const int g_tune_lo[FDY_TUNE_COUNT] = {1, 1, 0, 0, 0, 0, 0, 0};
-const int g_tune_hi[FDY_TUNE_COUNT] = {15, 16, 1 << 30, 8, 63, 0, 0, 0};
+const int g_tune_hi[FDY_TUNE_COUNT] = {15, 16, 1 << 30, 64, 63, 0, 0, 0};
 }  // namespace
 
 extern "C" int fdy__tune_get(int knob) {

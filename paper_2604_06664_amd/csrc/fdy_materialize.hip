@@ -14,12 +14,13 @@
 //                            the same for each rank's patch list.  Plain per-lane binary
 //                            searches: tens of thousands of them run side by side, and one
 //                            request per halving is what the memory system serves best.
-//   main  (tile x map)       stages the template tile in LDS, scatters c2 rebased pointers
-//                            (new_base[m][region] + offset), c3 32-bit overrides and c4
-//                            64-bit rank patches into LDS in that order, then streams the
-//                            tile out with coalesced stores.  Templates, relocation lists
-//                            and base maps are re-read per map from L2 / Infinity Cache;
-//                            only the output is compulsory HBM traffic.
+//   main  (tile x map group) stages the template tile in LDS and the tile's relocation entries
+//                            in registers once, then per base map of its group scatters c2
+//                            rebased pointers (new_base[m][region] + offset), c3 32-bit
+//                            overrides and c4 64-bit rank patches into LDS in that order and
+//                            streams the tile out with coalesced stores.  Templates,
+//                            relocation lists and base maps are re-read per group from L2 /
+//                            Infinity Cache; only the output is compulsory HBM traffic.
 //   dims  (one thread / node) launch dimensions of the template with grid overrides.
 #include "fdy_device.hpp"
 #include "fdy_tune.h"
@@ -61,6 +62,7 @@ struct MatParams {
   u64* out_words;
   u32* out_dims;
   u32* d_status;
+  u32 map_group;  // consecutive base maps handled by one workgroup of the main kernel
 };
 
 // Exclusive scan of one u64 per thread over a 1024-thread workgroup; returns the exclusive
@@ -221,81 +223,135 @@ __global__ __launch_bounds__(256) void mat_prep_patch_kernel(MatParams p) {
   p.ws.tile_patch[i] = make_uint2(lo, hi);
 }
 
+// Stage the template tile in LDS: 16-byte global loads from the first even word on.
+__device__ __forceinline__ void stage_tile(u64* buf, const u64* src, u64 src_word, u32 n, u32 tid) {
+  const u32 head = (u32)(src_word & 1);  // words before 16-byte alignment (n >= 1 here)
+  const u32 pairs = (n - head) >> 1;
+  if (tid == 0 && head) buf[0] = src[0];
+  for (u32 i = tid; i < pairs; i += kMatBlock) {
+    const u64x2 v = *reinterpret_cast<const u64x2*>(src + head + 2 * i);
+    buf[head + 2 * i] = v.x;
+    buf[head + 2 * i + 1] = v.y;
+  }
+  if (tid == 0 && head + 2 * pairs < n) buf[n - 1] = src[n - 1];
+}
+
+// One workgroup per (tile, group of consecutive base maps).  What does not depend on the map
+// is fetched once per workgroup: the tile entry, the template tile (LDS) and this thread's
+// share of the tile's relocation entries (registers; the slice holds at most kMatTile
+// entries, kMatPre per thread).  Per map only the base-map gathers, the scatter into LDS
+// and the store of the tile repeat.  Relocations and overrides hit the same words for every
+// map, so the LDS copy needs no refresh between maps; rank patches differ per map, so with
+// patches the tile is staged again (from L2) for every map after the first.
+constexpr int kMatPre = kMatTile / kMatBlock;
+constexpr int kMatStore = kMatTile / (2 * kMatBlock);  // 16-byte chunks per thread
+
 __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
   __shared__ __align__(16) u64 buf[kMatTile];
+  typedef u64 v2u64 __attribute__((ext_vector_type(2)));
   const fdy_mat_desc& d = p.d;
-  const u32 j = blockIdx.x, m = blockIdx.y, tid = threadIdx.x;
+  const u32 j = blockIdx.x, tid = threadIdx.x;
+  const u32 m0 = blockIdx.y * p.map_group;
+  const u32 m1 = min(m0 + p.map_group, d.n_maps);
   const MatTile ent = p.ws.tiles[j];
   const u32 n = ent.n_words;
   if (n == 0) return;
-  // c1: stage the template tile in LDS; 16-byte global loads from the first even word on
   const u64* src = d.src_words + ent.src_word;
-  {
-    const u32 head = (u32)(ent.src_word & 1) & (n ? 1u : 0u);  // words before 16-byte alignment
-    const u32 pairs = (n - head) >> 1;
-    if (tid == 0 && head) buf[0] = src[0];
-    for (u32 i = tid; i < pairs; i += kMatBlock) {
-      const u64x2 v = *reinterpret_cast<const u64x2*>(src + head + 2 * i);
-      buf[head + 2 * i] = v.x;
-      buf[head + 2 * i + 1] = v.y;
-    }
-    if (tid == 0 && head + 2 * pairs < n) buf[n - 1] = src[n - 1];
-  }
-  __syncthreads();
-  // c2: rebase
-  const u64* nb = d.new_base + (u64)m * d.n_alloc;
+  stage_tile(buf, src, ent.src_word, n, tid);  // c1
   bool bad = false;
-  for (u32 q = ent.reloc_lo + tid; q < ent.reloc_hi; q += kMatBlock) {
-    const u64x2 raw = *reinterpret_cast<const u64x2*>(&d.relocs[q]);
-    const u32 word = (u32)raw.x, region = (u32)(raw.x >> 32);
-    const u64 k = (u64)word - ent.src_word;
-    if (k < n && region < d.n_alloc) buf[k] = nb[region] + raw.y;
-    else bad = true;
+  u32 rk[kMatPre], rr[kMatPre];
+  u64 ro[kMatPre];
+#pragma unroll
+  for (int i = 0; i < kMatPre; ++i) {
+    const u32 q = ent.reloc_lo + tid + (u32)i * kMatBlock;
+    rk[i] = 0xffffffffu;
+    rr[i] = 0;
+    ro[i] = 0;
+    if (q < ent.reloc_hi) {
+      const u64x2 raw = *reinterpret_cast<const u64x2*>(&d.relocs[q]);
+      const u32 word = (u32)raw.x, region = (u32)(raw.x >> 32);
+      const u64 k = (u64)word - ent.src_word;
+      if (k < n && region < d.n_alloc) {
+        rk[i] = (u32)k;
+        rr[i] = region;
+        ro[i] = raw.y;
+      } else {
+        bad = true;
+      }
+    }
   }
+  const bool has_ovr = ent.ovr_lo < ent.ovr_hi;
+  const bool has_patch = d.map_rank != nullptr;
   __syncthreads();
-  // c3: 32-bit overrides
-  u32* buf32 = reinterpret_cast<u32*>(buf);
-  for (u32 q = ent.ovr_lo + tid; q < ent.ovr_hi; q += kMatBlock) {
-    const fdy_ovr32 o = d.ovr[q];
-    const u64 b = (u64)o.byte_off - (u64)ent.k0 * 8;
-    if ((b >> 3) < n && (b & 3) == 0) buf32[b >> 2] = o.value;
-    else bad = true;
-  }
-  __syncthreads();
-  // c4: rank patches
-  if (d.map_rank) {
-    const u32 rk = d.map_rank[m];
-    if (rk < d.n_ranks) {
-      const uint2 pr = p.ws.tile_patch[(u64)j * d.n_ranks + rk];
-      for (u32 q = pr.x + tid; q < pr.y; q += kMatBlock) {
-        const u64x2 raw = *reinterpret_cast<const u64x2*>(&d.patch[q]);
-        const u64 k = (u64)(u32)raw.x - ent.k0;
-        if (k < n) buf[k] = raw.y;
+  for (u32 m = m0; m < m1; ++m) {
+    if (has_patch && m != m0) {
+      stage_tile(buf, src, ent.src_word, n, tid);
+      __syncthreads();
+    }
+    // c2: rebase
+    const u64* nb = d.new_base + (u64)m * d.n_alloc;
+    u64 base[kMatPre];
+#pragma unroll
+    for (int i = 0; i < kMatPre; ++i) base[i] = rk[i] != 0xffffffffu ? nb[rr[i]] : 0;
+#pragma unroll
+    for (int i = 0; i < kMatPre; ++i)
+      if (rk[i] != 0xffffffffu) buf[rk[i]] = base[i] + ro[i];
+    // c3: 32-bit overrides
+    if (has_ovr) {
+      __syncthreads();
+      u32* buf32 = reinterpret_cast<u32*>(buf);
+      for (u32 q = ent.ovr_lo + tid; q < ent.ovr_hi; q += kMatBlock) {
+        const fdy_ovr32 o = d.ovr[q];
+        const u64 b = (u64)o.byte_off - (u64)ent.k0 * 8;
+        if ((b >> 3) < n && (b & 3) == 0) buf32[b >> 2] = o.value;
         else bad = true;
       }
-    } else {
-      bad = true;
+    }
+    // c4: rank patches
+    if (has_patch) {
+      __syncthreads();
+      const u32 rk_m = d.map_rank[m];
+      if (rk_m < d.n_ranks) {
+        const uint2 pr = p.ws.tile_patch[(u64)j * d.n_ranks + rk_m];
+        for (u32 q = pr.x + tid; q < pr.y; q += kMatBlock) {
+          const u64x2 raw = *reinterpret_cast<const u64x2*>(&d.patch[q]);
+          const u64 k = (u64)(u32)raw.x - ent.k0;
+          if (k < n) buf[k] = raw.y;
+          else bad = true;
+        }
+      } else {
+        bad = true;
+      }
     }
     __syncthreads();
+    // stream the tile out: LDS -> registers, then 16-byte non-temporal stores (the output is
+    // written once and not read again here; keeping it out of L2 leaves the templates, lists
+    // and base maps there).  The barrier sits between the LDS reads and the global stores so
+    // that the next map's scatter can start while the stores drain.
+    const u64 out_at = (u64)m * d.out_words_per_map + ent.out_word;
+    u64* out = p.out_words + out_at;
+    const u32 head = (u32)(out_at & 1);
+    const u32 pairs = (n - head) >> 1;
+    v2u64 v[kMatStore];
+#pragma unroll
+    for (int c = 0; c < kMatStore; ++c) {
+      const u32 i = tid + (u32)c * kMatBlock;
+      if (i < pairs) {
+        v[c].x = buf[head + 2 * i];
+        v[c].y = buf[head + 2 * i + 1];
+      }
+    }
+    const u64 first = buf[0], last = buf[n - 1];
+    if (m + 1 < m1) __syncthreads();
+#pragma unroll
+    for (int c = 0; c < kMatStore; ++c) {
+      const u32 i = tid + (u32)c * kMatBlock;
+      if (i < pairs) __builtin_nontemporal_store(v[c], reinterpret_cast<v2u64*>(out + head + 2 * i));
+    }
+    if (tid == 0 && head) __builtin_nontemporal_store(first, out);
+    if (tid == 0 && head + 2 * pairs < n) __builtin_nontemporal_store(last, out + n - 1);
   }
   if (bad) raise_status(p.d_status, FDY_ST_BAD_INDEX);
-  // stream the tile out: 16-byte non-temporal stores (the output is written once and not
-  // read again here; keeping it out of L2 leaves the templates, lists and base maps there)
-  const u64 out_at = (u64)m * d.out_words_per_map + ent.out_word;
-  u64* out = p.out_words + out_at;
-  {
-    const u32 head = (u32)(out_at & 1) & (n ? 1u : 0u);
-    const u32 pairs = (n - head) >> 1;
-    if (tid == 0 && head) __builtin_nontemporal_store(buf[0], out);
-    for (u32 i = tid; i < pairs; i += kMatBlock) {
-      typedef u64 v2u64 __attribute__((ext_vector_type(2)));
-      v2u64 v;
-      v.x = buf[head + 2 * i];
-      v.y = buf[head + 2 * i + 1];
-      __builtin_nontemporal_store(v, reinterpret_cast<v2u64*>(out + head + 2 * i));
-    }
-    if (tid == 0 && head + 2 * pairs < n) __builtin_nontemporal_store(buf[n - 1], out + n - 1);
-  }
 }
 
 __global__ __launch_bounds__(256) void mat_dims_kernel(MatParams p) {
@@ -403,6 +459,7 @@ extern "C" int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words
   p.out_words = (u64*)d_out_words;
   p.out_dims = d_out_dims;
   p.d_status = d_status;
+  p.map_group = 1;
   hipStream_t stream = (hipStream_t)hip_stream;
   (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
 
@@ -420,7 +477,14 @@ extern "C" int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words
     prof_end(FDY_PROF_MAT_PREP_TILES, stream);
     FDY_HIP_TRY(hipGetLastError());
     prof_begin(FDY_PROF_MAT_MAIN, stream);
-    hipLaunchKernelGGL(mat_main_kernel, dim3(p.ws.max_tiles, d.n_maps), dim3(kMatBlock), 0, stream, p);
+    // Base maps per workgroup.  Measured on MI355X, groups above 2 (4 with rank patches, where
+    // the tile is staged again per map anyway) lose more to the coarser tail of the launch
+    // than they save in repeated loads.
+    u32 mg = (u32)fdy__tune_get(FDY_TUNE_MAT_MAP_GROUP);
+    if (mg == 0) mg = d.map_rank ? 4 : 2;
+    p.map_group = mg < d.n_maps ? mg : d.n_maps;
+    const u32 n_groups = (d.n_maps + p.map_group - 1) / p.map_group;
+    hipLaunchKernelGGL(mat_main_kernel, dim3(p.ws.max_tiles, n_groups), dim3(kMatBlock), 0, stream, p);
     prof_end(FDY_PROF_MAT_MAIN, stream);
     FDY_HIP_TRY(hipGetLastError());
   }
