@@ -80,6 +80,7 @@ struct ScanParams {
   u32* ticket;
   const u32* top;  // [top_n] level-0 keys, padded with 0xffffffff
   const u64* mid[kMaxMid];  // mid[j-1] = every 8^j-th base, padded with ~0
+  const uint4* leaf;        // packed table, 64 bytes per 8 entries (null: not built)
   u64* cstate;     // [n_chunks] per-chunk totals / inclusive prefixes
   u32 n_sub;       // sub-tiles
   u32 top_n;       // power of two
@@ -219,18 +220,48 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
         if (m[n[c] + step] <= w[c]) n[c] += step;
     }
   }
+  // Packed levels: the whole 64-byte node of 8 keys per candidate, fetched with four
+  // independent 16-byte loads (requests to one line merge, so this costs the memory system
+  // about what a single probe does, where three dependent probes cost three round trips and
+  // three requests: the vector L1 is far too small to keep a node between two probes of the
+  // same lane).  The child is the last key not above w: keys are ascending, padded with ~0,
+  // and the first key of the node is known not to exceed w.
+  u64 gb[N];  // exact base of the first entry of the candidate's table line (level 1's key)
+#pragma unroll
+  for (int c = 0; c < N; ++c) gb[c] = 0;
   for (int j = (int)p.levels - 1; j >= 1; --j) {
     const u64* m = p.mid[j - 1];
+    u64x2 k[N][4];
 #pragma unroll
-    for (int c = 0; c < N; ++c) n[c] *= 8;
-    if (p.debug & 8) continue;  // timing experiment: skip this level's probes
+    for (int c = 0; c < N; ++c) {
+      n[c] *= 8;
 #pragma unroll
-    for (u32 step = 4; step; step >>= 1) {
+      for (int h = 0; h < 4; ++h) k[c][h] = *reinterpret_cast<const u64x2*>(&m[n[c] + 2 * h]);
+    }
+    if (p.debug & 8) continue;  // timing experiment: ignore this level's keys
 #pragma unroll
-      for (int c = 0; c < N; ++c)
-        if (m[n[c] + step] <= w[c]) n[c] += step;
+    for (int c = 0; c < N; ++c) {
+      u32 at = 0;
+      gb[c] = k[c][0].x;
+#pragma unroll
+      for (int h = 1; h < 8; ++h) {
+        const u64 key = (h & 1) ? k[c][h >> 1].y : k[c][h >> 1].x;
+        if (key <= w[c]) {
+          at = h;
+          gb[c] = key;
+        }
+      }
+      n[c] += at;
     }
   }
+  // Leaf: 8 consecutive entries of the table.  Large tables are not read directly: a packed
+  // copy holds each line in 64 bytes, {base - first base of the line, size} in 32 bits each,
+  // which halves what the candidate has to pull through the memory fabric (this fetch is what
+  // bounds the scan when the table outgrows L2).  A line whose values do not fit, and the
+  // last, partial line, are marked and read from the table itself; so are all lines of small
+  // tables, which stay in L2 anyway.  Either way the whole line is fetched at once, one
+  // candidate after the other (the loads in flight per lane already cover the latency; more
+  // would only cost registers).
   u64x2 e[N];
   if (p.levels == 0) {
 #pragma unroll
@@ -238,25 +269,55 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
   } else {
 #pragma unroll
     for (int c = 0; c < N; ++c) {
-      n[c] *= 8;
-      e[c] = *reinterpret_cast<const u64x2*>(&p.table[n[c]]);
-    }
+      bool exact = true;
+      if (p.leaf) {
+        const uint4* line = p.leaf + n[c] * 4;
+        uint4 q[4];
 #pragma unroll
-    for (u32 step = 4; step; step >>= 1) {
-      if (p.debug & 16) break;  // timing experiment: skip the probes inside the table line
-      u64x2 q[N];
-      bool in[N];
+        for (int h = 0; h < 4; ++h) q[h] = line[h];
+        if (q[0].x != 0xffffffffu) {
+          exact = false;
+          const u64 x = w[c] - gb[c];
+          u32 d = 0, z = q[0].y, at = 0;
+          if (!(p.debug & 16)) {  // timing experiment: ignore entries 1..7
 #pragma unroll
-      for (int c = 0; c < N; ++c) {
-        in[c] = n[c] + step < p.n_alloc;
-        if (in[c]) q[c] = *reinterpret_cast<const u64x2*>(&p.table[n[c] + step]);
-      }
-#pragma unroll
-      for (int c = 0; c < N; ++c)
-        if (in[c] && q[c].x <= w[c]) {
-          n[c] += step;
-          e[c] = q[c];
+            for (int h = 1; h < 8; ++h) {
+              const u32 dh = (h & 1) ? q[h >> 1].z : q[h >> 1].x;
+              const u32 zh = (h & 1) ? q[h >> 1].w : q[h >> 1].y;
+              if ((u64)dh <= x) {
+                d = dh;
+                z = zh;
+                at = h;
+              }
+            }
+          }
+          e[c].x = gb[c] + d;
+          e[c].y = z;
+          n[c] = n[c] * 8 + at;
         }
+      }
+      if (exact) {
+        n[c] *= 8;
+        u64x2 q[8];
+#pragma unroll
+        for (int h = 0; h < 8; ++h) {
+          q[h].x = ~0ull;
+          q[h].y = 0;
+          if (n[c] + h < p.n_alloc) q[h] = *reinterpret_cast<const u64x2*>(&p.table[n[c] + h]);
+        }
+        e[c] = q[0];
+        u32 at = 0;
+        if (!(p.debug & 16)) {
+#pragma unroll
+          for (int h = 1; h < 8; ++h)
+            if (q[h].x <= w[c]) {
+              e[c] = q[h];
+              at = h;
+            }
+        }
+        n[c] += at;
+      }
+      __builtin_amdgcn_sched_barrier(0);  // keep the next candidate's loads behind this one's
     }
   }
 #pragma unroll
@@ -582,6 +643,8 @@ struct ScanInit {
   u32 f0_log2;
   u64* mid[kMaxMid];
   u32 mid_len[kMaxMid];
+  uint4* leaf;     // packed table lines, or null
+  u32 leaf_lines;  // ceil(n_alloc / 8) when built
   u32 n_sub;
   u64* cstate;
   u32 n_chunks;
@@ -605,6 +668,29 @@ __global__ void scan_init_kernel(ScanInit a) {
       const u64 j = i << (3 * lv);
       a.mid[lv - 1][i] = j < a.n_alloc ? a.table[j].base : ~0ull;
     }
+  }
+  if (i < a.leaf_lines) {
+    // line i of the packed table: {base - base of the line's first entry, size} per entry in
+    // 32 bits each; first word 0xffffffff: "read this line from the table" (a value does not
+    // fit, or the line is the last, partial one)
+    const u64 e0 = i * 8;
+    u32 d[8] = {0, 0, 0, 0, 0, 0, 0, 0}, z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    bool fits = e0 + 8 <= a.n_alloc;
+    if (fits) {
+      const u64 b0 = a.table[e0].base;
+#pragma unroll
+      for (int h = 0; h < 8; ++h) {
+        const u64 dh = a.table[e0 + h].base - b0, zh = a.table[e0 + h].size;
+        fits = fits && (dh >> 32) == 0 && (zh >> 32) == 0;
+        d[h] = (u32)dh;
+        z[h] = (u32)zh;
+      }
+    }
+    // d[0] is 0 for a packed line, so 0xffffffff there is unambiguous
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+      a.leaf[i * 4 + h] = fits ? make_uint4(d[2 * h], z[2 * h], d[2 * h + 1], z[2 * h + 1])
+                               : make_uint4(0xffffffffu, 0, 0xffffffffu, 0);
   }
   if (i < a.n_chunks) a.cstate[i] = 0;
   if (i == 0) {
@@ -636,8 +722,8 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 struct ScanPlan {
   u32 top_n, levels, f0_log2, n_sub, round;
   u32 mid_len[kMaxMid];
-  u32 n_chunks;
-  size_t off_top, off_mid[kMaxMid], off_cstate, total;
+  u32 n_chunks, leaf_lines;
+  size_t off_top, off_mid[kMaxMid], off_leaf, off_cstate, total;
 };
 
 bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
@@ -680,6 +766,11 @@ bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
     pl->off_mid[lv - 1] = off;
     off += align256((size_t)len * 8);
   }
+  // the packed copy of the table pays once the table itself no longer stays in L2; it needs
+  // the exact base of each line's first entry, which packed level 1 supplies
+  pl->leaf_lines = (levels >= 2 && pl->mid_len[0]) ? (n_alloc + 7) / 8 : 0;
+  pl->off_leaf = off;
+  off += align256((size_t)pl->leaf_lines * 64);
   pl->round = pl->n_sub < kSmallSubTiles ? kRoundSmall : kRoundBig;
   const u32 chunk = kWaves * pl->round;
   pl->n_chunks = (pl->n_sub + chunk - 1) / chunk;
@@ -728,6 +819,8 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
     a.mid[j] = (u64*)(ws + pl.off_mid[j]);
     a.mid_len[j] = pl.mid_len[j];
   }
+  a.leaf = pl.leaf_lines ? (uint4*)(ws + pl.off_leaf) : nullptr;
+  a.leaf_lines = pl.leaf_lines;
   a.n_sub = pl.n_sub;
   a.cstate = (u64*)(ws + pl.off_cstate);
   a.n_chunks = pl.n_chunks;
@@ -736,6 +829,7 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   u32 n_init = pl.top_n > pl.n_chunks ? pl.top_n : pl.n_chunks;
   for (int j = 0; j < kMaxMid; ++j)
     if (pl.mid_len[j] > n_init) n_init = pl.mid_len[j];
+  if (pl.leaf_lines > n_init) n_init = pl.leaf_lines;
   prof_begin(FDY_PROF_SCAN_INIT, stream);
   hipLaunchKernelGGL(scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream, a);
   prof_end(FDY_PROF_SCAN_INIT, stream);
@@ -753,6 +847,7 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   p.ticket = a.ticket;
   p.top = a.top;
   for (int j = 0; j < kMaxMid; ++j) p.mid[j] = a.mid[j];
+  p.leaf = a.leaf;
   p.cstate = a.cstate;
   p.n_sub = pl.n_sub;
   p.top_n = pl.top_n;
