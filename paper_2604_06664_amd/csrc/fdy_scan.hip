@@ -3,32 +3,39 @@
 // The scan classifies every 8-byte word of the captured argument blobs against the sorted
 // allocation table (the relaxation of Section 4.1.1's identical-layout requirement: find
 // every embedded pointer kernel-agnostically, because argument buffers are opaque -
-// Section 2.2, Appendix B).  It is one streaming pass over the words; what bounds it is HBM
-// bandwidth for the words plus the rate at which the memory system serves divergent lookups
-// into the table (measured on MI355X: ~2.5e11 per-lane loads/s when the target stays in L2,
-// ~8e10/s when it comes from the Infinity Cache), so table traffic per candidate is kept to
-// one 64-byte node per packed level plus one 128-byte line of the table.
+// Section 2.2, Appendix B).  It is one streaming pass over the words.  What bounds it, in
+// this order, as measured on MI355X: (1) the dependent round trips of a search (LDS, then L2,
+// then the memory side), which a wave pays once per batch of candidates and which only other
+// waves and other batches can hide; (2) what the candidates pull through the memory fabric
+// once the table outgrows the 4 MiB L2 of an XCD (a 128-byte table line per candidate is
+// 2.5x the bytes of the words themselves at 15 % candidates); (3) HBM bandwidth for the words.
+// Hence: candidates of several sub-tiles are searched together in dense rounds, every level
+// of the hierarchy is fetched as one whole node, and large tables are read through a packed
+// copy of half the size.
 //
 // Work decomposition.  A persistent workgroup of 8 waves stages the top level of the table
 // hierarchy in LDS once.  Work is handed out by an atomic ticket, but not per sub-tile
 // (same-address atomics complete at under 1e8/s on this chip, which alone would cap a
-// 1 GiB scan near 1.3 TB/s): a workgroup draws a chunk of 24 sub-tiles (512 words each)
-// per ticket and deals them to its waves in rows, sub-tile = base + row*8 + wave.  Per row a
-// wave
-//   1. loads 8 words per lane with 16-byte coalesced loads (the next row's loads are already
-//      in flight) and rejects every word outside the table's span with one
-//      subtract-and-compare;
-//   2. compacts the surviving candidates, in word order, into its private LDS queue (wave
-//      ballot + popcount ranks), so that the interval search runs on dense lanes only;
-//   3. searches the hierarchy, up to three candidates per lane interleaved so that their
-//      dependent steps overlap:
+// 1 GiB scan near 1.3 TB/s): a workgroup draws a chunk of 32 sub-tiles (512 words each)
+// per ticket: two groups, in each of which every wave owns two consecutive sub-tiles,
+// sub-tile = base + (group*8 + wave)*2 + row.  Tickets are drawn two rounds ahead, so the
+// words of the next group (of this chunk or the next) are already in flight while a group is
+// searched.  Per group a wave
+//   1. takes its 2 x 8 words per lane (16-byte coalesced non-temporal loads) and rejects
+//      every word outside the table's span with one subtract-and-compare;
+//   2. compacts the surviving candidates of both sub-tiles, in word order, into its private
+//      LDS queue (wave ballot + popcount ranks), so that the interval search runs on dense
+//      rounds of 64 lanes and its round trips are paid once per group, not per sub-tile;
+//   3. searches the hierarchy, up to three rounds (three candidates per lane) interleaved so
+//      that their dependent steps overlap:
 //        level 0  sampled bases (every S-th, S = 8^k) as 31-bit keys (base - span_lo) >> sh
-//                 in LDS, binary search; a key equal to the candidate's is ambiguous and is
+//                 in LDS, 4-ary steps; a key equal to the candidate's is ambiguous and is
 //                 settled against the exact base in the table (rare);
 //        level j  k-1 packed arrays "every 8^j-th base" in global memory, small enough to
-//                 stay in L2: one 64-byte node of 8 keys per level;
-//        leaf     8 consecutive {base,size} entries of the table itself = one 128-byte line;
-//      results (region, offset, local word index) stay in registers;
+//                 stay in L2: one 64-byte node of 8 keys per level, fetched whole;
+//        leaf     8 consecutive {base,size} entries: from the packed copy of the table (64
+//                 bytes per line) when the table is large, else from the table itself;
+//      region and offset of each candidate stay in registers, its word index in LDS;
 //   4. counts its hits into LDS.
 // One workgroup barrier per chunk makes the counts and the next ticket visible.  The output
 // position of the chunk comes from a decoupled look-back over per-CHUNK state words (flag and
@@ -41,13 +48,20 @@
 // registers in ascending word order.
 // The input is read exactly once and the relocation table written exactly once.
 //
-// A sub-tile with more than 192 candidates (over a third of its words inside the table's
-// span - never the case for argument blobs, but legal) is handled in windows of queue size,
-// searched twice (count, then write); slower, same result.
+// A group with more than 384 candidates (over a third of its words inside the table's span
+// - never the case for argument blobs, but legal) is handled sub-tile by sub-tile in windows
+// of queue size, searched twice (count, then write); slower, same result.
 //
 // Tickets are handed out in increasing order and a wave only ever waits for chunks with
 // smaller numbers, which are already owned by resident workgroups; the wait is bounded by a
 // spin limit after which FDY_ST_SPIN is raised and the kernel still terminates.
+//
+// Loops whose bodies hold a whole search are not written as loops: past a size the optimizer
+// declines to unroll even a `#pragma unroll` loop, and a rolled loop indexes the
+// register-resident results dynamically, which sends them to scratch memory.  Groups are
+// therefore instantiated one by one from a generic lambda with a compile-time index.
+#include <type_traits>
+
 #include "fdy_device.hpp"
 #include "fdy_tune.h"
 
@@ -60,12 +74,11 @@ constexpr int kBlock = kWaves * 64;
 constexpr int kLoads = 4;                      // 16-byte loads per lane per sub-tile
 constexpr int kWpl = 2 * kLoads;               // words per lane per sub-tile
 constexpr int kSub = 64 * kWpl;                // words per sub-tile (512)
-constexpr int kRoundBig = 3;                   // rows (sub-tiles per wave) per ticket, large inputs
-constexpr int kRoundSmall = 1;                 // ... small inputs: more, smaller chunks fill the chip
-constexpr u32 kSmallSubTiles = 256 * kWaves * kRoundBig * 2;  // below this many sub-tiles: small
-static_assert(kSub <= 65536 && kWaves * kRoundBig <= 64, "a chunk's counts fit one wave");
+constexpr int kGroupsBig = 2, kGBig = 2;       // large inputs: a wave takes 2 groups of 2 sub-tiles per ticket
+constexpr int kGroupsSmall = 1, kGSmall = 1;   // small inputs: more, smaller chunks fill the chip
+constexpr u32 kSmallSubTiles = 256 * kWaves * kGroupsBig * kGBig * 2;  // below this many sub-tiles: small
 constexpr int kQcap = 192;                     // queue entries per wave
-constexpr int kRegRounds = 3;                  // rounds of 64 candidates a row keeps in registers
+constexpr int kRegRounds = 3;                  // rounds of 64 candidates per sub-tile kept in registers
 constexpr int kMaxMid = 6;                     // packed levels in global memory
 constexpr u32 kMiss = 0xffffffffu;
 
@@ -195,10 +208,28 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
     kw[c] = (u32)((w[c] - span_lo) >> key_shift);
     i[c] = 0;
   }
-  for (u32 step = p.top_n >> 1; step; step >>= 1) {
+  // level 0: 4-ary steps (three independent LDS reads each) halve the number of dependent LDS
+  // round trips of a binary search; one binary step first when log2(top_n) is odd
+  u32 span = p.top_n;
+  if (__popc(span - 1) & 1) {
+    span >>= 1;
 #pragma unroll
     for (int c = 0; c < N; ++c)
-      if (top[i[c] + step] <= kw[c]) i[c] += step;
+      if (top[i[c] + span] <= kw[c]) i[c] += span;
+  }
+#pragma unroll 1
+  for (u32 left = (u32)__popc(span - 1) >> 1; left; --left) {
+    span >>= 2;
+    u32 a[N], b[N], d[N];
+#pragma unroll
+    for (int c = 0; c < N; ++c) {
+      a[c] = top[i[c] + span];
+      b[c] = top[i[c] + 2 * span];
+      d[c] = top[i[c] + 3 * span];
+    }
+#pragma unroll
+    for (int c = 0; c < N; ++c)
+      i[c] += span * ((a[c] <= kw[c] ? 1u : 0u) + (b[c] <= kw[c] ? 1u : 0u) + (d[c] <= kw[c] ? 1u : 0u));
   }
 #pragma unroll
   for (int c = 0; c < N; ++c) {
@@ -296,26 +327,21 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
           n[c] = n[c] * 8 + at;
         }
       }
-      if (exact) {
+      if (exact) {  // three dependent probes inside the table line: few registers, rarely taken
         n[c] *= 8;
-        u64x2 q[8];
-#pragma unroll
-        for (int h = 0; h < 8; ++h) {
-          q[h].x = ~0ull;
-          q[h].y = 0;
-          if (n[c] + h < p.n_alloc) q[h] = *reinterpret_cast<const u64x2*>(&p.table[n[c] + h]);
-        }
-        e[c] = q[0];
-        u32 at = 0;
+        e[c] = *reinterpret_cast<const u64x2*>(&p.table[n[c]]);
         if (!(p.debug & 16)) {
-#pragma unroll
-          for (int h = 1; h < 8; ++h)
-            if (q[h].x <= w[c]) {
-              e[c] = q[h];
-              at = h;
+#pragma unroll 1
+          for (u32 step = 4; step; step >>= 1) {
+            if (n[c] + step < p.n_alloc) {
+              const u64x2 q = *reinterpret_cast<const u64x2*>(&p.table[n[c] + step]);
+              if (q.x <= w[c]) {
+                n[c] += step;
+                e[c] = q;
+              }
             }
+          }
         }
-        n[c] += at;
       }
       __builtin_amdgcn_sched_barrier(0);  // keep the next candidate's loads behind this one's
     }
@@ -328,10 +354,9 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
   }
 }
 
-// One sub-tile's words as a wave holds them: 8 per lane, with the span pre-filter outcome and
-// each candidate's rank in word order (load k, lane, half).
-struct SubTile {
-  u64 w[kWpl];
+// Outcome of the span pre-filter for one sub-tile as a wave holds it (8 words per lane): which
+// words are candidates, and each candidate's rank in word order (load k, lane, half).
+struct Filt {
   bool c[kWpl];
   u32 crank[kWpl];
   u32 Q;
@@ -353,7 +378,7 @@ __device__ __forceinline__ void load_words(const ScanParams& p, u32 sub, u64 spa
       w[2 * k] = v.x;
       w[2 * k + 1] = v.y;
     }
-  } else {
+  } else {  // the ragged tail, and sub-tiles past the end (no word is read, none is a candidate)
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
       const u64 idx = wbase + (k * 64 + lane) * 2;
@@ -363,13 +388,13 @@ __device__ __forceinline__ void load_words(const ScanParams& p, u32 sub, u64 spa
   }
 }
 
-__device__ __forceinline__ void filter_words(SubTile& t, u64 span_lo, u64 span_len) {
+__device__ __forceinline__ void filter_words(const u64 (&w)[kWpl], Filt& t, u64 span_lo, u64 span_len) {
   const u64 lt = lanemask_lt();
   t.Q = 0;
 #pragma unroll
   for (int k = 0; k < kLoads; ++k) {
-    t.c[2 * k] = (t.w[2 * k] - span_lo) < span_len;
-    t.c[2 * k + 1] = (t.w[2 * k + 1] - span_lo) < span_len;
+    t.c[2 * k] = (w[2 * k] - span_lo) < span_len;
+    t.c[2 * k + 1] = (w[2 * k + 1] - span_lo) < span_len;
     const u64 b0 = ballot(t.c[2 * k]), b1 = ballot(t.c[2 * k + 1]);
     const u32 pre = t.Q + __popcll(b0 & lt) + __popcll(b1 & lt);
     t.crank[2 * k] = pre;
@@ -378,15 +403,17 @@ __device__ __forceinline__ void filter_words(SubTile& t, u64 span_lo, u64 span_l
   }
 }
 
-// Candidates with rank in [win, win + wn) go to queue slots [0, wn).
-__device__ __forceinline__ void enqueue(const SubTile& t, u32 win, u32 wn, u64* qw, unsigned short* qi) {
+// Candidates with rank in [win, win + wn) go to queue slots qoff + [0, wn); the index stored
+// with each is its word's distance from word 0 of the sub-tile `row` places before this one.
+__device__ __forceinline__ void enqueue(const u64 (&w)[kWpl], const Filt& t, u32 row, u32 win, u32 wn,
+                                        u32 qoff, u64* qw, unsigned short* qi) {
   const u32 lane = lane_id();
   wave_lds_fence();
 #pragma unroll
   for (int r = 0; r < kWpl; ++r)
     if (t.c[r] && t.crank[r] - win < wn) {  // unsigned: also false below the window
-      qw[t.crank[r] - win] = t.w[r];
-      qi[t.crank[r] - win] = (unsigned short)(((r >> 1) * 64 + lane) * 2 + (r & 1));
+      qw[qoff + t.crank[r] - win] = w[r];
+      qi[qoff + t.crank[r] - win] = (unsigned short)(row * kSub + ((r >> 1) * 64 + lane) * 2 + (r & 1));
     }
   wave_lds_fence();
 }
@@ -401,16 +428,18 @@ __device__ __forceinline__ void store_reloc(const ScanParams& p, u64 at, u32 wor
   }
 }
 
-// Dense sub-tile (more candidates than the register-resident path holds): windows of queue
-// size; counts when `write` is false, writes from position `pos` otherwise.  Returns hits.
-__device__ u64 dense_pass(const ScanParams& p, const SubTile& t, const u32* top, u64 span_lo,
-                          u32 key_shift, u64* qw, unsigned short* qi, u64 wbase, bool write, u64 pos) {
+// Dense sub-tile (its wave's group holds more candidates than the register-resident path
+// keeps): windows of queue size; counts when `write` is false, writes from position `pos`
+// otherwise.  Returns hits.
+__device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt& t, const u32* top,
+                          u64 span_lo, u32 key_shift, u64* qw, unsigned short* qi, u64 wbase, bool write,
+                          u64 pos) {
   const u32 lane = lane_id();
   const u64 lt = lanemask_lt();
   u64 H = 0;
   for (u32 win = 0; win < t.Q; win += kQcap) {
     const u32 wn = t.Q - win < (u32)kQcap ? t.Q - win : (u32)kQcap;
-    enqueue(t, win, wn, qw, qi);
+    enqueue(w, t, 0, win, wn, 0, qw, qi);
     for (u32 q0 = 0; q0 < wn; q0 += 64) {
       const u32 q = q0 + lane;
       const bool valid = q < wn;
@@ -427,13 +456,13 @@ __device__ u64 dense_pass(const ScanParams& p, const SubTile& t, const u32* top,
   return H;
 }
 
-// Searches queue rounds [R0, R0 + N) (64 entries each), N per lane in flight at once; results
-// stay in the caller's registers (region = kMiss for "no hit").
-template <int N, int R0>
+// Searches queue rounds [R0, R0 + N) (64 entries each), N per lane in flight at once; region
+// (kMiss for "no hit") and offset stay in the caller's registers, round k's lane l holding the
+// result of queue slot 64 k + l.
+template <int N, int R0, int kGR>
 __device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, u64 span_lo, u32 key_shift,
-                                           const u64* qw, const unsigned short* qi, u32 Q,
-                                           u32 (&reg)[kRegRounds],
-                                           u64 (&off)[kRegRounds], u32 (&idx)[kRegRounds], u64& H) {
+                                           const u64* qw, u32 Q, u32 (&reg)[kGR], u64 (&off)[kGR], u64& H) {
+  static_assert(R0 + N <= kGR, "rounds");
   const u32 lane = lane_id();
   u64 wv[N];
   Found f[N];
@@ -449,76 +478,107 @@ __device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, 
     const bool hit = valid[r] && f[r].hit;
     reg[R0 + r] = hit ? f[r].region : kMiss;
     off[R0 + r] = f[r].offset;
-    idx[R0 + r] = valid[r] ? qi[(R0 + r) * 64 + lane] : 0;
     H += __popcll(ballot(hit));
   }
 }
 
-// Results of one round (kRound rows of one wave), register-resident: per row up to kRegRounds
-// rounds of 64 candidates.
-template <int kRound>
+// Rounds [R0, R0 + 3) as far as there are candidates, with as many chains per lane as rounds.
+template <int R0, int kGR>
+__device__ __forceinline__ void run_group(const ScanParams& p, const u32* top, u64 span_lo, u32 key_shift,
+                                          const u64* qw, u32 Q, u32 (&reg)[kGR], u64 (&off)[kGR], u64& H) {
+  if constexpr (R0 + 3 <= kGR) {
+    const u32 nr = (Q + 63) >> 6;
+    if (nr >= (u32)R0 + 3) run_rounds<3, R0, kGR>(p, top, span_lo, key_shift, qw, Q, reg, off, H);
+    else if (nr == (u32)R0 + 2) run_rounds<2, R0, kGR>(p, top, span_lo, key_shift, qw, Q, reg, off, H);
+    else if (nr == (u32)R0 + 1) run_rounds<1, R0, kGR>(p, top, span_lo, key_shift, qw, Q, reg, off, H);
+  }
+}
+
+// Results of one wave for one chunk, register-resident but for the candidates' word indices,
+// which stay where the queue put them in LDS (two halves, used by alternate rounds).  The wave's sub-tiles come in kGroups
+// groups of kG consecutive ones; the candidates of a group share one queue and are searched
+// in dense rounds of 64, up to kG * kRegRounds rounds per group.
+template <int kGroups, int kG>
 struct RoundResults {
-  u32 reg[kRound][kRegRounds];  // region, kMiss for "no hit"
-  u32 idx[kRound][kRegRounds];  // word index inside the sub-tile
-  u64 off[kRound][kRegRounds];  // offset inside the region
-  u32 Q[kRound];                // candidates of the row (dense path if above the register limit)
-  u32 H[kRound];                // hits of the row
-  u64 cnt_incl;                 // lane l: hits of the chunk's sub-tiles 0..l
-  u32 base;                     // first sub-tile of the chunk
+  static constexpr int kGR = kG * kRegRounds;
+  u32 reg[kGroups][kGR];  // region, kMiss for "no hit"
+  u64 off[kGroups][kGR];  // offset inside the region
+  u32 b;                  // which half of the wave's index queues belongs to this chunk
+  u32 Q[kGroups];         // candidates of the group (dense path if above the register limit)
+  u32 H[kGroups];         // hits of the group
+  u64 cnt_incl;           // lane l: hits of the chunk's (group, wave) units 0..l
+  u32 base;               // first sub-tile of the chunk
 };
 
-// Ordered write of one round's hits, given the chunk's exclusive prefix.
-template <int kRound>
-__device__ __forceinline__ void write_round(const ScanParams& p, const RoundResults<kRound>& r, u64 chunk_excl,
-                                            const u32* top, u64 span_lo, u64 span_len, u32 key_shift,
-                                            u64* qw, unsigned short* qi) {
+// Ordered write of one chunk's hits of this wave, given the chunk's exclusive prefix.
+template <int kGroups, int kG>
+__device__ __forceinline__ void write_round(const ScanParams& p, const RoundResults<kGroups, kG>& r,
+                                            u64 chunk_excl, const u32* top, u64 span_lo, u64 span_len,
+                                            u32 key_shift, u64* qw, unsigned short* qi_all) {
+  constexpr int kGR = kG * kRegRounds;
   const u32 wave = threadIdx.x >> 6;
   const u64 lt = lanemask_lt();
 #pragma unroll
-  for (int j = 0; j < kRound; ++j) {
-    const u32 sub = r.base + j * kWaves + wave;
-    if (sub < p.n_sub) {
-      const u64 wbase = (u64)sub * kSub;
-      const u64 excl = chunk_excl + __shfl(r.cnt_incl, j * kWaves + wave) - r.H[j];
-      if (r.Q[j] <= (u32)(kRegRounds * 64)) {
-        u64 pos = excl;
+  for (int g = 0; g < kGroups; ++g) {
+    const u32 first_sub = r.base + (g * kWaves + wave) * kG;
+    u64 pos = chunk_excl + __shfl(r.cnt_incl, g * kWaves + wave) - r.H[g];
+    unsigned short* qi = qi_all + (r.b * kGroups + g) * (kG * kQcap);
+    if (r.Q[g] <= (u32)(kGR * 64)) {
+      const u64 wbase = (u64)first_sub * kSub;
 #pragma unroll
-        for (int k = 0; k < kRegRounds; ++k) {
-          const bool hit = r.reg[j][k] != kMiss;
-          const u64 bl = ballot(hit);
-          if (hit) store_reloc(p, pos + __popcll(bl & lt), (u32)(wbase + r.idx[j][k]), r.reg[j][k], r.off[j][k]);
-          pos += __popcll(bl);
-        }
-      } else {
-        SubTile d;
-        load_words(p, sub, span_lo, d.w);
-        filter_words(d, span_lo, span_len);
-        dense_pass(p, d, top, span_lo, key_shift, qw, qi, wbase, true, excl);
+      for (int k = 0; k < kGR; ++k) {
+        const bool hit = r.reg[g][k] != kMiss;
+        const u64 bl = ballot(hit);
+        if (hit)
+          store_reloc(p, pos + __popcll(bl & lt), (u32)(wbase + qi[k * 64 + lane_id()]), r.reg[g][k], r.off[g][k]);
+        pos += __popcll(bl);
+      }
+    } else {
+      for (int j = 0; j < kG; ++j) {
+        const u32 sub = first_sub + j;
+        u64 w[kWpl];
+        Filt t;
+        load_words(p, sub, span_lo, w);
+        filter_words(w, t, span_lo, span_len);
+        pos += dense_pass(p, w, t, top, span_lo, key_shift, qw, qi, (u64)sub * kSub, true, pos);
       }
     }
   }
 }
 
-template <int kRound>
+template <int kGroups, int kG>
 __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
-  constexpr int kChunk = kWaves * kRound;  // sub-tiles a workgroup draws per ticket
+  constexpr int kUnits = kGroups * kWaves;  // (group, wave) units of a chunk, in word order
+  constexpr int kChunk = kUnits * kG;       // sub-tiles a workgroup draws per ticket
+  constexpr int kGR = kG * kRegRounds;
+  constexpr u32 kQwave = kG * kQcap;        // queue entries per wave
+  static_assert(kUnits <= 64 && kG * kSub <= 65536, "a chunk's counts fit one wave; 16-bit queue indices");
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  __shared__ u32 s_next[2];         // next chunk's first sub-tile, per round parity
-  __shared__ u32 s_cnt[2][kChunk];  // hit counts of the chunk's sub-tiles
+  __shared__ u32 s_next[2];         // first sub-tile of the chunk two rounds ahead, per round parity
+  __shared__ u32 s_cnt[2][kUnits];  // hit counts of the chunk's units
   __shared__ u64 s_excl[2];         // previous chunk's exclusive prefix, from the closer wave
   u32* top = reinterpret_cast<u32*>(smem_raw);  // [top_n]
   unsigned char* qbase = smem_raw + (size_t)p.top_n * 4;
   const u32 tid = threadIdx.x;
   const u32 lane = tid & 63;
   const u32 wave = tid >> 6;
-  u64* qw = reinterpret_cast<u64*>(qbase) + wave * kQcap;  // candidate values
-  unsigned short* qi =
-      reinterpret_cast<unsigned short*>(qbase + (size_t)kWaves * kQcap * 8) + wave * kQcap;  // local word
+  u64* qw = reinterpret_cast<u64*>(qbase) + wave * kQwave;  // candidate values
+  unsigned short* qi_all = reinterpret_cast<unsigned short*>(qbase + (size_t)kWaves * kQwave * 8) +
+                           wave * (2 * kGroups * kQwave);  // word indices: [round parity][group][slot]
   const bool closer = wave == kWaves - 1;  // one wave per workgroup speaks for the chunk
 
+  // Chunks are drawn two rounds ahead, so that a round knows where the next one reads and can
+  // have those loads in flight while it searches.  The first two draws are kept apart (the
+  // level-0 staging lies between them): the workgroups that start together then hold
+  // interleaved chunks rather than pairs of neighbours, which keeps chunk order close to the
+  // order in time that the look-back counts on.
+  if (tid == 0) s_next[0] = atomicAdd(p.ticket, (u32)kChunk);
   for (u32 i = tid; i < p.top_n; i += kBlock) top[i] = p.top[i];
-  if (tid == 0) s_next[1] = atomicAdd(p.ticket, (u32)kChunk);  // round 0 reads parity (0 - 1) & 1
   __syncthreads();
+  if (tid == 0) s_next[1] = atomicAdd(p.ticket, (u32)kChunk);
+  u32 base = s_next[0];
+  __syncthreads();
+  u32 nbase = s_next[1];
 
   const u64 span_lo = p.table[0].base;
   const u64 span_len = p.table[p.n_alloc - 1].base + p.table[p.n_alloc - 1].size - span_lo;
@@ -528,57 +588,65 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   // searched, the previous round's results wait in registers; by the time its prefix is
   // needed the chunks before it have long published their totals, so the look-back does not
   // stall on other workgroups.
-  RoundResults<kRound> prev, cur;
+  RoundResults<kGroups, kG> prev, cur;
   bool have_prev = false;
   prev.base = 0;
+  prev.b = 0;
   prev.cnt_incl = 0;
 
-  SubTile t;
-  u32 base = s_next[1];
-  if (base + wave < p.n_sub) load_words(p, base + wave, span_lo, t.w);
+  u64 w[kG][kWpl];  // the group of sub-tiles this wave works on next
+#pragma unroll
+  for (int r = 0; r < kG; ++r) load_words(p, base + wave * kG + r, span_lo, w[r]);
 
   for (u32 round = 0; base < p.n_sub; ++round) {
     const u32 b = round & 1;
     u32 next = 0;
-    if (tid == 0) next = atomicAdd(p.ticket, (u32)kChunk);  // published at this round's barrier
+    if (tid == 0) next = atomicAdd(p.ticket, (u32)kChunk);  // round + 2's chunk, published at this round's barrier
     cur.base = base;
+    cur.b = b;
 
-    // ---- search and count every row of this chunk
+    auto do_group = [&](auto group_c) {
+      constexpr int g = decltype(group_c)::value;
+      const u32 first_sub = base + (g * kWaves + wave) * kG;
+      unsigned short* qi = qi_all + (b * kGroups + g) * kQwave;
+      // ---- the candidates of the group's sub-tiles go to one queue, in word order, so that
+      // the search runs in dense rounds of 64 and pays its round trips once per group
+      u32 Q = 0;
 #pragma unroll
-    for (int j = 0; j < kRound; ++j) {
-      const u32 sub = base + j * kWaves + wave;
-      cur.Q[j] = 0;
-      cur.H[j] = 0;
+      for (int r = 0; r < kG; ++r) {
+        Filt t;
+        filter_words(w[r], t, span_lo, span_len);
+        if (Q + t.Q <= (u32)(kGR * 64)) enqueue(w[r], t, r, 0, t.Q, Q, qw, qi);
+        Q += t.Q;
+      }
+      {  // the next group's words (this chunk's or the next one's), in flight during the search
+        const u32 nsub = g + 1 < kGroups ? first_sub + kWaves * kG : nbase + wave * kG;
 #pragma unroll
-      for (int r = 0; r < kRegRounds; ++r) cur.reg[j][r] = kMiss;
-      if (sub < p.n_sub) {
-        filter_words(t, span_lo, span_len);
-        u64 nw[kWpl];
-        const bool more = j + 1 < kRound && sub + kWaves < p.n_sub;
-        if (more) load_words(p, sub + kWaves, span_lo, nw);  // next row's words, in flight
-        u64 H = 0;
-        if (t.Q <= (u32)(kRegRounds * 64)) {
-          enqueue(t, 0, t.Q, qw, qi);
-          // all rounds of the row in flight together (up to three chains per lane)
-#define FDY_RUN(N, R0) \
-  run_rounds<N, R0>(p, top, span_lo, key_shift, qw, qi, t.Q, cur.reg[j], cur.off[j], cur.idx[j], H)
-          const u32 nr = (t.Q + 63) >> 6;
-          if (nr == 1) FDY_RUN(1, 0);
-          else if (nr == 2) FDY_RUN(2, 0);
-          else if (nr == 3) FDY_RUN(3, 0);
-#undef FDY_RUN
-        } else {
-          H = dense_pass(p, t, top, span_lo, key_shift, qw, qi, (u64)sub * kSub, false, 0);
-        }
-        cur.Q[j] = t.Q;
-        cur.H[j] = (u32)H;
-        if (more) {
+        for (int r = 0; r < kG; ++r) load_words(p, nsub + r, span_lo, w[r]);
+      }
 #pragma unroll
-          for (int k = 0; k < kWpl; ++k) t.w[k] = nw[k];
+      for (int r = 0; r < kGR; ++r) cur.reg[g][r] = kMiss;
+      u64 H = 0;
+      if (Q <= (u32)(kGR * 64)) {
+        run_group<0, kGR>(p, top, span_lo, key_shift, qw, Q, cur.reg[g], cur.off[g], H);
+        run_group<3, kGR>(p, top, span_lo, key_shift, qw, Q, cur.reg[g], cur.off[g], H);
+        run_group<6, kGR>(p, top, span_lo, key_shift, qw, Q, cur.reg[g], cur.off[g], H);
+      } else {
+        for (int r = 0; r < kG; ++r) {
+          u64 dw[kWpl];
+          Filt t;
+          load_words(p, first_sub + r, span_lo, dw);
+          filter_words(dw, t, span_lo, span_len);
+          H += dense_pass(p, dw, t, top, span_lo, key_shift, qw, qi, (u64)(first_sub + r) * kSub, false, 0);
         }
       }
-      if (lane == 0) s_cnt[b][j * kWaves + wave] = cur.H[j];
-    }
+      cur.Q[g] = Q;
+      cur.H[g] = (u32)H;
+      if (lane == 0) s_cnt[b][g * kWaves + wave] = cur.H[g];
+    };
+    do_group(std::integral_constant<int, 0>{});
+    if constexpr (kGroups > 1) do_group(std::integral_constant<int, 1>{});
+    static_assert(kGroups <= 2, "groups are instantiated by hand");
 
     // ---- the previous chunk's exclusive prefix (closer wave), then the round's one barrier
     if (closer && have_prev) {
@@ -597,21 +665,20 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
     if (tid == 0) s_next[b] = next;
     __syncthreads();  // counts, next ticket and the previous chunk's prefix are visible
 
-    // next round's first row: loads in flight while the previous round is written out
-    const u32 nbase = s_next[b];
-    if (nbase + wave < p.n_sub) load_words(p, nbase + wave, span_lo, t.w);
+    const u32 nnbase = s_next[b];  // the chunk of the round after the next
 
-    const u64 cnt = lane < (u32)kChunk ? s_cnt[b][lane] : 0;
-    cur.cnt_incl = wave_incl_scan_u64(cnt);  // lane l: hits of sub-tiles base..base+l
+    const u64 cnt = lane < (u32)kUnits ? s_cnt[b][lane] : 0;
+    cur.cnt_incl = wave_incl_scan_u64(cnt);  // lane l: hits of units 0..l
     {
       const u32 chunk = base / kChunk;
       const u64 total = __shfl(cur.cnt_incl, 63);  // all lanes take part in the shuffle
       if (closer && lane == 0) st_state(&p.cstate[chunk], (chunk == 0 ? kFlagInc : kFlagAgg) | total);
     }
-    if (have_prev) write_round(p, prev, s_excl[b], top, span_lo, span_len, key_shift, qw, qi);
+    if (have_prev) write_round(p, prev, s_excl[b], top, span_lo, span_len, key_shift, qw, qi_all);
     prev = cur;
     have_prev = true;
     base = nbase;
+    nbase = nnbase;
   }
 
   // ---- drain: the last chunk this workgroup searched
@@ -630,7 +697,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       }
     }
     __syncthreads();
-    write_round(p, prev, s_excl[0], top, span_lo, span_len, key_shift, qw, qi);
+    write_round(p, prev, s_excl[0], top, span_lo, span_len, key_shift, qw, qi_all);
   }
 }
 
@@ -720,7 +787,7 @@ u32 pow2_ceil(u32 v) {
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct ScanPlan {
-  u32 top_n, levels, f0_log2, n_sub, round;
+  u32 top_n, levels, f0_log2, n_sub, groups, g;
   u32 mid_len[kMaxMid];
   u32 n_chunks, leaf_lines;
   size_t off_top, off_mid[kMaxMid], off_leaf, off_cstate, total;
@@ -771,8 +838,10 @@ bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
   pl->leaf_lines = (levels >= 2 && pl->mid_len[0]) ? (n_alloc + 7) / 8 : 0;
   pl->off_leaf = off;
   off += align256((size_t)pl->leaf_lines * 64);
-  pl->round = pl->n_sub < kSmallSubTiles ? kRoundSmall : kRoundBig;
-  const u32 chunk = kWaves * pl->round;
+  const bool small = pl->n_sub < kSmallSubTiles;
+  pl->groups = small ? kGroupsSmall : kGroupsBig;
+  pl->g = small ? kGSmall : kGBig;
+  const u32 chunk = kWaves * pl->groups * pl->g;
   pl->n_chunks = (pl->n_sub + chunk - 1) / chunk;
   pl->off_cstate = off;
   off += align256((size_t)pl->n_chunks * 8);
@@ -808,6 +877,12 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   hipStream_t stream = (hipStream_t)hip_stream;
   (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
   unsigned char* ws = (unsigned char*)d_workspace;
+  int dev = 0, n_cu = 256;
+  FDY_HIP_TRY(hipGetDevice(&dev));
+  FDY_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+  const u32 per_cu = (u32)fdy__tune_get(FDY_TUNE_SCAN_WG_PER_CU);
+  u32 grid = (u32)n_cu * per_cu;  // persistent workgroups
+  if (grid > pl.n_chunks) grid = pl.n_chunks;
   ScanInit a;
   a.table = d_table;
   a.n_alloc = n_alloc;
@@ -857,14 +932,8 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   p.spin_limit = (u32)fdy__tune_get(FDY_TUNE_SCAN_SPIN_LIMIT);
   p.debug = (u32)fdy__tune_get(FDY_TUNE_SCAN_DEBUG);
 
-  const size_t lds = (size_t)pl.top_n * 4 + (size_t)kWaves * kQcap * 10;
-  int dev = 0, n_cu = 256;
-  FDY_HIP_TRY(hipGetDevice(&dev));
-  FDY_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-  const u32 per_cu = (u32)fdy__tune_get(FDY_TUNE_SCAN_WG_PER_CU);
-  u32 grid = (u32)n_cu * per_cu;
-  if (grid > pl.n_chunks) grid = pl.n_chunks;
-  auto kern = pl.round == kRoundSmall ? scan_kernel<kRoundSmall> : scan_kernel<kRoundBig>;
+  const size_t lds = (size_t)pl.top_n * 4 + (size_t)kWaves * pl.g * kQcap * (8 + 2 * 2 * pl.groups);
+  auto kern = pl.g == kGSmall ? scan_kernel<kGroupsSmall, kGSmall> : scan_kernel<kGroupsBig, kGBig>;
   FDY_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   prof_begin(FDY_PROF_SCAN_MAIN, stream);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), lds, stream, p);
