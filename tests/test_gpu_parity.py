@@ -123,6 +123,47 @@ def test_scan_truncated_key_ambiguity(hip, oracle):
         fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, old)
 
 
+def test_scan_large_input_dense_groups_and_wide_lines(hip, oracle):
+    """The large-input kernel variant (two groups of two sub-tiles per wave) on an input long
+    enough to select it, with everything that variant handles specially: stretches where every
+    word is a pointer (groups beyond the register-resident limit: windowed two-pass path),
+    moderate and zero density elsewhere, a ragged tail, and a 200,000-entry table read through
+    its packed copy in which some 8-entry lines cannot be packed (an allocation of 5 GiB, a
+    gap of 6 GiB) and the last line is partial."""
+    rng = np.random.default_rng(77)
+    A = 200_003
+    size = rng.integers(16, 1 << 16, A).astype(np.uint64)
+    gap = rng.integers(0, 4096, A).astype(np.uint64) * np.uint64(16)
+    size[::1000] = np.uint64(5 << 30)       # a size that does not fit 32 bits
+    gap[500::1000] = np.uint64(6 << 30)     # a line that spans more than 4 GiB
+    start = np.concatenate([[0], np.cumsum(size + gap)[:-1]]).astype(np.uint64)
+    table = np.zeros(A, L.ALLOC)
+    table["base"], table["size"] = np.uint64(0x7E00_0000_1000) + start, size
+    assert oracle.table_validate(table)[0] == 0
+    W = 16500 * 512 + 777
+    words = rng.integers(0, 1 << 20, W).astype(np.uint64)  # small integers: outside the span
+
+    def plant(lo, hi, density):
+        idx = lo + np.flatnonzero(rng.random(hi - lo) < density)
+        reg = rng.integers(0, A, len(idx))
+        kind = rng.integers(0, 8, len(idx))
+        off = (rng.random(len(idx)) * table["size"][reg]).astype(np.uint64)
+        off = np.where(kind == 0, np.uint64(0), off)                            # first byte
+        off = np.where(kind == 1, table["size"][reg] - np.uint64(1), off)       # last byte
+        off = np.where(kind == 2, table["size"][reg], off)                      # one past: no hit
+        words[idx] = table["base"][reg] + off
+        words[idx[kind == 3]] = table["base"][reg[kind == 3]] - np.uint64(1)    # one below
+
+    plant(0, 2_000_000, 0.30)
+    plant(2_000_000, 2_600_000, 1.0)     # dense: every group overflows the register path
+    plant(2_600_000, 2_600_700, 0.0)
+    plant(3_000_000, 3_001_536, 1.0)     # a dense island of three sub-tiles
+    plant(5_000_000, W, 0.12)
+    plant(W - 777, W, 1.0)               # dense ragged tail
+    got = check_scan(hip, oracle, words, table, tag="large variant")
+    assert len(got) > 1_000_000
+
+
 def test_scan_bounded_wait_is_reported_not_hung(hip):
     """Host-forced error path: with a spin limit of 0 a workgroup that finds its predecessor
     unfinished gives up at once, raises FDY_ST_SPIN and still terminates."""
