@@ -183,8 +183,9 @@ def main():
                          "used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build is single-GPU by design (the hot path shards without "
-              "communication; see DESIGN.md) - run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build is single-GPU by design (every unit of the hot path is "
+              "independent, so ranks would run it without communication) - run with --gpus 1",
+              file=sys.stderr)
         sys.exit(2)
     import torch
 
