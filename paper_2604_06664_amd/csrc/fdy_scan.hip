@@ -29,8 +29,10 @@
 //   3. searches the hierarchy, up to three rounds (three candidates per lane) interleaved so
 //      that their dependent steps overlap:
 //        level 0  sampled bases (every S-th, S = 8^k) as 31-bit keys (base - span_lo) >> sh
-//                 in LDS, 4-ary steps; a key equal to the candidate's is ambiguous and is
-//                 settled against the exact base in the table (rare);
+//                 in LDS, behind a bucket index over the key space (which keys can the
+//                 answer be among), so that a search reads 3-5 keys, not 14; a key equal to
+//                 the candidate's is ambiguous and is settled against the exact base in the
+//                 table (rare);
 //        level j  k-1 packed arrays "every 8^j-th base" in global memory, small enough to
 //                 stay in L2: one 64-byte node of 8 keys per level, fetched whole;
 //        leaf     8 consecutive {base,size} entries: from the packed copy of the table (64
@@ -92,6 +94,8 @@ struct ScanParams {
   u64* d_count;
   u32* ticket;
   const u32* top;  // [top_n] level-0 keys, padded with 0xffffffff
+  const unsigned short* bstart;  // [n_buckets + 1] level-0 keys below each bucket's first key value
+  u32 bucket_log2;  // log2(n_buckets)
   const u64* mid[kMaxMid];  // mid[j-1] = every 8^j-th base, padded with ~0
   const uint4* leaf;        // packed table, 64 bytes per 8 entries (null: not built)
   u64* cstate;     // [n_chunks] per-chunk totals / inclusive prefixes
@@ -189,6 +193,14 @@ __device__ __forceinline__ u32 key_shift_for(u64 span_len) {
   return bits > 31u ? bits - 31u : 0u;
 }
 
+// The level-0 key space is cut into 2^bucket_log2 equal buckets (key >> shift); the shift is the
+// smallest that maps the span's largest key below the bucket count.
+__device__ __forceinline__ u32 bucket_shift_for(u64 span_len, u32 key_shift, u32 bucket_log2) {
+  const u64 max_key = (span_len - 1) >> key_shift;
+  const u32 bits = max_key ? 64u - (u32)__clzll((long long)max_key) : 0u;
+  return bits > bucket_log2 ? bits - bucket_log2 : 0u;
+}
+
 struct Found {
   bool hit;
   u32 region;
@@ -199,8 +211,9 @@ struct Found {
 // The N chains are independent; writing every step for all of them lets their LDS and
 // global round trips overlap, which is what the dependent steps of one chain cannot do.
 template <int N>
-__device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 span_lo, u32 key_shift,
+__device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
                                        const u64 (&w)[N], Found (&f)[N]) {
+  const u32 key_shift = shifts & 0xffu, bucket_shift = shifts >> 8;
   u32 kw[N], i[N];
   u64 n[N];
 #pragma unroll
@@ -208,28 +221,38 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
     kw[c] = (u32)((w[c] - span_lo) >> key_shift);
     i[c] = 0;
   }
-  // level 0: 4-ary steps (three independent LDS reads each) halve the number of dependent LDS
-  // round trips of a binary search; one binary step first when log2(top_n) is odd
-  u32 span = p.top_n;
-  if (__popc(span - 1) & 1) {
-    span >>= 1;
-#pragma unroll
-    for (int c = 0; c < N; ++c)
-      if (top[i[c] + span] <= kw[c]) i[c] += span;
-  }
-#pragma unroll 1
-  for (u32 left = (u32)__popc(span - 1) >> 1; left; --left) {
-    span >>= 2;
-    u32 a[N], b[N], d[N];
+  // level 0: a bucket index first (which keys can the answer be among: two adjacent 16-bit
+  // reads), then a binary search among just those.  With about one key per bucket that is 3-5
+  // LDS reads in 2-4 dependent steps, where a search over all 16,384 keys takes 14 (or 21 in
+  // 7 steps, 4-ary): level 0 was 27 % of the kernel's time, most of it LDS bank conflicts of
+  // 64 lanes reading random keys.  Clustered tables degrade towards the plain binary search.
+  {
+    const unsigned short* bst = reinterpret_cast<const unsigned short*>(top + p.top_n);
+    u32 lo[N], hi[N];
 #pragma unroll
     for (int c = 0; c < N; ++c) {
-      a[c] = top[i[c] + span];
-      b[c] = top[i[c] + 2 * span];
-      d[c] = top[i[c] + 3 * span];
+      const u32 bk = kw[c] >> bucket_shift;
+      lo[c] = bst[bk];
+      hi[c] = bst[bk + 1];
+    }
+    for (;;) {
+      bool open = false;
+#pragma unroll
+      for (int c = 0; c < N; ++c) open = open || lo[c] < hi[c];
+      if (!ballot(open)) break;
+      u32 k[N];
+#pragma unroll
+      for (int c = 0; c < N; ++c) k[c] = lo[c] < hi[c] ? top[(lo[c] + hi[c]) >> 1] : 0u;
+#pragma unroll
+      for (int c = 0; c < N; ++c)
+        if (lo[c] < hi[c]) {
+          const u32 mid = (lo[c] + hi[c]) >> 1;
+          if (k[c] <= kw[c]) lo[c] = mid + 1;
+          else hi[c] = mid;
+        }
     }
 #pragma unroll
-    for (int c = 0; c < N; ++c)
-      i[c] += span * ((a[c] <= kw[c] ? 1u : 0u) + (b[c] <= kw[c] ? 1u : 0u) + (d[c] <= kw[c] ? 1u : 0u));
+    for (int c = 0; c < N; ++c) i[c] = lo[c] - 1;  // keys not above kw, minus one; key 0 is 0
   }
 #pragma unroll
   for (int c = 0; c < N; ++c) {
@@ -432,7 +455,7 @@ __device__ __forceinline__ void store_reloc(const ScanParams& p, u64 at, u32 wor
 // keeps): windows of queue size; counts when `write` is false, writes from position `pos`
 // otherwise.  Returns hits.
 __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt& t, const u32* top,
-                          u64 span_lo, u32 key_shift, u64* qw, unsigned short* qi, u64 wbase, bool write,
+                          u64 span_lo, u32 shifts, u64* qw, unsigned short* qi, u64 wbase, bool write,
                           u64 pos) {
   const u32 lane = lane_id();
   const u64 lt = lanemask_lt();
@@ -445,7 +468,7 @@ __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt&
       const bool valid = q < wn;
       const u64 wv[1] = {valid ? qw[q] : span_lo};
       Found f[1];
-      search<1>(p, top, span_lo, key_shift, wv, f);
+      search<1>(p, top, span_lo, shifts, wv, f);
       const bool hit = valid && f[0].hit;
       const u64 b = ballot(hit);
       if (write && hit)
@@ -460,7 +483,7 @@ __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt&
 // (kMiss for "no hit") and offset stay in the caller's registers, round k's lane l holding the
 // result of queue slot 64 k + l.
 template <int N, int R0, int kGR>
-__device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, u64 span_lo, u32 key_shift,
+__device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
                                            const u64* qw, u32 Q, u32 (&reg)[kGR], u64 (&off)[kGR], u64& H) {
   static_assert(R0 + N <= kGR, "rounds");
   const u32 lane = lane_id();
@@ -472,7 +495,7 @@ __device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, 
     valid[r] = (R0 + r) * 64 + lane < Q;
     wv[r] = valid[r] ? qw[(R0 + r) * 64 + lane] : span_lo;
   }
-  search<N>(p, top, span_lo, key_shift, wv, f);
+  search<N>(p, top, span_lo, shifts, wv, f);
 #pragma unroll
   for (int r = 0; r < N; ++r) {
     const bool hit = valid[r] && f[r].hit;
@@ -484,13 +507,13 @@ __device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, 
 
 // Rounds [R0, R0 + 3) as far as there are candidates, with as many chains per lane as rounds.
 template <int R0, int kGR>
-__device__ __forceinline__ void run_group(const ScanParams& p, const u32* top, u64 span_lo, u32 key_shift,
+__device__ __forceinline__ void run_group(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
                                           const u64* qw, u32 Q, u32 (&reg)[kGR], u64 (&off)[kGR], u64& H) {
   if constexpr (R0 + 3 <= kGR) {
     const u32 nr = (Q + 63) >> 6;
-    if (nr >= (u32)R0 + 3) run_rounds<3, R0, kGR>(p, top, span_lo, key_shift, qw, Q, reg, off, H);
-    else if (nr == (u32)R0 + 2) run_rounds<2, R0, kGR>(p, top, span_lo, key_shift, qw, Q, reg, off, H);
-    else if (nr == (u32)R0 + 1) run_rounds<1, R0, kGR>(p, top, span_lo, key_shift, qw, Q, reg, off, H);
+    if (nr >= (u32)R0 + 3) run_rounds<3, R0, kGR>(p, top, span_lo, shifts, qw, Q, reg, off, H);
+    else if (nr == (u32)R0 + 2) run_rounds<2, R0, kGR>(p, top, span_lo, shifts, qw, Q, reg, off, H);
+    else if (nr == (u32)R0 + 1) run_rounds<1, R0, kGR>(p, top, span_lo, shifts, qw, Q, reg, off, H);
   }
 }
 
@@ -514,7 +537,7 @@ struct RoundResults {
 template <int kGroups, int kG>
 __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResults<kGroups, kG>& r,
                                             u64 chunk_excl, const u32* top, u64 span_lo, u64 span_len,
-                                            u32 key_shift, u64* qw, unsigned short* qi_all) {
+                                            u32 shifts, u64* qw, unsigned short* qi_all) {
   constexpr int kGR = kG * kRegRounds;
   const u32 wave = threadIdx.x >> 6;
   const u64 lt = lanemask_lt();
@@ -540,7 +563,7 @@ __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResu
         Filt t;
         load_words(p, sub, span_lo, w);
         filter_words(w, t, span_lo, span_len);
-        pos += dense_pass(p, w, t, top, span_lo, key_shift, qw, qi, (u64)sub * kSub, true, pos);
+        pos += dense_pass(p, w, t, top, span_lo, shifts, qw, qi, (u64)sub * kSub, true, pos);
       }
     }
   }
@@ -557,8 +580,10 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   __shared__ u32 s_next[2];         // first sub-tile of the chunk two rounds ahead, per round parity
   __shared__ u32 s_cnt[2][kUnits];  // hit counts of the chunk's units
   __shared__ u64 s_excl[2];         // previous chunk's exclusive prefix, from the closer wave
-  u32* top = reinterpret_cast<u32*>(smem_raw);  // [top_n]
-  unsigned char* qbase = smem_raw + (size_t)p.top_n * 4;
+  u32* top = reinterpret_cast<u32*>(smem_raw);  // [top_n], then the bucket index behind it
+  unsigned short* bst = reinterpret_cast<unsigned short*>(top + p.top_n);  // [n_buckets + 1]
+  const u32 n_bst = (1u << p.bucket_log2) + 1;
+  unsigned char* qbase = smem_raw + (size_t)p.top_n * 4 + (((size_t)n_bst * 2 + 15) & ~(size_t)15);
   const u32 tid = threadIdx.x;
   const u32 lane = tid & 63;
   const u32 wave = tid >> 6;
@@ -574,6 +599,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   // order in time that the look-back counts on.
   if (tid == 0) s_next[0] = atomicAdd(p.ticket, (u32)kChunk);
   for (u32 i = tid; i < p.top_n; i += kBlock) top[i] = p.top[i];
+  for (u32 i = tid; i < n_bst; i += kBlock) bst[i] = p.bstart[i];
   __syncthreads();
   if (tid == 0) s_next[1] = atomicAdd(p.ticket, (u32)kChunk);
   u32 base = s_next[0];
@@ -582,7 +608,9 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
 
   const u64 span_lo = p.table[0].base;
   const u64 span_len = p.table[p.n_alloc - 1].base + p.table[p.n_alloc - 1].size - span_lo;
-  const u32 key_shift = key_shift_for(span_len);
+  // level-0 key shift (low byte) and bucket shift, passed along as one value
+  const u32 shifts = key_shift_for(span_len) |
+                     (bucket_shift_for(span_len, key_shift_for(span_len), p.bucket_log2) << 8);
 
   // The output position of a chunk is looked up one round late: while this round's rows are
   // searched, the previous round's results wait in registers; by the time its prefix is
@@ -628,16 +656,16 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       for (int r = 0; r < kGR; ++r) cur.reg[g][r] = kMiss;
       u64 H = 0;
       if (Q <= (u32)(kGR * 64)) {
-        run_group<0, kGR>(p, top, span_lo, key_shift, qw, Q, cur.reg[g], cur.off[g], H);
-        run_group<3, kGR>(p, top, span_lo, key_shift, qw, Q, cur.reg[g], cur.off[g], H);
-        run_group<6, kGR>(p, top, span_lo, key_shift, qw, Q, cur.reg[g], cur.off[g], H);
+        run_group<0, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H);
+        run_group<3, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H);
+        run_group<6, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H);
       } else {
         for (int r = 0; r < kG; ++r) {
           u64 dw[kWpl];
           Filt t;
           load_words(p, first_sub + r, span_lo, dw);
           filter_words(dw, t, span_lo, span_len);
-          H += dense_pass(p, dw, t, top, span_lo, key_shift, qw, qi, (u64)(first_sub + r) * kSub, false, 0);
+          H += dense_pass(p, dw, t, top, span_lo, shifts, qw, qi, (u64)(first_sub + r) * kSub, false, 0);
         }
       }
       cur.Q[g] = Q;
@@ -674,7 +702,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       const u64 total = __shfl(cur.cnt_incl, 63);  // all lanes take part in the shuffle
       if (closer && lane == 0) st_state(&p.cstate[chunk], (chunk == 0 ? kFlagInc : kFlagAgg) | total);
     }
-    if (have_prev) write_round(p, prev, s_excl[b], top, span_lo, span_len, key_shift, qw, qi_all);
+    if (have_prev) write_round(p, prev, s_excl[b], top, span_lo, span_len, shifts, qw, qi_all);
     prev = cur;
     have_prev = true;
     base = nbase;
@@ -697,7 +725,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       }
     }
     __syncthreads();
-    write_round(p, prev, s_excl[0], top, span_lo, span_len, key_shift, qw, qi_all);
+    write_round(p, prev, s_excl[0], top, span_lo, span_len, shifts, qw, qi_all);
   }
 }
 
@@ -706,6 +734,9 @@ struct ScanInit {
   u32 n_alloc;
   u32* top;
   u32 top_n;
+  u32 sampled;  // level-0 keys that are real (the rest is padding)
+  unsigned short* bstart;
+  u32 bucket_log2;
   u32 levels;
   u32 f0_log2;
   u64* mid[kMaxMid];
@@ -729,6 +760,18 @@ __global__ void scan_init_kernel(ScanInit a) {
   if (i < a.top_n) {
     const u64 j = i << (3 * a.levels + a.f0_log2);
     a.top[i] = j < a.n_alloc ? (u32)((a.table[j].base - span_lo) >> key_shift) : 0xffffffffu;
+  }
+  if (i <= (1ull << a.bucket_log2)) {
+    // bucket i starts at key value i << shift: how many level-0 keys lie below it
+    const u64 target = i << bucket_shift_for(span_len, key_shift, a.bucket_log2);
+    const u32 sh = 3 * a.levels + a.f0_log2;
+    u32 lo = 0, hi = a.sampled;
+    while (lo < hi) {
+      const u32 mid = lo + ((hi - lo) >> 1);
+      if (((a.table[(u64)mid << sh].base - span_lo) >> key_shift) < target) lo = mid + 1;
+      else hi = mid;
+    }
+    a.bstart[i] = (unsigned short)lo;
   }
   for (u32 lv = 1; lv <= a.levels; ++lv) {
     if (i < a.mid_len[lv - 1]) {
@@ -789,8 +832,8 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 struct ScanPlan {
   u32 top_n, levels, f0_log2, n_sub, groups, g;
   u32 mid_len[kMaxMid];
-  u32 n_chunks, leaf_lines;
-  size_t off_top, off_mid[kMaxMid], off_leaf, off_cstate, total;
+  u32 n_chunks, leaf_lines, sampled, bucket_log2;
+  size_t off_top, off_bst, off_mid[kMaxMid], off_leaf, off_cstate, total;
 };
 
 bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
@@ -817,6 +860,11 @@ bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
   size_t off = 256;
   pl->off_top = off;
   off += align256((size_t)pl->top_n * 4);
+  pl->sampled = sampled;
+  pl->bucket_log2 = 0;  // one bucket per level-0 key, at most 2^14 (16-bit starts, 32 KiB of LDS)
+  while ((2u << pl->bucket_log2) <= pl->top_n && pl->bucket_log2 < 14) ++pl->bucket_log2;
+  pl->off_bst = off;
+  off += align256((((size_t)1 << pl->bucket_log2) + 1) * 2);
   for (int j = 0; j < kMaxMid; ++j) {
     pl->mid_len[j] = 0;
     pl->off_mid[j] = off;
@@ -888,6 +936,9 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   a.n_alloc = n_alloc;
   a.top = (u32*)(ws + pl.off_top);
   a.top_n = pl.top_n;
+  a.sampled = pl.sampled;
+  a.bstart = (unsigned short*)(ws + pl.off_bst);
+  a.bucket_log2 = pl.bucket_log2;
   a.levels = pl.levels;
   a.f0_log2 = pl.f0_log2;
   for (int j = 0; j < kMaxMid; ++j) {
@@ -905,6 +956,7 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   for (int j = 0; j < kMaxMid; ++j)
     if (pl.mid_len[j] > n_init) n_init = pl.mid_len[j];
   if (pl.leaf_lines > n_init) n_init = pl.leaf_lines;
+  if ((1u << pl.bucket_log2) + 1 > n_init) n_init = (1u << pl.bucket_log2) + 1;
   prof_begin(FDY_PROF_SCAN_INIT, stream);
   hipLaunchKernelGGL(scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream, a);
   prof_end(FDY_PROF_SCAN_INIT, stream);
@@ -921,6 +973,8 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   p.d_count = (u64*)d_count;
   p.ticket = a.ticket;
   p.top = a.top;
+  p.bstart = a.bstart;
+  p.bucket_log2 = a.bucket_log2;
   for (int j = 0; j < kMaxMid; ++j) p.mid[j] = a.mid[j];
   p.leaf = a.leaf;
   p.cstate = a.cstate;
@@ -932,7 +986,8 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   p.spin_limit = (u32)fdy__tune_get(FDY_TUNE_SCAN_SPIN_LIMIT);
   p.debug = (u32)fdy__tune_get(FDY_TUNE_SCAN_DEBUG);
 
-  const size_t lds = (size_t)pl.top_n * 4 + (size_t)kWaves * pl.g * kQcap * (8 + 2 * 2 * pl.groups);
+  const size_t lds = (size_t)pl.top_n * 4 + (((((size_t)1 << pl.bucket_log2) + 1) * 2 + 15) & ~(size_t)15) +
+                     (size_t)kWaves * pl.g * kQcap * (8 + 2 * 2 * pl.groups);
   auto kern = pl.g == kGSmall ? scan_kernel<kGroupsSmall, kGSmall> : scan_kernel<kGroupsBig, kGBig>;
   FDY_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   prof_begin(FDY_PROF_SCAN_MAIN, stream);

@@ -82,7 +82,7 @@ def test_scan_hierarchical_levels(hip, oracle):
     ar = small(4)  # 65,536 allocations
     old = fdy.tune_get(fdy.TUNE_SCAN_TOP_LOG2)
     try:
-        for top_log2 in (1, 3, 8, 11, 12, 13, 15):
+        for top_log2 in (1, 3, 8, 11, 12, 13, 14):
             assert fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, top_log2) >= 0
             check_scan(hip, oracle, ar.words[:300000], ar.table, tag=f"top_log2={top_log2}")
             check_scan(hip, oracle, ar.words[:5000], ar.table[:1000], tag=f"A=1000 top_log2={top_log2}")
