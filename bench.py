@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # summary profiles/whole_path_config4_hbm_traffic_pmc.txt and are reported only for the
 # workload and kernels they were collected on.
 PMC_TRAFFIC_BYTES = {
-    (4, "scan_kernel"): 2_996_583_014 + 216_742_400,
-    (4, "mat_main_kernel"): 2_605_461_094 + 1_073_890_714,
+    (4, "scan_kernel"): 3_014_008_832 + 216_754_688,
+    (4, "mat_main_kernel"): 2_605_340_058 + 1_073_878_323,
 }
 
 
