@@ -31,13 +31,13 @@ def build_lib(verbose=False):
     return LIB
 
 
-TOY_SRC = os.path.join(ROOT, "tests", "toy_graph", "toy_graph.hip")
+TOY_SRC = [os.path.join(ROOT, "tests", "toy_graph", f) for f in ("toy_graph.hip", "install_scale.hip")]
 TOY_LIB = os.path.join(ROOT, "tests", "toy_graph", "libtoy_graph.so")
 
 
 def build_toy(verbose=False):
-    """The toy hipGraph end-to-end check (a test program; links against libfdy.so)."""
-    cmd = [hipcc()] + FLAGS + ["-I", os.path.join(ROOT, "include"), TOY_SRC, "-L", PKG, "-lfdy",
+    """The toy hipGraph end-to-end checks (test programs; link against libfdy.so)."""
+    cmd = [hipcc()] + FLAGS + ["-I", os.path.join(ROOT, "include")] + TOY_SRC + ["-L", PKG, "-lfdy",
                                "-Wl,-rpath,$ORIGIN/../../paper_2604_06664_amd", "-o", TOY_LIB]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -28,3 +28,35 @@ def test_toy_graph_install_and_replay():
     rc = toy.toy_graph_check(msg, 512)
     print("[toy]", msg.value.decode(), flush=True)
     assert rc == 0, msg.value.decode()
+
+
+def test_install_at_decode_graph_scale():
+    """hipGraph install at the node count of one dense-decode graph (36 layers x 16 kernels):
+    67 graphs x 2 new layouts materialized by the library, installed node by node into the
+    template's executable graph, each replayed and checked against a host simulation.  Prints
+    the install time per graph beside building and instantiating the graph from scratch (the
+    two quantities of Table 2 of the paper; its numbers are for other hardware and real
+    kernels, so they are context, not a bar)."""
+    import torch
+
+    assert torch.cuda.is_available()
+    assert os.path.exists(LIB), "build it first: python -c 'import __graft_entry__ as g; g.build()'"
+    import paper_2604_06664_amd as fdy
+
+    fdy.lib()
+    C.CDLL(fdy.LIB_PATH, mode=C.RTLD_GLOBAL)
+    toy = C.CDLL(LIB)
+    toy.install_scale_check.restype = C.c_int
+    toy.install_scale_check.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_double),
+                                        C.c_char_p, C.c_int]
+    msg = C.create_string_buffer(1024)
+    stats = (C.c_double * 8)()
+    print("[install] 576 nodes x 67 graphs x 2 maps", flush=True)
+    rc = toy.install_scale_check(576, 67, 2, stats, msg, 1024)
+    print("[install]", msg.value.decode(), flush=True)
+    assert rc == 0, msg.value.decode()
+    assert stats[5] == 67 * 2 and stats[6] == 2 * 576
+    out = os.path.join(os.path.dirname(HERE), "gpurun_out")
+    if os.path.isdir(out):
+        with open(os.path.join(out, "install_scale.txt"), "w") as f:
+            f.write(msg.value.decode() + "\n" + " ".join(f"{v:.4f}" for v in stats) + "\n")
