@@ -156,12 +156,27 @@ def cpu_baseline(ar, run, n):
     got_out = fdy.to_host(run.mat.d_out, np.uint64, n)
     parity = parity and bool(np.array_equal(got_out, out[0]))
     secs = t_scan + t_mat
+    # secondary: the same oracle scan function over disjoint word ranges on all host cores (the
+    # paper's preparation "scales linearly with CPU threads", Section 4.2.1); no new logic
+    from concurrent.futures import ThreadPoolExecutor
+
+    threads = min(16, os.cpu_count() or 1)
+    cuts = [n * i // threads for i in range(threads + 1)]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        parts = list(ex.map(lambda i: oracle.scan(words[cuts[i]:cuts[i + 1]], ar.table)[1], range(threads)))
+    t_scan_mt = time.perf_counter() - t0
+    mt_ok = sum(parts) == cnt
     return dict(value=round(2 * n * 8 / secs / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
                 sample=f"first {n} words ({n * 8 / 2**20:.0f} MiB) of the workload against the full "
                        f"allocation table: scan {t_scan:.2f}s + segment+materialize {t_mat:.2f}s, "
                        f"single thread",
                 scan_gbs=round(n * 8 / t_scan / 1e9, 4), materialize_gbs=round(n * 8 / t_mat / 1e9, 4),
-                gpu_matches_oracle_on_sample=parity)
+                gpu_matches_oracle_on_sample=parity,
+                all_cores=dict(value=round(2 * n * 8 / (t_scan_mt + t_mat) / 1e9, 4), unit="GB/s",
+                               cores=threads, scan_s=round(t_scan_mt, 3), counts_agree=mt_ok,
+                               note="oracle scan over disjoint word ranges, one range per thread; "
+                                    "materialize single-threaded"))
 
 
 def session_reloc_dtype():
