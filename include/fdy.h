@@ -164,6 +164,29 @@ int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, const fdy_alloc
                       uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
                       uint32_t* d_status, void* hip_stream);
 
+/* ---- fused scan + rebase (variant; a1 + c1 + c2 in one pass) ------------------------
+ * For one new layout and no templating (a new instance whose addresses differ, Section
+ * 4.1.1 relaxed; argument buffers are opaque, Section 2.2), the relocation table need not
+ * exist: with i, offset as in fdy_scan_pointers,
+ *   d_out_words[j] = d_new_base[i] + offset (mod 2^64)   if word j is a hit,
+ *   d_out_words[j] = d_words[j]                          otherwise,
+ * which equals fdy_scan_pointers followed by fdy_materialize with one source graph, one
+ * base map and no overrides or patches.  Every input word is read once and every output
+ * word written once.
+ *
+ *   d_words, d_table as for fdy_scan_pointers
+ *   d_new_base       [n_alloc] device, 8-byte aligned
+ *   d_out_words      [n_words] device, 16-byte aligned; either d_words itself (in place) or
+ *                    an array that does not overlap it (anything else: FDY_ERR_INVALID_ARG)
+ *   d_count          device uint64_t: number of hits
+ *   d_workspace      as for fdy_scan_pointers (same size query)
+ *   d_status         device uint32_t or NULL (no status bit is raised by this call today)
+ */
+int fdy_scan_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
+                    uint32_t n_alloc, const uint64_t* d_new_base, uint64_t* d_out_words,
+                    uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
+                    uint32_t* d_status, void* hip_stream);
+
 /* ---- (a2) relocation segmentation ---------------------------------------------------
  * For each boundary d_word_off[s], s in [0, n_off): d_reloc_off[s] = number of entries of
  * d_relocs[0, min(*d_count, reloc_capacity)) whose word is < d_word_off[s] (lower bound in

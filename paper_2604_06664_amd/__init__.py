@@ -4,8 +4,8 @@ Argument marshalling only: every step of the path runs in the library's kernels.
 supplies device memory and streams.  There is no CPU fallback: if the built library is
 missing, importing the binding functions raises.
 
-Entry points keep the names of include/fdy.h: fdy_scan_pointers, fdy_reloc_segment,
-fdy_fingerprint, fdy_materialize (+ workspace queries, fdy_table_validate, fdy_strerror).
+Entry points keep the names of include/fdy.h: fdy_scan_pointers, fdy_scan_rebase,
+fdy_reloc_segment, fdy_fingerprint, fdy_materialize (+ workspace queries, fdy_table_validate, fdy_strerror).
 """
 from __future__ import annotations
 
@@ -61,6 +61,10 @@ def lib():
         L.fdy_scan_pointers.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p,
                                         C.c_uint64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
                                         C.c_void_p]
+        L.fdy_scan_rebase.restype = C.c_int
+        L.fdy_scan_rebase.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
+                                      C.c_void_p]
         L.fdy_reloc_segment.restype = C.c_int
         L.fdy_reloc_segment.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32,
                                         C.c_void_p, C.c_void_p]
@@ -144,6 +148,14 @@ def fdy_scan_pointers(d_words, n_words, d_table, n_alloc, d_relocs, reloc_capaci
     return _check(rc, "fdy_scan_pointers") if check else rc
 
 
+def fdy_scan_rebase(d_words, n_words, d_table, n_alloc, d_new_base, d_out_words, d_count,
+                    d_workspace, workspace_bytes, d_status=None, stream=None, check=True):
+    rc = lib().fdy_scan_rebase(_ptr(d_words), int(n_words), _ptr(d_table), int(n_alloc),
+                               _ptr(d_new_base), _ptr(d_out_words), _ptr(d_count), _ptr(d_workspace),
+                               int(workspace_bytes), _ptr(d_status), _stream(stream))
+    return _check(rc, "fdy_scan_rebase") if check else rc
+
+
 def fdy_reloc_segment(d_relocs, d_count, reloc_capacity, d_word_off, n_off, d_reloc_off,
                       stream=None, check=True):
     rc = lib().fdy_reloc_segment(_ptr(d_relocs), _ptr(d_count), int(reloc_capacity),
@@ -179,10 +191,10 @@ def tune_set(knob, value):
     return lib().fdy__tune_set(knob, value)
 
 
-PROF_SLOTS = 9
+PROF_SLOTS = 10
 
 
-PROF_SCAN_MAIN, PROF_MAT_MAIN = 0, 7
+PROF_SCAN_MAIN, PROF_MAT_MAIN, PROF_SCAN_REBASE = 0, 7, 9
 
 
 def prof_enable(n_records, slots=None):

@@ -105,6 +105,8 @@ struct ScanParams {
   u32 f0_log2;     // level 0 samples every (2^f0_log2 * 8^k)-th base
   u32* d_status;
   u32 spin_limit;
+  const u64* new_base;  // fused scan + rebase only: [n_alloc]
+  u64* out;             // fused scan + rebase only: [n_words]
   u32 debug;  // timing experiments only (results are then wrong): 1 skip chunk walk, 4 skip loads
 };
 
@@ -729,6 +731,170 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   }
 }
 
+// ---- fused scan + rebase: out[j] = new_base[region] + offset for a hit, words[j] otherwise.
+// One pass, no relocation table, hence no ordering between waves: every wave works through
+// groups of kFusedG consecutive sub-tiles on its own (static grid stride).  It searches the
+// group's candidates exactly as the scan does, but a hit's queue slot receives the rebased
+// value; the lanes that loaded the words then take their candidates' final values back from
+// the queue and store the whole sub-tile with the same coalesced 16-byte stores a copy would
+// use (storing candidates one by one from the search lanes was measured at half the speed:
+// 20 M scattered 8-byte writes into lines that had already left the L2).  out may be the
+// input array itself: a wave has read a sub-tile completely before it writes any of it, and
+// no other wave touches that sub-tile.
+template <int N>
+__device__ __forceinline__ void rebase_rounds(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
+                                              u64* qw, u32 Q, u32 r0, u64& H) {
+  const u32 lane = lane_id();
+  u64 wv[N];
+  Found f[N];
+  bool valid[N];
+#pragma unroll
+  for (int r = 0; r < N; ++r) {
+    valid[r] = (r0 + r) * 64 + lane < Q;
+    wv[r] = valid[r] ? qw[(r0 + r) * 64 + lane] : span_lo;
+  }
+  search<N>(p, top, span_lo, shifts, wv, f);
+  u64 nb[N];
+#pragma unroll
+  for (int r = 0; r < N; ++r) nb[r] = valid[r] && f[r].hit ? p.new_base[f[r].region] : 0;
+#pragma unroll
+  for (int r = 0; r < N; ++r) {
+    const bool hit = valid[r] && f[r].hit;
+    if (hit) qw[(r0 + r) * 64 + lane] = nb[r] + f[r].offset;  // a miss keeps its value
+    H += __popcll(ballot(hit));
+  }
+}
+
+// Rebases queue entries [0, Q) in place, in rounds of 64, up to three rounds interleaved.
+__device__ __forceinline__ void rebase_queue(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
+                                             u64* qw, u32 Q, u64& H) {
+  const u32 nr = (Q + 63) >> 6;
+  for (u32 r0 = 0; r0 < nr; r0 += 3) {
+    const u32 left = nr - r0;
+    if (left >= 3) rebase_rounds<3>(p, top, span_lo, shifts, qw, Q, r0, H);
+    else if (left == 2) rebase_rounds<2>(p, top, span_lo, shifts, qw, Q, r0, H);
+    else rebase_rounds<1>(p, top, span_lo, shifts, qw, Q, r0, H);
+  }
+}
+
+// Candidates with rank in [win, win + wn) take their final value back from queue slots
+// qoff + [0, wn).
+__device__ __forceinline__ void dequeue(u64 (&w)[kWpl], const Filt& t, u32 win, u32 wn, u32 qoff,
+                                        const u64* qw) {
+  wave_lds_fence();
+#pragma unroll
+  for (int r = 0; r < kWpl; ++r)
+    if (t.c[r] && t.crank[r] - win < wn) w[r] = qw[qoff + t.crank[r] - win];
+  wave_lds_fence();
+}
+
+__device__ __forceinline__ void store_words(const ScanParams& p, u32 sub, const u64 (&w)[kWpl]) {
+  typedef u64 v2u64 __attribute__((ext_vector_type(2)));
+  const u32 lane = lane_id();
+  const u64 wbase = (u64)sub * kSub;
+  if (wbase + kSub <= p.n_words) {
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      v2u64 v;
+      v.x = w[2 * k];
+      v.y = w[2 * k + 1];
+      __builtin_nontemporal_store(v, reinterpret_cast<v2u64*>(p.out + wbase + (k * 64 + lane) * 2));
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const u64 idx = wbase + (k * 64 + lane) * 2;
+      if (idx < p.n_words) p.out[idx] = w[2 * k];
+      if (idx + 1 < p.n_words) p.out[idx + 1] = w[2 * k + 1];
+    }
+  }
+}
+
+constexpr int kFusedG = 2;  // sub-tiles per group
+
+__global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
+  constexpr u32 kQwave = kFusedG * kQcap;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  u32* top = reinterpret_cast<u32*>(smem_raw);
+  unsigned short* bst = reinterpret_cast<unsigned short*>(top + p.top_n);
+  const u32 n_bst = (1u << p.bucket_log2) + 1;
+  unsigned char* qbase = smem_raw + (size_t)p.top_n * 4 + (((size_t)n_bst * 2 + 15) & ~(size_t)15);
+  const u32 tid = threadIdx.x;
+  const u32 lane = tid & 63;
+  const u32 wave = tid >> 6;
+  u64* qw = reinterpret_cast<u64*>(qbase) + wave * kQwave;
+  unsigned short* qi = reinterpret_cast<unsigned short*>(qbase + (size_t)kWaves * kQwave * 8) + wave * kQwave;
+  for (u32 i = tid; i < p.top_n; i += kBlock) top[i] = p.top[i];
+  for (u32 i = tid; i < n_bst; i += kBlock) bst[i] = p.bstart[i];
+  __syncthreads();
+
+  const u64 span_lo = p.table[0].base;
+  const u64 span_len = p.table[p.n_alloc - 1].base + p.table[p.n_alloc - 1].size - span_lo;
+  const u32 shifts = key_shift_for(span_len) |
+                     (bucket_shift_for(span_len, key_shift_for(span_len), p.bucket_log2) << 8);
+
+  // consecutive waves of a workgroup take consecutive groups; workgroups stride over the rest
+  const u32 n_groups = (p.n_sub + kFusedG - 1) / kFusedG;
+  const u32 stride = gridDim.x * kWaves;
+  u32 grp = blockIdx.x * kWaves + wave;
+  u64 H = 0;
+  u64 w[kFusedG][kWpl];
+  if (grp < n_groups) {
+#pragma unroll
+    for (int r = 0; r < kFusedG; ++r) load_words(p, grp * kFusedG + r, span_lo, w[r]);
+  }
+  for (; grp < n_groups; grp += stride) {
+    const u32 first_sub = grp * kFusedG;
+    Filt t[kFusedG];
+    u32 qoff[kFusedG];
+    u32 Q = 0;
+#pragma unroll
+    for (int r = 0; r < kFusedG; ++r) {
+      filter_words(w[r], t[r], span_lo, span_len);
+      qoff[r] = Q;
+      Q += t[r].Q;
+    }
+    // the next group's words, in flight during the search
+    const bool more = grp + stride < n_groups;
+    u64 nw[kFusedG][kWpl];
+    if (more) {
+#pragma unroll
+      for (int r = 0; r < kFusedG; ++r) load_words(p, (grp + stride) * kFusedG + r, span_lo, nw[r]);
+    }
+    if (Q <= kQwave) {
+#pragma unroll
+      for (int r = 0; r < kFusedG; ++r) enqueue(w[r], t[r], r, 0, t[r].Q, qoff[r], qw, qi);
+      rebase_queue(p, top, span_lo, shifts, qw, Q, H);
+#pragma unroll
+      for (int r = 0; r < kFusedG; ++r) dequeue(w[r], t[r], 0, t[r].Q, qoff[r], qw);
+    } else {
+      // dense group: sub-tile by sub-tile (instantiated, not looped: the words stay in
+      // registers), in windows of the queue's size
+      auto dense_row = [&](auto row_c) {
+        constexpr int r = decltype(row_c)::value;
+        for (u32 win = 0; win < t[r].Q; win += kQwave) {
+          const u32 wn = t[r].Q - win < kQwave ? t[r].Q - win : kQwave;
+          enqueue(w[r], t[r], 0, win, wn, 0, qw, qi);
+          rebase_queue(p, top, span_lo, shifts, qw, wn, H);
+          dequeue(w[r], t[r], win, wn, 0, qw);
+        }
+      };
+      dense_row(std::integral_constant<int, 0>{});
+      dense_row(std::integral_constant<int, 1>{});
+      static_assert(kFusedG == 2, "rows are instantiated by hand");
+    }
+#pragma unroll
+    for (int r = 0; r < kFusedG; ++r) store_words(p, first_sub + r, w[r]);
+    if (more) {
+#pragma unroll
+      for (int r = 0; r < kFusedG; ++r)
+#pragma unroll
+        for (int k = 0; k < kWpl; ++k) w[r][k] = nw[r][k];
+    }
+  }
+  if (lane == 0 && H) atomicAdd(reinterpret_cast<unsigned long long*>(p.d_count), (unsigned long long)H);
+}
+
 struct ScanInit {
   const fdy_alloc* table;
   u32 n_alloc;
@@ -748,6 +914,7 @@ struct ScanInit {
   u32 n_chunks;
   u32* ticket;
   u64* d_count;
+  u32 zero_count;  // fused scan + rebase: the count is accumulated, so it starts at 0
 };
 
 // Builds the level-0 keys and the packed mid levels, clears the sub-tile states and ticket.
@@ -805,7 +972,7 @@ __global__ void scan_init_kernel(ScanInit a) {
   if (i < a.n_chunks) a.cstate[i] = 0;
   if (i == 0) {
     *a.ticket = 0;
-    if (a.n_sub == 0 || a.n_alloc == 0) *a.d_count = 0;
+    if (a.n_sub == 0 || a.n_alloc == 0 || a.zero_count) *a.d_count = 0;
   }
 }
 
@@ -909,10 +1076,13 @@ extern "C" size_t fdy_scan_workspace_bytes(uint64_t n_words, uint32_t n_alloc) {
   return pl.total;
 }
 
-extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
-                                 uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
-                                 uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
-                                 uint32_t* d_status, void* hip_stream) {
+// Shared by the scan and the fused scan + rebase (d_out != null): checks, workspace layout,
+// the init kernel, then the main kernel of either.
+static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
+                       uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity, uint64_t* d_count,
+                       const uint64_t* d_new_base, uint64_t* d_out, void* d_workspace,
+                       size_t workspace_bytes, uint32_t* d_status, void* hip_stream) {
+  const bool fused = d_out != nullptr;
   if (n_words > kMaxWords) return FDY_ERR_INVALID_ARG;
   if (!d_count) return FDY_ERR_INVALID_ARG;
   if (n_words && (!d_words || ((uintptr_t)d_words & 15))) return FDY_ERR_INVALID_ARG;
@@ -952,6 +1122,7 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   a.n_chunks = pl.n_chunks;
   a.ticket = (u32*)ws;
   a.d_count = (u64*)d_count;
+  a.zero_count = fused ? 1u : 0u;
   u32 n_init = pl.top_n > pl.n_chunks ? pl.top_n : pl.n_chunks;
   for (int j = 0; j < kMaxMid; ++j)
     if (pl.mid_len[j] > n_init) n_init = pl.mid_len[j];
@@ -961,7 +1132,12 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   hipLaunchKernelGGL(scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream, a);
   prof_end(FDY_PROF_SCAN_INIT, stream);
   FDY_HIP_TRY(hipGetLastError());
-  if (pl.n_sub == 0 || n_alloc == 0) return FDY_OK;  // nothing can be a pointer
+  if (pl.n_sub == 0) return FDY_OK;
+  if (n_alloc == 0) {  // nothing can be a pointer; the fused form still owes the copy
+    if (fused && d_out != d_words)
+      FDY_HIP_TRY(hipMemcpyAsync(d_out, d_words, n_words * 8, hipMemcpyDeviceToDevice, stream));
+    return FDY_OK;
+  }
 
   ScanParams p;
   p.words = (const u64*)d_words;
@@ -985,9 +1161,24 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   p.d_status = d_status;
   p.spin_limit = (u32)fdy__tune_get(FDY_TUNE_SCAN_SPIN_LIMIT);
   p.debug = (u32)fdy__tune_get(FDY_TUNE_SCAN_DEBUG);
+  p.new_base = (const u64*)d_new_base;
+  p.out = (u64*)d_out;
 
-  const size_t lds = (size_t)pl.top_n * 4 + (((((size_t)1 << pl.bucket_log2) + 1) * 2 + 15) & ~(size_t)15) +
-                     (size_t)kWaves * pl.g * kQcap * (8 + 2 * 2 * pl.groups);
+  const size_t lds0 = (size_t)pl.top_n * 4 + (((((size_t)1 << pl.bucket_log2) + 1) * 2 + 15) & ~(size_t)15);
+  if (fused) {
+    const size_t lds = lds0 + (size_t)kWaves * kFusedG * kQcap * 10;
+    const u32 n_groups = (pl.n_sub + kFusedG - 1) / kFusedG;
+    u32 fgrid = (u32)n_cu;  // one workgroup per compute unit (256 registers per lane)
+    if (fgrid > (n_groups + kWaves - 1) / kWaves) fgrid = (n_groups + kWaves - 1) / kWaves;
+    FDY_HIP_TRY(hipFuncSetAttribute((const void*)scan_rebase_kernel,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    prof_begin(FDY_PROF_SCAN_REBASE, stream);
+    hipLaunchKernelGGL(scan_rebase_kernel, dim3(fgrid), dim3(kBlock), lds, stream, p);
+    prof_end(FDY_PROF_SCAN_REBASE, stream);
+    FDY_HIP_TRY(hipGetLastError());
+    return FDY_OK;
+  }
+  const size_t lds = lds0 + (size_t)kWaves * pl.g * kQcap * (8 + 2 * 2 * pl.groups);
   auto kern = pl.g == kGSmall ? scan_kernel<kGroupsSmall, kGSmall> : scan_kernel<kGroupsBig, kGBig>;
   FDY_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   prof_begin(FDY_PROF_SCAN_MAIN, stream);
@@ -995,6 +1186,33 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
   prof_end(FDY_PROF_SCAN_MAIN, stream);
   FDY_HIP_TRY(hipGetLastError());
   return FDY_OK;
+}
+
+extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
+                                 uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
+                                 uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
+                                 uint32_t* d_status, void* hip_stream) {
+  return scan_launch(d_words, n_words, d_table, n_alloc, d_relocs, reloc_capacity, d_count, nullptr, nullptr,
+                     d_workspace, workspace_bytes, d_status, hip_stream);
+}
+
+extern "C" int fdy_scan_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
+                               uint32_t n_alloc, const uint64_t* d_new_base, uint64_t* d_out_words,
+                               uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
+                               uint32_t* d_status, void* hip_stream) {
+  if (n_words && (!d_out_words || ((uintptr_t)d_out_words & 15))) return FDY_ERR_INVALID_ARG;
+  if (n_alloc && (!d_new_base || ((uintptr_t)d_new_base & 7))) return FDY_ERR_INVALID_ARG;
+  if (n_words == 0) {  // nothing to write; keep the count defined
+    if (!d_count) return FDY_ERR_INVALID_ARG;
+    return scan_launch(d_words, 0, d_table, n_alloc, nullptr, 0, d_count, nullptr, nullptr, d_workspace,
+                       workspace_bytes, d_status, hip_stream);
+  }
+  if (d_out_words != d_words) {  // exactly the same array, or disjoint
+    const uintptr_t a = (uintptr_t)d_words, b = (uintptr_t)d_out_words, len = (uintptr_t)n_words * 8;
+    if (a < b + len && b < a + len) return FDY_ERR_INVALID_ARG;
+  }
+  return scan_launch(d_words, n_words, d_table, n_alloc, nullptr, 0, d_count, d_new_base, d_out_words,
+                     d_workspace, workspace_bytes, d_status, hip_stream);
 }
 
 extern "C" int fdy_reloc_segment(const fdy_reloc* d_relocs, const uint64_t* d_count,

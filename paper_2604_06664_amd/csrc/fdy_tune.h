@@ -36,7 +36,8 @@ enum {
   FDY_PROF_MAT_PREP_TILES = 6,
   FDY_PROF_MAT_MAIN = 7,
   FDY_PROF_MAT_DIMS = 8,
-  FDY_PROF_SLOTS = 9
+  FDY_PROF_SCAN_REBASE = 9,
+  FDY_PROF_SLOTS = 10
 };
 int fdy__prof_enable(int n_records);
 void fdy__prof_mask(unsigned slot_mask); /* which slots record; default all */

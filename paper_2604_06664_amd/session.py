@@ -50,6 +50,40 @@ def scan(words, table, capacity=None):
     return run.result()
 
 
+class ScanRebaseRun:
+    """Device-resident inputs, output and workspace of one fdy_scan_rebase problem."""
+
+    def __init__(self, words, table, new_base, in_place=False, n_words=None, n_alloc=None):
+        # n_words / n_alloc: record counts when words / table are device byte tensors
+        self.n_words = int(len(words) if n_words is None else n_words)
+        self.n_alloc = int(len(table) if n_alloc is None else n_alloc)
+        self.d_words = words if torch.is_tensor(words) else fdy.to_device(words)
+        self.d_table = table if torch.is_tensor(table) else fdy.to_device(table)
+        self.d_new_base = new_base if torch.is_tensor(new_base) else fdy.to_device(
+            np.ascontiguousarray(new_base, np.uint64))
+        self.d_out = self.d_words if in_place else fdy.device_bytes(self.n_words * 8, fill=0xEE)
+        self.d_count = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+        self.ws_bytes = fdy.fdy_scan_workspace_bytes(self.n_words, self.n_alloc)
+        self.d_ws = fdy.device_bytes(self.ws_bytes)
+        self.d_status = _status_tensor()
+
+    def launch(self, stream=None):
+        return fdy.fdy_scan_rebase(self.d_words, self.n_words, self.d_table, self.n_alloc,
+                                   self.d_new_base, self.d_out, self.d_count, self.d_ws,
+                                   self.ws_bytes, self.d_status, stream)
+
+    def result(self):
+        torch.cuda.synchronize()
+        return (fdy.to_host(self.d_out, np.uint64, self.n_words), int(self.d_count.item()),
+                int(self.d_status.item()))
+
+
+def scan_rebase(words, table, new_base, in_place=False):
+    run = ScanRebaseRun(words, table, new_base, in_place)
+    run.launch()
+    return run.result()
+
+
 def reloc_segment(d_relocs, d_count, capacity, word_off):
     d_off = fdy.to_device(np.ascontiguousarray(word_off, np.uint64))
     d_out = fdy.device_bytes(len(word_off) * 8, fill=0xEE)

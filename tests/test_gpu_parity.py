@@ -199,6 +199,77 @@ def test_scan_argument_errors(hip):
     torch.cuda.synchronize()
 
 
+# ------------------------------------------------------------------- fused scan + rebase
+def oracle_rebase(oracle, words, table, new_base):
+    """What fdy_scan_rebase must produce, from the oracle's own scan and materialize: one
+    source graph holding all the words, one base map, no overrides, no patches."""
+    words = np.ascontiguousarray(words, np.uint64)
+    relocs, cnt = oracle.scan(words, table)
+    woff = np.array([0, len(words)], np.uint64)
+    mp = MatProblem(
+        src_words=words, src_word_off=woff, src_nodes=np.zeros(0, L.NODE), src_node_off=[0, 0],
+        relocs=relocs, src_reloc_off=oracle.reloc_segment(relocs, woff), tmpl_graph=[0], graph_tmpl=[0],
+        ovr=np.zeros(0, L.OVR32), ovr_off=[0, 0], govr=np.zeros(0, L.GRID_OVR), govr_off=[0, 0],
+        new_base=np.ascontiguousarray(new_base, np.uint64).reshape(1, -1), map_rank=None, n_ranks=0,
+        patch=np.zeros(0, L.PATCH), patch_off=[0])
+    out, _ = oracle.materialize(mp, want_dims=False)
+    return out[0], cnt
+
+
+def check_rebase(hip, oracle, words, table, new_base, tag="", in_place=False):
+    say(f"[scan_rebase] {tag} W={len(words)} A={len(table)} in_place={in_place}")
+    ref, rcnt = oracle_rebase(oracle, words, table, new_base) if len(words) else (np.zeros(0, np.uint64), 0)
+    got, cnt, status = hip.scan_rebase(words, table, new_base, in_place=in_place)
+    assert cnt == rcnt and status == 0
+    assert np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_scan_rebase_small_configs(hip, oracle, idx):
+    ar = small(idx)
+    check_rebase(hip, oracle, ar.words, ar.table, ar.new_base[0], tag=ar.name)
+    check_rebase(hip, oracle, ar.words, ar.table, ar.new_base[0], tag=ar.name + " in place", in_place=True)
+
+
+def test_scan_rebase_edge_cases(hip, oracle):
+    import paper_2604_06664_amd as fdy
+
+    ar = small(4)  # 65,536 allocations
+    nb = ar.new_base[0]
+    check_rebase(hip, oracle, np.zeros(0, np.uint64), ar.table, nb, tag="no words")
+    check_rebase(hip, oracle, ar.words[:1], ar.table, nb, tag="one word")
+    for n in (1023, 1024, 1025, 2047, 4097, 70001):  # group and sub-tile boundaries, odd tails
+        check_rebase(hip, oracle, ar.words[:n], ar.table, nb, tag="ragged")
+    # no table: a plain copy
+    got, cnt, status = hip.scan_rebase(ar.words[:5000], ar.table[:0], nb[:0])
+    assert cnt == 0 and status == 0 and np.array_equal(got, ar.words[:5000])
+    # every word a hit (groups beyond the queue: windowed path), touching intervals, extremes,
+    # sums that wrap mod 2^64
+    dense = mk_table([(0x1000 + 64 * i, 64) for i in range(300)] + [(2**64 - 0x100, 0xFF)])
+    rng = np.random.default_rng(5)
+    w = (0x1000 + rng.integers(0, 64 * 300, 9000)).astype(np.uint64)
+    w[::97] = np.uint64(2**64 - 1)
+    w[1::97] = np.uint64(2**64 - 2)
+    w[2::97] = np.uint64(0xFFF)
+    dnb = rng.integers(0, 1 << 64, len(dense), dtype=np.uint64)
+    check_rebase(hip, oracle, w, dense, dnb, tag="all hits")
+    check_rebase(hip, oracle, w, dense, dnb, tag="all hits in place", in_place=True)
+    # every depth of the hierarchy, with the packed table copy and unpackable lines
+    old = fdy.tune_get(fdy.TUNE_SCAN_TOP_LOG2)
+    try:
+        for top_log2 in (3, 9, 12):
+            fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, top_log2)
+            check_rebase(hip, oracle, ar.words[:200000], ar.table, nb, tag=f"top_log2={top_log2}")
+    finally:
+        fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, old)
+    # overlapping, non-identical input and output ranges are refused on the host
+    run = hip.ScanRebaseRun(ar.words[:4096], ar.table, nb)
+    rc = fdy.fdy_scan_rebase(run.d_words, 2048, run.d_table, run.n_alloc, run.d_new_base,
+                             run.d_words.data_ptr() + 1024 * 8, run.d_count, run.d_ws, run.ws_bytes,
+                             run.d_status, check=False)
+    assert rc == fdy.FDY_ERR_INVALID_ARG
+
+
 def test_reloc_segment(hip, oracle):
     ar = small(2)
     run = hip.ScanRun(ar.words, ar.table)
