@@ -10,7 +10,7 @@ int g_tune[FDY_TUNE_COUNT] = {
     /* MAT_MAP_GROUP     */ 0,
     0, 0, 0, 0};
 const int g_tune_lo[FDY_TUNE_COUNT] = {1, 1, 0, 0, 0, 0, 0, 0};
-const int g_tune_hi[FDY_TUNE_COUNT] = {14, 16, 1 << 30, 64, 63, 0, 0, 0};
+const int g_tune_hi[FDY_TUNE_COUNT] = {14, 16, 1 << 30, 64, 0, 0, 0, 0};
 }  // namespace
 
 extern "C" int fdy__tune_get(int knob) {

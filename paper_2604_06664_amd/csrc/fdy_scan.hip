@@ -107,7 +107,6 @@ struct ScanParams {
   u32 spin_limit;
   const u64* new_base;  // fused scan + rebase only: [n_alloc]
   u64* out;             // fused scan + rebase only: [n_words]
-  u32 debug;  // timing experiments only (results are then wrong): 1 skip chunk walk, 4 skip loads
 };
 
 constexpr u64 kFlagAgg = 1ull << 62;
@@ -294,7 +293,6 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
 #pragma unroll
       for (int h = 0; h < 4; ++h) k[c][h] = *reinterpret_cast<const u64x2*>(&m[n[c] + 2 * h]);
     }
-    if (p.debug & 8) continue;  // timing experiment: ignore this level's keys
 #pragma unroll
     for (int c = 0; c < N; ++c) {
       u32 at = 0;
@@ -335,16 +333,14 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
           exact = false;
           const u64 x = w[c] - gb[c];
           u32 d = 0, z = q[0].y, at = 0;
-          if (!(p.debug & 16)) {  // timing experiment: ignore entries 1..7
 #pragma unroll
-            for (int h = 1; h < 8; ++h) {
-              const u32 dh = (h & 1) ? q[h >> 1].z : q[h >> 1].x;
-              const u32 zh = (h & 1) ? q[h >> 1].w : q[h >> 1].y;
-              if ((u64)dh <= x) {
-                d = dh;
-                z = zh;
-                at = h;
-              }
+          for (int h = 1; h < 8; ++h) {
+            const u32 dh = (h & 1) ? q[h >> 1].z : q[h >> 1].x;
+            const u32 zh = (h & 1) ? q[h >> 1].w : q[h >> 1].y;
+            if ((u64)dh <= x) {
+              d = dh;
+              z = zh;
+              at = h;
             }
           }
           e[c].x = gb[c] + d;
@@ -355,15 +351,13 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
       if (exact) {  // three dependent probes inside the table line: few registers, rarely taken
         n[c] *= 8;
         e[c] = *reinterpret_cast<const u64x2*>(&p.table[n[c]]);
-        if (!(p.debug & 16)) {
 #pragma unroll 1
-          for (u32 step = 4; step; step >>= 1) {
-            if (n[c] + step < p.n_alloc) {
-              const u64x2 q = *reinterpret_cast<const u64x2*>(&p.table[n[c] + step]);
-              if (q.x <= w[c]) {
-                n[c] += step;
-                e[c] = q;
-              }
+        for (u32 step = 4; step; step >>= 1) {
+          if (n[c] + step < p.n_alloc) {
+            const u64x2 q = *reinterpret_cast<const u64x2*>(&p.table[n[c] + step]);
+            if (q.x <= w[c]) {
+              n[c] += step;
+              e[c] = q;
             }
           }
         }
@@ -390,10 +384,7 @@ struct Filt {
 __device__ __forceinline__ void load_words(const ScanParams& p, u32 sub, u64 span_lo, u64 (&w)[kWpl]) {
   const u32 lane = lane_id();
   const u64 wbase = (u64)sub * kSub;
-  if (p.debug & 4) {
-#pragma unroll
-    for (int k = 0; k < kWpl; ++k) w[k] = span_lo - 1;
-  } else if (wbase + kSub <= p.n_words) {
+  if (wbase + kSub <= p.n_words) {
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
       // streamed once: non-temporal, so that the table levels keep their place in L2
@@ -682,7 +673,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
     if (closer && have_prev) {
       const u32 pchunk = prev.base / kChunk;
       const u64 total = __shfl(prev.cnt_incl, 63);
-      const u64 excl = (p.debug & 1) ? 0 : chunk_exclusive_prefix(p.cstate, pchunk, p.spin_limit, p.d_status);
+      const u64 excl = chunk_exclusive_prefix(p.cstate, pchunk, p.spin_limit, p.d_status);
       if (lane == 0) {
         if (pchunk != 0) st_state(&p.cstate[pchunk], kFlagInc | ((excl + total) & kValMask));
         if (prev.base + kChunk >= p.n_sub) {  // the last chunk: the grand total
@@ -716,7 +707,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
     if (closer) {
       const u32 pchunk = prev.base / kChunk;
       const u64 total = __shfl(prev.cnt_incl, 63);
-      const u64 excl = (p.debug & 1) ? 0 : chunk_exclusive_prefix(p.cstate, pchunk, p.spin_limit, p.d_status);
+      const u64 excl = chunk_exclusive_prefix(p.cstate, pchunk, p.spin_limit, p.d_status);
       if (lane == 0) {
         if (pchunk != 0) st_state(&p.cstate[pchunk], kFlagInc | ((excl + total) & kValMask));
         if (prev.base + kChunk >= p.n_sub) {  // the last chunk: the grand total
@@ -1160,7 +1151,6 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   p.f0_log2 = pl.f0_log2;
   p.d_status = d_status;
   p.spin_limit = (u32)fdy__tune_get(FDY_TUNE_SCAN_SPIN_LIMIT);
-  p.debug = (u32)fdy__tune_get(FDY_TUNE_SCAN_DEBUG);
   p.new_base = (const u64*)d_new_base;
   p.out = (u64*)d_out;
 

@@ -13,7 +13,6 @@ enum {
   FDY_TUNE_SCAN_WG_PER_CU = 1,  /* persistent scan workgroups launched per compute unit    */
   FDY_TUNE_SCAN_SPIN_LIMIT = 2, /* polls of a predecessor tile before giving up            */
   FDY_TUNE_MAT_MAP_GROUP = 3,     /* base maps per materialize workgroup, 0 = automatic      */
-  FDY_TUNE_SCAN_DEBUG = 4,      /* timing experiments: parts of the scan switched off      */
   FDY_TUNE_COUNT = 8
 };
 
