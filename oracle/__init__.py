@@ -171,3 +171,20 @@ def materialize_brute(mi: MatProblem):
     if rc != 0:
         raise ValueError("oracle: materialize inputs are not valid")
     return out
+
+
+def derive_overrides(words, word_off, graph_tmpl, tmpl_graph, capacity=None):
+    """-> (ovr OVR32[min(total, capacity)], ovr_off u64[G+1]); raises on mismatched sizes."""
+    w = _c(words, np.uint64)
+    wo = _c(word_off, np.uint64)
+    gt = _c(graph_tmpl, np.uint32)
+    tg = _c(tmpl_graph, np.uint32)
+    G = len(gt)
+    cap = 2 * len(w) if capacity is None else int(capacity)
+    ovr = np.zeros(cap, L.OVR32)
+    off = np.zeros(G + 1, np.uint64)
+    rc = lib().orc_derive_overrides(_p(w), _p(wo), C.c_uint32(G), _p(gt), _p(tg), C.c_uint32(len(tg)),
+                                    _p(ovr), C.c_uint64(cap), _p(off))
+    if rc != 0:
+        raise ValueError("oracle: derive_overrides inputs are not valid")
+    return ovr[: min(int(off[G]), cap)].copy(), off

@@ -23,6 +23,12 @@
 //                    arguments): copy, rebase, override, patch, in that order.  A
 //                    word-at-a-time form is provided for pinning.
 //
+//  * derive        - the SAVE side of Section 4.2.1 / Section 5.3: within a topology group
+//                    the graphs "differ only in per-node parameters", so a non-template graph
+//                    is stored as what differs from its template.  The plain definition: every
+//                    32-bit half of the graph's argument words that is not equal to the
+//                    template's half at the same place, in ascending byte order.
+//
 // Parity pins (see tests/test_oracle_*.py): brute-force forms on small inputs, generator
 // ground truth (every planted pointer found, no boundary decoy flagged), identity and
 // round-trip invariants, the published SplitMix64 test vector.  No function here is
@@ -353,6 +359,42 @@ int orc_materialize_brute(const MatArgs* a, uint64_t* out_words, uint64_t out_wo
       pos += nw;
     }
   }
+  return 0;
+}
+
+// Per-graph overrides by comparison with the template: for graph g, template source graph
+// s = tmpl_graph[graph_tmpl[g]], every byte offset b (multiple of 4) at which the 32-bit
+// little-endian value of g's blob differs from s's becomes {b, value in g}; ascending b per
+// graph, graphs in order; ovr_off[g] = entries before graph g, ovr_off[G] = total (also when
+// it exceeds `capacity`; then only the first `capacity` entries are stored).
+// -1: a template index out of range, or a graph whose word count differs from its template's.
+int orc_derive_overrides(const uint64_t* words, const uint64_t* word_off, uint32_t G,
+                         const uint32_t* graph_tmpl, const uint32_t* tmpl_graph, uint32_t T, Ovr32* ovr,
+                         uint64_t capacity, uint64_t* ovr_off) {
+  uint64_t K = 0;
+  for (uint32_t g = 0; g < G; ++g) {
+    ovr_off[g] = K;
+    if (graph_tmpl[g] >= T) return -1;
+    const uint32_t s = tmpl_graph[graph_tmpl[g]];
+    if (s >= G) return -1;
+    const uint64_t nw = word_off[g + 1] - word_off[g];
+    if (word_off[s + 1] - word_off[s] != nw) return -1;
+    const unsigned char* a = reinterpret_cast<const unsigned char*>(words + word_off[g]);
+    const unsigned char* b = reinterpret_cast<const unsigned char*>(words + word_off[s]);
+    for (uint64_t off = 0; off < nw * 8; off += 4) {
+      uint32_t va, vb;
+      std::memcpy(&va, a + off, 4);
+      std::memcpy(&vb, b + off, 4);
+      if (va != vb) {
+        if (K < capacity) {
+          ovr[K].byte_off = (uint32_t)off;
+          ovr[K].value = va;
+        }
+        ++K;
+      }
+    }
+  }
+  ovr_off[G] = K;
   return 0;
 }
 
