@@ -224,6 +224,40 @@ int fdy_fingerprint(const fdy_node* d_nodes, const uint64_t* d_node_off, uint32_
                     uint32_t field_mask, uint64_t* d_keys, uint32_t* d_template_id,
                     uint32_t* d_tmpl_graph, uint32_t* d_n_templates, void* hip_stream);
 
+/* ---- override derivation (SAVE side of templating; variant, after (b)) ----------------
+ * Within a topology group the graphs differ only in per-node parameters (Section 4.2.1,
+ * Section 5.3), so a non-template graph is stored as what differs from its template.  For
+ * graph g let s = d_tmpl_graph[d_graph_tmpl[g]] (as fdy_fingerprint produces them); for every
+ * byte offset b, a multiple of 4, at which the 32-bit little-endian value of g's blob
+ * differs from s's, the entry {byte_off = b, value = g's value} is written; ascending b per
+ * graph, graphs in order.  d_ovr_off[g] = entries before graph g, d_ovr_off[n_graphs] = the
+ * total, also when it exceeds ovr_capacity (then only the first ovr_capacity entries are
+ * written and FDY_ST_CAPACITY is raised).  The lists are what fdy_materialize takes as ovr /
+ * ovr_off when the same array of words is its source archive: template + overrides = graph.
+ * A word that holds a pointer and differs from the template's is reported like any other;
+ * such a graph does not share its template's parameters and should not share its group.
+ *
+ *   d_words          device, 8-byte aligned: all graphs' words; graph g owns words
+ *                    [d_word_off[g], d_word_off[g+1])
+ *   n_words_total    host copy of d_word_off[n_graphs] (sizes the workspace; a mismatch
+ *                    raises FDY_ST_BAD_SIZE and yields no entries)
+ *   d_graph_tmpl     [n_graphs] template id of each graph
+ *   d_tmpl_graph     [n_templates] source graph of each template
+ *   d_ovr            [ovr_capacity] out, 8-byte aligned
+ *   d_ovr_off        [n_graphs+1] out
+ *   d_workspace      device, 256-byte aligned, >= fdy_derive_workspace_bytes() bytes
+ *   d_status         device uint32_t or NULL: FDY_ST_BAD_INDEX for a template id or source
+ *                    graph out of range, FDY_ST_BAD_SIZE for a graph whose word count
+ *                    differs from its template's (such graphs get no entries)
+ *   n_graphs <= 2^20, n_words_total < 2^40, every graph below 2^29 words (32-bit offsets)
+ */
+size_t fdy_derive_workspace_bytes(uint64_t n_words_total, uint32_t n_graphs);
+int fdy_derive_overrides(const uint64_t* d_words, uint64_t n_words_total, const uint64_t* d_word_off,
+                         uint32_t n_graphs, const uint32_t* d_graph_tmpl,
+                         const uint32_t* d_tmpl_graph, uint32_t n_templates, fdy_ovr32* d_ovr,
+                         uint64_t ovr_capacity, uint64_t* d_ovr_off, void* d_workspace,
+                         size_t workspace_bytes, uint32_t* d_status, void* hip_stream);
+
 /* ---- (c) template materialization ---------------------------------------------------
  * For every base map m and every output graph g (Section 4.2.1: prepare the parameter
  * sets of the non-template graphs; Section 4.2.2: patch rank-dependent state), in this

@@ -367,7 +367,8 @@ int orc_materialize_brute(const MatArgs* a, uint64_t* out_words, uint64_t out_wo
 // little-endian value of g's blob differs from s's becomes {b, value in g}; ascending b per
 // graph, graphs in order; ovr_off[g] = entries before graph g, ovr_off[G] = total (also when
 // it exceeds `capacity`; then only the first `capacity` entries are stored).
-// -1: a template index out of range, or a graph whose word count differs from its template's.
+// -1: a template index out of range, a graph whose word count differs from its template's,
+// or a graph of 2^29 words or more.
 int orc_derive_overrides(const uint64_t* words, const uint64_t* word_off, uint32_t G,
                          const uint32_t* graph_tmpl, const uint32_t* tmpl_graph, uint32_t T, Ovr32* ovr,
                          uint64_t capacity, uint64_t* ovr_off) {
@@ -379,6 +380,7 @@ int orc_derive_overrides(const uint64_t* words, const uint64_t* word_off, uint32
     if (s >= G) return -1;
     const uint64_t nw = word_off[g + 1] - word_off[g];
     if (word_off[s + 1] - word_off[s] != nw) return -1;
+    if (nw >> 29) return -1;  // byte offsets are 32-bit
     const unsigned char* a = reinterpret_cast<const unsigned char*>(words + word_off[g]);
     const unsigned char* b = reinterpret_cast<const unsigned char*>(words + word_off[s]);
     for (uint64_t off = 0; off < nw * 8; off += 4) {

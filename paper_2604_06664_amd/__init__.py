@@ -71,6 +71,12 @@ def lib():
         L.fdy_fingerprint.restype = C.c_int
         L.fdy_fingerprint.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.fdy_derive_workspace_bytes.restype = C.c_size_t
+        L.fdy_derive_workspace_bytes.argtypes = [C.c_uint64, C.c_uint32]
+        L.fdy_derive_overrides.restype = C.c_int
+        L.fdy_derive_overrides.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p,
+                                           C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p,
+                                           C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.fdy_materialize_workspace_bytes.restype = C.c_size_t
         L.fdy_materialize_workspace_bytes.argtypes = [C.POINTER(fdy_mat_desc)]
         L.fdy_materialize.restype = C.c_int
@@ -169,6 +175,20 @@ def fdy_fingerprint(d_nodes, d_node_off, n_graphs, field_mask, d_keys, d_templat
                                _ptr(d_keys), _ptr(d_template_id), _ptr(d_tmpl_graph),
                                _ptr(d_n_templates), _stream(stream))
     return _check(rc, "fdy_fingerprint") if check else rc
+
+
+def fdy_derive_workspace_bytes(n_words_total, n_graphs):
+    return lib().fdy_derive_workspace_bytes(int(n_words_total), int(n_graphs))
+
+
+def fdy_derive_overrides(d_words, n_words_total, d_word_off, n_graphs, d_graph_tmpl, d_tmpl_graph,
+                         n_templates, d_ovr, ovr_capacity, d_ovr_off, d_workspace, workspace_bytes,
+                         d_status=None, stream=None, check=True):
+    rc = lib().fdy_derive_overrides(_ptr(d_words), int(n_words_total), _ptr(d_word_off), int(n_graphs),
+                                    _ptr(d_graph_tmpl), _ptr(d_tmpl_graph), int(n_templates),
+                                    _ptr(d_ovr), int(ovr_capacity), _ptr(d_ovr_off), _ptr(d_workspace),
+                                    int(workspace_bytes), _ptr(d_status), _stream(stream))
+    return _check(rc, "fdy_derive_overrides") if check else rc
 
 
 def fdy_materialize_workspace_bytes(h_desc):

@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libfdy.so")
-SOURCES = ["fdy_api.hip", "fdy_scan.hip", "fdy_fingerprint.hip", "fdy_materialize.hip"]
+SOURCES = ["fdy_api.hip", "fdy_scan.hip", "fdy_fingerprint.hip", "fdy_materialize.hip", "fdy_derive.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
     "-Wno-unused-parameter",

@@ -65,36 +65,6 @@ struct MatParams {
   u32 map_group;  // consecutive base maps handled by one workgroup of the main kernel
 };
 
-// Exclusive scan of one u64 per thread over a 1024-thread workgroup; returns the exclusive
-// prefix and sets `total` (same in every thread).  s_buf: 17 u64 of LDS.
-__device__ u64 block_excl_scan_1024(u64 v, u64* s_buf, u64& total) {
-  const u32 l = lane_id(), w = threadIdx.x >> 6;
-  u64 inc = v;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const u64 o = __shfl_up(inc, d);
-    if (l >= (u32)d) inc += o;
-  }
-  if (l == 63) s_buf[w] = inc;
-  __syncthreads();
-  if (w == 0) {
-    const u64 x = l < 16 ? s_buf[l] : 0;
-    u64 xi = x;
-#pragma unroll
-    for (int d = 1; d < 16; d <<= 1) {
-      const u64 o = __shfl_up(xi, d);
-      if (l >= (u32)d) xi += o;
-    }
-    if (l < 16) s_buf[l] = xi - x;
-    if (l == 15) s_buf[16] = xi;
-  }
-  __syncthreads();
-  const u64 r = s_buf[w] + inc - v;
-  total = s_buf[16];
-  __syncthreads();
-  return r;
-}
-
 __global__ __launch_bounds__(1024) void mat_prep_graphs_kernel(MatParams p) {
   __shared__ u64 s_buf[17];
   const fdy_mat_desc& d = p.d;

@@ -109,6 +109,30 @@ def fingerprint(nodes, node_off, mask, want_tmpl_graph=True):
     return keys, tid, tg, dict(d_keys=d_keys, d_tid=d_tid, d_tg=d_tg, d_nt=d_nt)
 
 
+def derive_overrides(words, word_off, graph_tmpl, tmpl_graph, capacity=None):
+    """-> (ovr OVR32[min(total, capacity)], ovr_off u64[G+1], status)"""
+    from synth import layout as L
+
+    words = np.ascontiguousarray(words, np.uint64)
+    word_off = np.ascontiguousarray(word_off, np.uint64)
+    gt = np.ascontiguousarray(graph_tmpl, np.uint32)
+    tg = np.ascontiguousarray(tmpl_graph, np.uint32)
+    G, W = len(gt), len(words)
+    cap = 2 * W if capacity is None else int(capacity)
+    d_words, d_off = fdy.to_device(words), fdy.to_device(word_off)
+    d_gt, d_tg = fdy.to_device(gt), fdy.to_device(tg)
+    d_ovr = fdy.device_bytes(cap * 8, fill=0xEE)
+    d_ovr_off = fdy.device_bytes((G + 1) * 8, fill=0xEE)
+    ws_bytes = fdy.fdy_derive_workspace_bytes(W, G)
+    d_ws = fdy.device_bytes(ws_bytes)
+    d_status = _status_tensor()
+    fdy.fdy_derive_overrides(d_words, W, d_off, G, d_gt, d_tg, len(tg), d_ovr, cap, d_ovr_off, d_ws,
+                             ws_bytes, d_status)
+    torch.cuda.synchronize()
+    off = fdy.to_host(d_ovr_off, np.uint64, G + 1)
+    return fdy.to_host(d_ovr, L.OVR32, min(int(off[G]), cap)), off, int(d_status.item())
+
+
 class MatRun:
     """Device-resident inputs, outputs and workspace of one fdy_materialize problem.
     `mp` is a synth.MatProblem (host arrays); `device_overrides` may replace uploaded arrays

@@ -35,7 +35,8 @@ def test_every_declared_symbol_is_exported(fdy):
     names = declared_functions()
     assert {"fdy_scan_pointers", "fdy_fingerprint", "fdy_materialize", "fdy_reloc_segment",
             "fdy_table_validate", "fdy_scan_workspace_bytes", "fdy_materialize_workspace_bytes",
-            "fdy_version", "fdy_strerror", "fdy_scan_rebase"} <= set(names)
+            "fdy_version", "fdy_strerror", "fdy_scan_rebase", "fdy_derive_overrides",
+            "fdy_derive_workspace_bytes"} <= set(names)
     raw = C.CDLL(fdy.LIB_PATH)
     for n in names:
         assert hasattr(raw, n), f"{n} declared in fdy.h but not exported"

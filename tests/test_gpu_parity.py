@@ -199,6 +199,63 @@ def test_scan_argument_errors(hip):
     torch.cuda.synchronize()
 
 
+# --------------------------------------------------------------------- override derivation
+def check_derive(hip, oracle, words, word_off, gt, tg, capacity=None, tag=""):
+    say(f"[derive] {tag} W={len(words)} G={len(gt)} T={len(tg)} cap={capacity}")
+    ref, roff = oracle.derive_overrides(words, word_off, gt, tg, capacity)
+    got, off, status = hip.derive_overrides(words, word_off, gt, tg, capacity)
+    assert np.array_equal(off, roff)
+    assert np.array_equal(got, ref)
+    cap = 2 * len(words) if capacity is None else capacity
+    assert status == (L.ST_CAPACITY if int(roff[-1]) > cap else 0)
+    return got, off
+
+
+def test_derive_overrides_random_and_edge_cases(hip, oracle):
+    from tests.test_oracle_derive import random_case
+
+    rng = np.random.default_rng(19)
+    for k in range(12):
+        G = int(rng.integers(1, 40))
+        T = int(rng.integers(1, G + 1))
+        words, word_off, gt, tg = random_case(rng, G, T, 5000 if k % 3 == 0 else 300)  # several tiles
+        check_derive(hip, oracle, words, word_off, gt, tg, tag=f"random {k}")
+    words, word_off, gt, tg = random_case(rng, 30, 4, 4100)
+    _, off = check_derive(hip, oracle, words, word_off, gt, tg, tag="for capacity")
+    total = int(off[-1])
+    if total > 2:
+        check_derive(hip, oracle, words, word_off, gt, tg, capacity=total // 2, tag="overflow")
+    check_derive(hip, oracle, words, word_off, gt, tg, capacity=0, tag="zero capacity")
+    # every half differs (output twice the number of words), exact tile multiples, empty graphs
+    a = np.arange(4096, dtype=np.uint64) * np.uint64(0x100000001)
+    both = np.concatenate([a, ~a, a[:0], a])
+    check_derive(hip, oracle, both, [0, 4096, 8192, 8192, 8192, 12288], [0, 0, 1, 1, 0], [0, 2], tag="all differ")
+    check_derive(hip, oracle, np.zeros(0, np.uint64), [0], np.zeros(0, np.uint32), np.zeros(0, np.uint32),
+                 tag="no graphs")
+    # bad inputs are flagged, not faulting: template id out of range, sizes that differ
+    got, off, status = hip.derive_overrides(a, [0, 2048, 4096], [0, 7], [0])
+    assert status == L.ST_BAD_INDEX and len(got) == 0 and list(off) == [0, 0, 0]
+    got, off, status = hip.derive_overrides(a, [0, 2048, 4096, 4096], [0, 0, 0], [0])
+    assert status == L.ST_BAD_SIZE and int(off[-1]) == 4096  # graph 2 (empty) skipped, graph 1 compared
+
+
+@pytest.mark.parametrize("idx", [2, 3, 5])
+def test_derive_overrides_archives_and_round_trip(hip, oracle, idx):
+    """Fingerprint -> derive -> materialize under the old bases, all on the GPU, gives back the
+    captured words of every graph: the generator's privileged override lists are not needed."""
+    ar = small(idx)
+    mask = L.FP_ALL & ~L.FP_GRID_X
+    _, tid, tg, _ = hip.fingerprint(ar.nodes, ar.node_off, mask)
+    assert np.array_equal(tid, ar.graph_tmpl) and np.array_equal(tg, ar.tmpl_graph)
+    ovr, off = check_derive(hip, oracle, ar.words, ar.word_off, tid, tg, tag=ar.name)
+    mp = problem(oracle, ar)
+    kw = {n: getattr(mp, n) for n in MatProblem.ARRAYS}
+    kw.update(ovr=ovr, ovr_off=off, new_base=ar.table["base"][None, :].copy(), map_rank=None)
+    mp2 = MatProblem(n_ranks=0, **kw)
+    out, _, status = hip.materialize(mp2, want_dims=False)
+    assert status == 0 and np.array_equal(out[0], ar.words)
+
+
 # ------------------------------------------------------------------- fused scan + rebase
 def oracle_rebase(oracle, words, table, new_base):
     """What fdy_scan_rebase must produce, from the oracle's own scan and materialize: one
