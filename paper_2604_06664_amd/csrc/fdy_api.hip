@@ -5,7 +5,7 @@
 namespace {
 int g_tune[FDY_TUNE_COUNT] = {
     /* SCAN_TOP_LOG2   */ 14,
-    /* SCAN_WG_PER_CU  */ 2,
+    /* SCAN_WG_PER_CU  */ 1,
     /* SCAN_SPIN_LIMIT */ 1 << 20,
     /* MAT_MAP_GROUP     */ 0,
     0, 0, 0, 0};
