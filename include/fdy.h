@@ -41,7 +41,7 @@
 extern "C" {
 #endif
 
-#define FDY_VERSION 100 /* major*10000 + minor*100 + patch */
+#define FDY_VERSION 200 /* major*10000 + minor*100 + patch */
 
 /* ---- return codes ------------------------------------------------------------------ */
 #define FDY_OK 0
@@ -53,11 +53,13 @@ extern "C" {
 #define FDY_ERR_ORDER (-6)       /* a host list is not strictly ascending by location */
 
 /* ---- device status bits (OR-ed into *d_status) ------------------------------------- */
-#define FDY_ST_CAPACITY 0x1u  /* scan: more hits than reloc_capacity; *d_count = needed  */
+#define FDY_ST_CAPACITY 0x1u  /* scan: more hits than reloc_capacity; *d_count = needed
+                                 (derive: more entries than ovr_capacity)               */
 #define FDY_ST_BAD_INDEX 0x2u /* an entry's word/region/node/template index was out of
                                  range and the entry was skipped                        */
 #define FDY_ST_BAD_SIZE 0x4u  /* materialize: out_words_per_map / out_nodes_total do not
-                                 equal the sums the device computed; nothing written     */
+                                 equal the sums the device computed; nothing written
+                                 (derive: a graph and its template differ in length)     */
 #define FDY_ST_SPIN 0x8u      /* scan: a bounded wait on a predecessor tile ran out      */
 
 /* ---- plain-data records ------------------------------------------------------------ */
