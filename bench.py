@@ -24,11 +24,13 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # FETCH_SIZE and WRITE_SIZE (two separate counter runs of this script), each scaled by the
 # reading of a plain 1 GiB device copy in the same run (fetch x2.000, write x1.000).  A
 # counter run cannot happen inside this process; the figures are those of the committed
-# summary profiles/whole_path_config4_hbm_traffic_pmc.txt and are reported only for the
-# workload and kernels they were collected on.
+# summaries profiles/whole_path_config4_hbm_traffic_pmc.txt and
+# profiles/whole_path_config5_kernel_stats_and_traffic.txt and are reported only for the
+# workloads and kernels they were collected on.
 PMC_TRAFFIC_BYTES = {
     (4, "scan_kernel"): 3_014_008_832 + 216_754_688,
     (4, "mat_main_kernel"): 2_605_340_058 + 1_073_878_323,
+    (5, "mat_main_kernel"): 71_212_442 + 1_575_544_832,
 }
 
 
