@@ -293,6 +293,9 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
 #pragma unroll
       for (int h = 0; h < 4; ++h) k[c][h] = *reinterpret_cast<const u64x2*>(&m[n[c] + 2 * h]);
     }
+    // every chain's node is requested before the first one is looked at (left to itself the
+    // scheduler sinks each chain's loads next to their use and the round trips line up)
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int c = 0; c < N; ++c) {
       u32 at = 0;
@@ -321,14 +324,20 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
 #pragma unroll
     for (int c = 0; c < N; ++c) e[c] = *reinterpret_cast<const u64x2*>(&p.table[n[c]]);
   } else {
+    uint4 ql[N][4];
+    if (p.leaf) {
+#pragma unroll
+      for (int c = 0; c < N; ++c) {
+#pragma unroll
+        for (int h = 0; h < 4; ++h) ql[c][h] = p.leaf[n[c] * 4 + h];
+      }
+      __builtin_amdgcn_sched_barrier(0);  // every chain's line is requested before the first is used
+    }
 #pragma unroll
     for (int c = 0; c < N; ++c) {
       bool exact = true;
       if (p.leaf) {
-        const uint4* line = p.leaf + n[c] * 4;
-        uint4 q[4];
-#pragma unroll
-        for (int h = 0; h < 4; ++h) q[h] = line[h];
+        const uint4 (&q)[4] = ql[c];
         if (q[0].x != 0xffffffffu) {
           exact = false;
           const u64 x = w[c] - gb[c];
