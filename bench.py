@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # profiles/whole_path_config5_kernel_stats_and_traffic.txt and are reported only for the
 # workloads and kernels they were collected on.
 PMC_TRAFFIC_BYTES = {
-    (4, "scan_kernel"): 3_014_008_832 + 216_754_688,
-    (4, "mat_main_kernel"): 2_605_340_058 + 1_073_878_323,
+    (4, "scan_kernel"): 2_977_627_215 + 216_750_853,
+    (4, "mat_main_kernel"): 2_605_316_919 + 1_073_902_976,
     (5, "mat_main_kernel"): 71_212_442 + 1_575_544_832,
 }
 
