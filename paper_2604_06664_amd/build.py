@@ -9,7 +9,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libfdy.so")
-SOURCES = ["fdy_api.hip", "fdy_scan.hip", "fdy_fingerprint.hip", "fdy_materialize.hip", "fdy_derive.hip"]
+SOURCES = ["fdy_api.hip", "fdy_scan.hip", "fdy_fingerprint.hip", "fdy_materialize.hip", "fdy_derive.hip",
+           "fdy_arena.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
     "-Wno-unused-parameter",
@@ -31,7 +32,8 @@ def build_lib(verbose=False):
     return LIB
 
 
-TOY_SRC = [os.path.join(ROOT, "tests", "toy_graph", f) for f in ("toy_graph.hip", "install_scale.hip")]
+TOY_SRC = [os.path.join(ROOT, "tests", "toy_graph", f) for f in ("toy_graph.hip", "install_scale.hip",
+                                                                "arena_graph.hip")]
 TOY_LIB = os.path.join(ROOT, "tests", "toy_graph", "libtoy_graph.so")
 
 

@@ -26,9 +26,14 @@ def fdy():
 
 
 def declared_functions():
-    src = open(os.path.join(ROOT, "include", "fdy.h")).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(fdy_[a-z_0-9]+)\s*\(", src)))
+    """Every function declared by a header under include/."""
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for h in sorted(os.listdir(inc)):
+        if h.endswith(".h"):
+            src = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, h)).read(), flags=re.S)
+            names |= set(re.findall(r"\b(fdy_[a-z_0-9]+)\s*\(", src))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(fdy):
@@ -36,7 +41,8 @@ def test_every_declared_symbol_is_exported(fdy):
     assert {"fdy_scan_pointers", "fdy_fingerprint", "fdy_materialize", "fdy_reloc_segment",
             "fdy_table_validate", "fdy_scan_workspace_bytes", "fdy_materialize_workspace_bytes",
             "fdy_version", "fdy_strerror", "fdy_scan_rebase", "fdy_derive_overrides",
-            "fdy_derive_workspace_bytes"} <= set(names)
+            "fdy_derive_workspace_bytes", "fdy_arena_create", "fdy_arena_alloc", "fdy_arena_table",
+            "fdy_arena_destroy"} <= set(names)
     raw = C.CDLL(fdy.LIB_PATH)
     for n in names:
         assert hasattr(raw, n), f"{n} declared in fdy.h but not exported"

@@ -60,3 +60,24 @@ def test_install_at_decode_graph_scale():
     if os.path.isdir(out):
         with open(os.path.join(out, "install_scale.txt"), "w") as f:
             f.write(msg.value.decode() + "\n" + " ".join(f"{v:.4f}" for v in stats) + "\n")
+
+
+def test_deterministic_arenas_end_to_end():
+    """Two arenas of the deterministic allocator replay one allocation sequence at different
+    bases; a graph built on the first is rebased for the second in one pass and replayed."""
+    import torch
+
+    assert torch.cuda.is_available()
+    assert os.path.exists(LIB), "build it first: python -c 'import __graft_entry__ as g; g.build()'"
+    import paper_2604_06664_amd as fdy
+
+    fdy.lib()
+    C.CDLL(fdy.LIB_PATH, mode=C.RTLD_GLOBAL)
+    toy = C.CDLL(LIB)
+    toy.arena_graph_check.restype = C.c_int
+    toy.arena_graph_check.argtypes = [C.c_char_p, C.c_int]
+    msg = C.create_string_buffer(1024)
+    print("[arena] two arenas, rebase, replay", flush=True)
+    rc = toy.arena_graph_check(msg, 1024)
+    print("[arena]", msg.value.decode(), flush=True)
+    assert rc == 0, msg.value.decode()
