@@ -17,12 +17,17 @@ from synth.problem import MatProblem
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "fdy_oracle.cpp")
-_LIB = os.path.join(_DIR, "libfdy_oracle.so")
+# FDY_ORACLE_LIB: load this prebuilt library instead (the mutation test points it at copies of
+# the oracle with a planted mistake, to show that the pins notice)
+_ALT = os.environ.get("FDY_ORACLE_LIB")
+_LIB = _ALT or os.path.join(_DIR, "libfdy_oracle.so")
 _lib = None
 
 
 def build(force=False):
     """Compile the oracle with the host compiler (no GPU toolchain involved)."""
+    if _ALT:
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
             ["g++", "-std=c++17", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared", _SRC, "-o", _LIB])
