@@ -129,26 +129,40 @@ __device__ __forceinline__ u32 lane_lower_bound(KeyFn key, u32 lo, u32 hi, u64 t
   return lo;
 }
 
-// One thread per output tile (independent of the base map).
-__global__ __launch_bounds__(256) void mat_prep_tiles_kernel(MatParams p) {
+// Where tile j (j < n_tiles) lies: its graph, template, source graph, first word inside the
+// graph, word count, first source word.
+struct TileGeom {
+  u32 g, t, s, n;
+  u64 k0, src_word;
+};
+__device__ __forceinline__ TileGeom tile_geometry(const MatParams& p, u32 j) {
   const fdy_mat_desc& d = p.d;
-  const u32 j = blockIdx.x * 256 + threadIdx.x;
+  const u64* tile_off = p.ws.tile_off;
+  TileGeom q;
+  // largest g with tile_off[g] <= j
+  q.g = lane_lower_bound([&](u32 i) { return tile_off[i]; }, 0u, d.n_graphs + 1u, (u64)j + 1) - 1;
+  q.t = d.graph_tmpl[q.g];
+  q.s = d.tmpl_graph[q.t];  // valid: graphs with a bad template have no tiles
+  const u64 w0 = d.src_word_off[q.s];
+  const u64 nw = d.src_word_off[q.s + 1] - w0;
+  q.k0 = ((u64)j - tile_off[q.g]) * kMatTile;
+  q.n = (u32)((nw - q.k0) < (u64)kMatTile ? (nw - q.k0) : (u64)kMatTile);
+  q.src_word = w0 + q.k0;
+  return q;
+}
+
+// Thread j: output tile j (independent of the base map).
+__device__ __forceinline__ void prep_tile(const MatParams& p, u32 j) {
+  const fdy_mat_desc& d = p.d;
   if (j >= p.ws.max_tiles) return;
   MatTile* ent = &p.ws.tiles[j];
   if (j >= p.ws.hdr->n_tiles) {
     ent->n_words = 0;
     return;
   }
-  const u64* tile_off = p.ws.tile_off;
-  // largest g with tile_off[g] <= j
-  const u32 g = lane_lower_bound([&](u32 i) { return tile_off[i]; }, 0u, d.n_graphs + 1u, (u64)j + 1) - 1;
-  const u32 t = d.graph_tmpl[g];
-  const u32 s = d.tmpl_graph[t];  // valid: graphs with a bad template have no tiles
-  const u64 w0 = d.src_word_off[s];
-  const u64 nw = d.src_word_off[s + 1] - w0;
-  const u64 k0 = ((u64)j - tile_off[g]) * kMatTile;
-  const u32 n = (u32)((nw - k0) < (u64)kMatTile ? (nw - k0) : (u64)kMatTile);
-  const u64 src_word = w0 + k0;
+  const TileGeom q = tile_geometry(p, j);
+  const u32 g = q.g, t = q.t, s = q.s, n = q.n;
+  const u64 k0 = q.k0, src_word = q.src_word;
   const fdy_reloc* relocs = d.relocs;
   const u32 rl0 = (u32)d.src_reloc_off[s], rl1 = (u32)d.src_reloc_off[s + 1];
   const u32 reloc_lo = lane_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, rl0, rl1, src_word);
@@ -176,20 +190,19 @@ __global__ __launch_bounds__(256) void mat_prep_tiles_kernel(MatParams p) {
   *ent = e;
 }
 
-// One thread per (output tile, rank): the slice of the rank's patch list inside the tile.
-__global__ __launch_bounds__(256) void mat_prep_patch_kernel(MatParams p) {
+// Thread i: (output tile, rank) pair i: the slice of the rank's patch list inside the tile.
+// Works from the tile's geometry, not from the tile table, which the same launch is writing.
+__device__ __forceinline__ void prep_patch(const MatParams& p, u64 i) {
   const fdy_mat_desc& d = p.d;
-  const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;
   const u32 R = d.n_ranks;
   if (i >= (u64)p.ws.hdr->n_tiles * R) return;
   const u32 j = (u32)(i / R), r = (u32)(i % R);
-  const MatTile& e = p.ws.tiles[j];
+  const TileGeom e = tile_geometry(p, j);
   const fdy_patch* patch = d.patch;
-  const u64 row = (u64)e.tmpl * R + r;
+  const u64 row = (u64)e.t * R + r;
   const u32 p0 = (u32)d.patch_off[row], p1 = (u32)d.patch_off[row + 1];
-  const u32 lo = lane_lower_bound([&](u32 q) { return (u64)patch[q].word; }, p0, p1, (u64)e.k0);
-  const u32 hi =
-      lane_lower_bound([&](u32 q) { return (u64)patch[q].word; }, lo, p1, (u64)e.k0 + e.n_words);
+  const u32 lo = lane_lower_bound([&](u32 q) { return (u64)patch[q].word; }, p0, p1, e.k0);
+  const u32 hi = lane_lower_bound([&](u32 q) { return (u64)patch[q].word; }, lo, p1, e.k0 + e.n);
   p.ws.tile_patch[i] = make_uint2(lo, hi);
 }
 
@@ -324,10 +337,10 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
   if (bad) raise_status(p.d_status, FDY_ST_BAD_INDEX);
 }
 
-__global__ __launch_bounds__(256) void mat_dims_kernel(MatParams p) {
+// Thread i: launch dimensions of output node i.
+__device__ __forceinline__ void write_dims(const MatParams& p, u64 i) {
   const fdy_mat_desc& d = p.d;
   if (!p.ws.hdr->ok) return;
-  const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;
   if (i >= d.out_nodes_total) return;
   // largest g with out_node_off[g] <= i
   const u64* off = p.ws.out_node_off;
@@ -358,6 +371,16 @@ __global__ __launch_bounds__(256) void mat_dims_kernel(MatParams p) {
   o[0] = make_uint2(gx, gy);
   o[1] = make_uint2(gz, nd.block[0]);
   o[2] = make_uint2(nd.block[1], nd.block[2]);
+}
+
+// Everything that only needs the per-graph prefix sums, in one launch (these are small and
+// launch-bound: three launches cost three times one): blocks [0, nb_tiles) resolve tiles,
+// the next nb_patch blocks the (tile, rank) patch slices, the rest write launch dimensions.
+__global__ __launch_bounds__(256) void mat_prep_tiles_kernel(MatParams p, u32 nb_tiles, u32 nb_patch) {
+  const u32 b = blockIdx.x;
+  if (b < nb_tiles) prep_tile(p, b * 256 + threadIdx.x);
+  else if (b < nb_tiles + nb_patch) prep_patch(p, (u64)(b - nb_tiles) * 256 + threadIdx.x);
+  else write_dims(p, (u64)(b - nb_tiles - nb_patch) * 256 + threadIdx.x);
 }
 
 bool desc_ok(const fdy_mat_desc* d) {
@@ -437,15 +460,17 @@ extern "C" int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words
   hipLaunchKernelGGL(mat_prep_graphs_kernel, dim3(1), dim3(1024), 0, stream, p);
   prof_end(FDY_PROF_MAT_PREP_GRAPHS, stream);
   FDY_HIP_TRY(hipGetLastError());
-  if (p.ws.max_tiles) {
+  const u32 nb_tiles = (p.ws.max_tiles + 255) / 256;
+  const u32 nb_patch = p.d.map_rank ? (u32)(((u64)p.ws.max_tiles * p.d.n_ranks + 255) / 256) : 0;
+  const u32 nb_dims = (d_out_dims && d.out_nodes_total) ? (u32)((d.out_nodes_total + 255) / 256) : 0;
+  if (nb_tiles + nb_patch + nb_dims) {
     prof_begin(FDY_PROF_MAT_PREP_TILES, stream);
-    hipLaunchKernelGGL(mat_prep_tiles_kernel, dim3((p.ws.max_tiles + 255) / 256), dim3(256), 0, stream, p);
-    if (p.d.map_rank) {
-      const u64 n_pairs = (u64)p.ws.max_tiles * p.d.n_ranks;
-      hipLaunchKernelGGL(mat_prep_patch_kernel, dim3((u32)((n_pairs + 255) / 256)), dim3(256), 0, stream, p);
-    }
+    hipLaunchKernelGGL(mat_prep_tiles_kernel, dim3(nb_tiles + nb_patch + nb_dims), dim3(256), 0, stream, p,
+                       nb_tiles, nb_patch);
     prof_end(FDY_PROF_MAT_PREP_TILES, stream);
     FDY_HIP_TRY(hipGetLastError());
+  }
+  if (p.ws.max_tiles) {
     prof_begin(FDY_PROF_MAT_MAIN, stream);
     // Base maps per workgroup.  Measured on MI355X, groups above 2 (4 with rank patches, where
     // the tile is staged again per map anyway) lose more to the coarser tail of the launch
@@ -456,13 +481,6 @@ extern "C" int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words
     const u32 n_groups = (d.n_maps + p.map_group - 1) / p.map_group;
     hipLaunchKernelGGL(mat_main_kernel, dim3(p.ws.max_tiles, n_groups), dim3(kMatBlock), 0, stream, p);
     prof_end(FDY_PROF_MAT_MAIN, stream);
-    FDY_HIP_TRY(hipGetLastError());
-  }
-  if (d_out_dims && d.out_nodes_total) {
-    prof_begin(FDY_PROF_MAT_DIMS, stream);
-    hipLaunchKernelGGL(mat_dims_kernel, dim3((u32)((d.out_nodes_total + 255) / 256)), dim3(256), 0,
-                       stream, p);
-    prof_end(FDY_PROF_MAT_DIMS, stream);
     FDY_HIP_TRY(hipGetLastError());
   }
   return FDY_OK;
