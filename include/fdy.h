@@ -42,7 +42,7 @@
 extern "C" {
 #endif
 
-#define FDY_VERSION 200 /* major*10000 + minor*100 + patch */
+#define FDY_VERSION 300 /* major*10000 + minor*100 + patch */
 
 /* ---- return codes ------------------------------------------------------------------ */
 #define FDY_OK 0
@@ -52,6 +52,10 @@ extern "C" {
 #define FDY_ERR_HIP (-4)         /* a HIP call or kernel launch failed                */
 #define FDY_ERR_WORKSPACE (-5)   /* workspace pointer null, misaligned or too small   */
 #define FDY_ERR_ORDER (-6)       /* a host list is not strictly ascending by location */
+#define FDY_ERR_IO (-7)          /* fdy_archive.h: a file could not be opened, mapped, written */
+#define FDY_ERR_FORMAT (-8)      /* fdy_archive.h: not an archive, or a damaged container       */
+#define FDY_ERR_CHECKSUM (-9)    /* fdy_archive.h: a stored sum does not match the bytes        */
+#define FDY_ERR_CONTENT (-10)    /* fdy_archive.h: the sections contradict each other           */
 
 /* ---- device status bits (OR-ed into *d_status) ------------------------------------- */
 #define FDY_ST_CAPACITY 0x1u  /* scan: more hits than reloc_capacity; *d_count = needed

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libfdy.so")
 SOURCES = ["fdy_api.hip", "fdy_scan.hip", "fdy_fingerprint.hip", "fdy_materialize.hip", "fdy_derive.hip",
-           "fdy_arena.hip"]
+           "fdy_arena.hip", "fdy_archive.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
     "-Wno-unused-parameter",

@@ -36,6 +36,10 @@ extern "C" const char* fdy_strerror(int code) {
     case FDY_ERR_HIP: return "a HIP call or kernel launch failed";
     case FDY_ERR_WORKSPACE: return "workspace is null, misaligned or too small";
     case FDY_ERR_ORDER: return "a list is not strictly ascending by location";
+    case FDY_ERR_IO: return "a file could not be opened, mapped or written";
+    case FDY_ERR_FORMAT: return "not an archive, or a damaged container";
+    case FDY_ERR_CHECKSUM: return "a stored sum does not match the bytes";
+    case FDY_ERR_CONTENT: return "the sections of the archive contradict each other";
     default: return "unknown fdy error code";
   }
 }
@@ -132,7 +136,7 @@ extern "C" int fdy__prof_read(int slot, int* n_records, float* total_ms, float* 
 extern "C" const char* fdy__prof_name(int slot) {
   static const char* names[FDY_PROF_SLOTS] = {
       "scan_kernel", "scan_init_kernel", "reloc_segment_kernel", "fp_key_kernel", "fp_group_kernel",
-      "mat_prep_graphs_kernel", "mat_prep_tiles_kernel", "mat_main_kernel", "mat_dims_kernel",
+      "mat_prep_graphs_kernel", "mat_prep_tiles_kernel", "mat_main_kernel", "(unused)",
       "scan_rebase_kernel"};
   return slot >= 0 && slot < FDY_PROF_SLOTS ? names[slot] : "?";
 }

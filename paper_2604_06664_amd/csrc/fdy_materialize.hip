@@ -7,13 +7,17 @@
 //
 //   prep A (one workgroup)   prefix sums over the output graphs: where each graph's words,
 //                            nodes and tiles start; verifies the caller's totals.
-//   prep B (one thread/tile) resolves each output tile once, independent of the base map:
+//   prep B (one launch)      three kinds of blocks side by side.  Tile blocks (one thread per
+//                            tile) resolve each output tile once, independent of the base map:
 //                            its graph, template, source words, and the sub-ranges of the
 //                            template's relocation list and the graph's override list that
-//                            fall inside the tile; prep C (one thread per tile and rank) does
-//                            the same for each rank's patch list.  Plain per-lane binary
-//                            searches: tens of thousands of them run side by side, and one
-//                            request per halving is what the memory system serves best.
+//                            fall inside the tile.  Patch blocks (one thread per tile and rank)
+//                            do the same for each rank's patch list.  Dims blocks (one thread
+//                            per node) write the launch dimensions of the template with the
+//                            graph's grid overrides.  Plain per-lane binary searches: tens of
+//                            thousands of them run side by side, and one request per halving is
+//                            what the memory system serves best.  One launch rather than three
+//                            because small archives are bound by launch latency.
 //   main  (tile x map group) stages the template tile in LDS and the tile's relocation entries
 //                            in registers once, then per base map of its group scatters c2
 //                            rebased pointers (new_base[m][region] + offset), c3 32-bit
@@ -21,7 +25,6 @@
 //                            streams the tile out with coalesced stores.  Templates,
 //                            relocation lists and base maps are re-read per group from L2 /
 //                            Infinity Cache; only the output is compulsory HBM traffic.
-//   dims  (one thread / node) launch dimensions of the template with grid overrides.
 #include "fdy_device.hpp"
 #include "fdy_tune.h"
 

@@ -49,7 +49,7 @@ def test_every_declared_symbol_is_exported(fdy):
 
 
 def test_version_and_error_strings(fdy):
-    assert fdy.fdy_version() == 200
+    assert fdy.fdy_version() == 300
     for code in range(0, -7, -1):
         assert fdy.fdy_strerror(code) not in ("", "unknown fdy error code")
     assert fdy.fdy_strerror(-99) == "unknown fdy error code"
