@@ -146,6 +146,22 @@ const char* fdy_strerror(int code);
  * An empty table (n_alloc == 0) is valid: nothing is a pointer. */
 int fdy_table_validate(const fdy_alloc* h_table, uint32_t n_alloc, uint32_t* h_bad_index);
 
+/* Inverse of a base map (host).  A base map places region r of `h_table` at h_new_base[r];
+ * the relaxation of Section 4.1.1 works in both directions: blobs that hold pointers into
+ * the NEW layout are taken back to the captured one (or classified against the new layout)
+ * by running the same scan with the new layout as its table.  This call builds that table:
+ *   h_inv_table[k]  = {h_new_base[r_k], size of region r_k}, ascending by new base
+ *   h_inv_base[k]   = captured base of region r_k      (the base map of the way back)
+ *   h_inv_region[k] = r_k                               (may be NULL)
+ * so that fdy_scan_rebase(words, h_inv_table, h_inv_base) undoes
+ * fdy_scan_rebase(words, h_table, h_new_base) on every pointer, and fdy_scan_pointers over
+ * h_inv_table reports region k for captured region r_k.  All arrays are HOST memory of
+ * n_alloc entries, outputs distinct from inputs.  FDY_ERR_INVALID_ARG: a null pointer with
+ * n_alloc > 0; FDY_ERR_TABLE: h_table is not valid, or the regions overlap or wrap in the new
+ * layout (then the way back is not a function; outputs are unspecified). */
+int fdy_layout_invert(const fdy_alloc* h_table, const uint64_t* h_new_base, uint32_t n_alloc,
+                      fdy_alloc* h_inv_table, uint64_t* h_inv_base, uint32_t* h_inv_region);
+
 /* ---- (a1) pointer scan -------------------------------------------------------------
  * Classifies every 8-byte word of d_words against the allocation table and emits the
  * relocation table (Section 4.1.1 and Section 2.2 give the need; the paper itself avoids

@@ -73,6 +73,22 @@ def table_validate(table):
     return rc, bad.value
 
 
+def layout_invert(table, new_base):
+    """Inverse of a base map: the new layout as a table sorted by new base, the captured bases
+    in that order, and which captured region each entry is.  Returns None if regions overlap
+    or wrap at their new places (plain Python integers; definition written out)."""
+    t = _c(table, L.ALLOC)
+    placed = sorted((int(nb), int(sz), int(ob), r)
+                    for r, (nb, sz, ob) in enumerate(zip(new_base, t["size"], t["base"])))
+    for k, (nb, sz, _, _) in enumerate(placed):
+        if sz < 1 or nb + sz >= 1 << 64 or (k and nb < placed[k - 1][0] + placed[k - 1][1]):
+            return None
+    inv = np.zeros(len(placed), L.ALLOC)
+    inv["base"] = [p[0] for p in placed]
+    inv["size"] = [p[1] for p in placed]
+    return inv, np.array([p[2] for p in placed], np.uint64), np.array([p[3] for p in placed], np.uint32)
+
+
 def _scan(fn, words, table, capacity=None):
     w = _c(words, np.uint64)
     t = _c(table, L.ALLOC)

@@ -5,7 +5,8 @@ supplies device memory and streams.  There is no CPU fallback: if the built libr
 missing, importing the binding functions raises.
 
 Entry points keep the names of include/fdy.h: fdy_scan_pointers, fdy_scan_rebase,
-fdy_reloc_segment, fdy_fingerprint, fdy_materialize (+ workspace queries, fdy_table_validate, fdy_strerror).
+fdy_reloc_segment, fdy_fingerprint, fdy_derive_overrides, fdy_materialize (+ workspace queries,
+fdy_table_validate, fdy_layout_invert, fdy_strerror); include/fdy_archive.h is bound in archive.py.
 """
 from __future__ import annotations
 
@@ -55,6 +56,8 @@ def lib():
         L.fdy_strerror.argtypes = [C.c_int]
         L.fdy_table_validate.restype = C.c_int
         L.fdy_table_validate.argtypes = [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32)]
+        L.fdy_layout_invert.restype = C.c_int
+        L.fdy_layout_invert.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.fdy_scan_workspace_bytes.restype = C.c_size_t
         L.fdy_scan_workspace_bytes.argtypes = [C.c_uint64, C.c_uint32]
         L.fdy_scan_pointers.restype = C.c_int
@@ -139,6 +142,21 @@ def fdy_table_validate(h_table):
     bad = C.c_uint32(0xFFFFFFFF)
     rc = lib().fdy_table_validate(t.ctypes.data if len(t) else None, len(t), C.byref(bad))
     return rc, bad.value
+
+
+def fdy_layout_invert(h_table, h_new_base, check=True):
+    """h_table: fdy_alloc records, h_new_base: uint64 per region (host numpy arrays) ->
+    (rc, inv_table, inv_base, inv_region) as new host arrays."""
+    t = np.ascontiguousarray(h_table)
+    nb = np.ascontiguousarray(h_new_base, np.uint64)
+    assert t.dtype.itemsize == 16 and len(nb) == len(t)
+    inv_t, inv_b, inv_r = np.zeros_like(t), np.zeros(len(t), np.uint64), np.zeros(len(t), np.uint32)
+    rc = lib().fdy_layout_invert(_ptr(t) if len(t) else None, _ptr(nb) if len(t) else None, len(t),
+                                 _ptr(inv_t) if len(t) else None, _ptr(inv_b) if len(t) else None,
+                                 _ptr(inv_r) if len(t) else None)
+    if check:
+        _check(rc, "fdy_layout_invert")
+    return rc, inv_t, inv_b, inv_r
 
 
 def fdy_scan_workspace_bytes(n_words, n_alloc):

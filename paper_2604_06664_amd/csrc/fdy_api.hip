@@ -1,4 +1,8 @@
-// fdy_api.hip - version, error strings, host-side table validation, tuning knobs.
+// fdy_api.hip - version, error strings, host-side table validation and layout inversion,
+// tuning knobs.
+#include <algorithm>
+#include <vector>
+
 #include "fdy_device.hpp"
 #include "fdy_tune.h"
 
@@ -62,8 +66,28 @@ extern "C" int fdy_table_validate(const fdy_alloc* h_table, uint32_t n_alloc, ui
   return FDY_OK;
 }
 
+extern "C" int fdy_layout_invert(const fdy_alloc* h_table, const uint64_t* h_new_base, uint32_t n_alloc,
+                                 fdy_alloc* h_inv_table, uint64_t* h_inv_base, uint32_t* h_inv_region) {
+  if (n_alloc == 0) return FDY_OK;
+  if (!h_table || !h_new_base || !h_inv_table || !h_inv_base) return FDY_ERR_INVALID_ARG;
+  if (fdy_table_validate(h_table, n_alloc, nullptr) != FDY_OK) return FDY_ERR_TABLE;
+  std::vector<uint32_t> order(n_alloc);
+  for (uint32_t r = 0; r < n_alloc; ++r) order[r] = r;
+  std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+    return h_new_base[a] != h_new_base[b] ? h_new_base[a] < h_new_base[b] : a < b;
+  });
+  for (uint32_t k = 0; k < n_alloc; ++k) {
+    const uint32_t r = order[k];
+    h_inv_table[k].base = h_new_base[r];
+    h_inv_table[k].size = h_table[r].size;
+    h_inv_base[k] = h_table[r].base;
+    if (h_inv_region) h_inv_region[k] = r;
+  }
+  // disjoint and non-wrapping in the new layout, or there is no way back
+  return fdy_table_validate(h_inv_table, n_alloc, nullptr) == FDY_OK ? FDY_OK : FDY_ERR_TABLE;
+}
+
 // ---- per-kernel event timing (bench support) -------------------------------------------
-#include <vector>
 namespace {
 struct ProfSlot {
   std::vector<hipEvent_t> a, b;

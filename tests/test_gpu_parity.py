@@ -327,6 +327,35 @@ def test_scan_rebase_edge_cases(hip, oracle):
     assert rc == fdy.FDY_ERR_INVALID_ARG
 
 
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_scan_rebase_there_and_back(hip, oracle, idx):
+    """Rebase into a new layout, then back through the inverted layout (fdy_layout_invert): the
+    second pass equals the oracle's rebase of the first pass's output, and every planted
+    pointer is its captured value again."""
+    import paper_2604_06664_amd as fdy
+
+    ar = small(idx)
+    nb = ar.new_base[0]
+    there, cnt, status = hip.scan_rebase(ar.words, ar.table, nb)
+    assert status == 0 and cnt == len(ar.ptr_word)
+    rc, inv_t, inv_b, inv_r = fdy.fdy_layout_invert(ar.table, nb)
+    want = oracle.layout_invert(ar.table, nb)
+    assert np.array_equal(inv_t, want[0]) and np.array_equal(inv_b, want[1])
+    say(f"[scan_rebase] {ar.name} back through the inverted layout, A={len(inv_t)}")
+    back, cnt_back, status = hip.scan_rebase(there, inv_t, inv_b)
+    ref, rcnt = oracle_rebase(oracle, there, inv_t, inv_b)
+    assert status == 0 and cnt_back == rcnt and np.array_equal(back, ref)
+    assert cnt_back >= cnt  # every moved pointer is found again (plus words that happen to lie there)
+    assert np.array_equal(back[ar.ptr_word], ar.words[ar.ptr_word])
+    # relocations of the new layout name the captured regions through inv_region
+    relocs, n, status = hip.scan(there, inv_t)
+    assert status == 0 and n == cnt_back
+    at = np.searchsorted(relocs["word"], ar.ptr_word)
+    assert np.array_equal(relocs["word"][at], ar.ptr_word.astype(np.uint32))
+    assert np.array_equal(inv_r[relocs["region"][at]], ar.ptr_region)
+    assert np.array_equal(relocs["offset"][at], ar.ptr_offset)
+
+
 def test_reloc_segment(hip, oracle):
     ar = small(2)
     run = hip.ScanRun(ar.words, ar.table)
