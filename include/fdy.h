@@ -210,6 +210,22 @@ int fdy_scan_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* 
                     uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
                     uint32_t* d_status, void* hip_stream);
 
+/* Variant of fdy_scan_pointers for pointers at 4-byte alignment (argument buffers are opaque
+ * byte strings, Section 2.2 / Appendix B: a packed structure may hold a pointer at any
+ * 4-byte offset).  The array is read as n_units 32-bit little-endian units; position q
+ * (0 <= q < n_units - 1) stands for the 64-bit value whose low half is unit q and whose high
+ * half is unit q + 1, and every position is classified like a word of fdy_scan_pointers.
+ * Relocations come out ascending by position, reloc.word = q (so an 8-byte-aligned pointer
+ * at word j appears as q = 2 j, and the call finds a superset of what fdy_scan_pointers finds
+ * on the same bytes).  d_units must be 16-byte aligned; n_units - 1 <= 2^32 - 257; the
+ * workspace is sized by fdy_scan_workspace_bytes(n_units, n_alloc).  Arguments, errors and
+ * status bits otherwise as for fdy_scan_pointers.  Reads the array once (each unit serves
+ * two positions) and writes the relocation table once. */
+int fdy_scan_pointers_stride4(const uint32_t* d_units, uint64_t n_units, const fdy_alloc* d_table,
+                              uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
+                              uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
+                              uint32_t* d_status, void* hip_stream);
+
 /* ---- (a2) relocation segmentation ---------------------------------------------------
  * For each boundary d_word_off[s], s in [0, n_off): d_reloc_off[s] = number of entries of
  * d_relocs[0, min(*d_count, reloc_capacity)) whose word is < d_word_off[s] (lower bound in

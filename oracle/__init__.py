@@ -110,6 +110,19 @@ def scan_brute(words, table, capacity=None):
     return _scan(lib().orc_scan_brute, words, table, capacity)
 
 
+def scan_stride4(units, table, capacity=None):
+    """units: uint32 array.  -> (relocs RELOC[min(count,capacity)] with word = position, count)"""
+    u = _c(units, np.uint32)
+    t = _c(table, L.ALLOC)
+    cap = max(len(u) - 1, 0) if capacity is None else int(capacity)
+    out = np.zeros(cap, L.RELOC)
+    cnt = C.c_uint64(0)
+    rc = lib().orc_scan_stride4(_p(u), C.c_uint64(len(u)), _p(t), C.c_uint32(len(t)), _p(out), C.c_uint64(cap),
+                                C.byref(cnt))
+    assert rc == 0
+    return out[: min(cnt.value, cap)].copy(), cnt.value
+
+
 def reloc_segment(relocs, word_off):
     r = _c(relocs, L.RELOC)
     wo = _c(word_off, np.uint64)

@@ -154,6 +154,17 @@ int orc_scan_brute(const uint64_t* words, uint64_t n_words, const Alloc* table, 
   return 0;
 }
 
+// Scan at 4-byte stride (variant for pointers at 4-byte alignment; argument buffers are
+// opaque bytes, Section 2.2 / Appendix B): the array is n_units 32-bit little-endian units,
+// position q in [0, n_units - 1) is the value unit[q] + 2^32 * unit[q + 1], classified as in
+// orc_scan; reloc.word = q.  The values are written out one by one and handed to orc_scan.
+int orc_scan_stride4(const uint32_t* units, uint64_t n_units, const Alloc* table, uint32_t n_alloc,
+                     Reloc* relocs, uint64_t capacity, uint64_t* count) {
+  std::vector<uint64_t> value(n_units ? n_units - 1 : 0);
+  for (uint64_t q = 0; q + 1 < n_units; ++q) value[q] = (uint64_t)units[q] | ((uint64_t)units[q + 1] << 32);
+  return orc_scan(value.data(), value.size(), table, n_alloc, relocs, capacity, count);
+}
+
 // out[s] = number of relocs (of the first n_relocs) with word < word_off[s].
 int orc_reloc_segment(const Reloc* relocs, uint64_t n_relocs, const uint64_t* word_off,
                       uint32_t n_off, uint64_t* out) {

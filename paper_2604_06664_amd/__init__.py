@@ -4,7 +4,7 @@ Argument marshalling only: every step of the path runs in the library's kernels.
 supplies device memory and streams.  There is no CPU fallback: if the built library is
 missing, importing the binding functions raises.
 
-Entry points keep the names of include/fdy.h: fdy_scan_pointers, fdy_scan_rebase,
+Entry points keep the names of include/fdy.h: fdy_scan_pointers, fdy_scan_pointers_stride4, fdy_scan_rebase,
 fdy_reloc_segment, fdy_fingerprint, fdy_derive_overrides, fdy_materialize (+ workspace queries,
 fdy_table_validate, fdy_layout_invert, fdy_strerror); include/fdy_archive.h is bound in archive.py.
 """
@@ -64,6 +64,8 @@ def lib():
         L.fdy_scan_pointers.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p,
                                         C.c_uint64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
                                         C.c_void_p]
+        L.fdy_scan_pointers_stride4.restype = C.c_int
+        L.fdy_scan_pointers_stride4.argtypes = L.fdy_scan_pointers.argtypes
         L.fdy_scan_rebase.restype = C.c_int
         L.fdy_scan_rebase.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
@@ -170,6 +172,15 @@ def fdy_scan_pointers(d_words, n_words, d_table, n_alloc, d_relocs, reloc_capaci
                                  _ptr(d_workspace), int(workspace_bytes), _ptr(d_status),
                                  _stream(stream))
     return _check(rc, "fdy_scan_pointers") if check else rc
+
+
+def fdy_scan_pointers_stride4(d_units, n_units, d_table, n_alloc, d_relocs, reloc_capacity, d_count,
+                              d_workspace, workspace_bytes, d_status=None, stream=None, check=True):
+    rc = lib().fdy_scan_pointers_stride4(_ptr(d_units), int(n_units), _ptr(d_table), int(n_alloc),
+                                         _ptr(d_relocs), int(reloc_capacity), _ptr(d_count),
+                                         _ptr(d_workspace), int(workspace_bytes), _ptr(d_status),
+                                         _stream(stream))
+    return _check(rc, "fdy_scan_pointers_stride4") if check else rc
 
 
 def fdy_scan_rebase(d_words, n_words, d_table, n_alloc, d_new_base, d_out_words, d_count,

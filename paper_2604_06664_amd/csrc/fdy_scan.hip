@@ -54,6 +54,10 @@
 // - never the case for argument blobs, but legal) is handled sub-tile by sub-tile in windows
 // of queue size, searched twice (count, then write); slower, same result.
 //
+// Variant at 4-byte stride (fdy_scan_pointers_stride4): the same kernel with kHalf set reads
+// the array as 32-bit units and treats every unit index as a position whose value is that
+// unit and the next one; only the loader and the numbering of positions differ.
+//
 // Tickets are handed out in increasing order and a wave only ever waits for chunks with
 // smaller numbers, which are already owned by resident workgroups; the wait is bounded by a
 // spin limit after which FDY_ST_SPIN is raised and the kernel still terminates.
@@ -390,10 +394,48 @@ struct Filt {
   u32 Q;
 };
 
+// kHalf: the array is read as 32-bit units and position q stands for the 64-bit value whose low
+// half is unit q and whose high half is unit q + 1 (pointers at 4-byte alignment inside packed
+// structures); p.n_words is then the number of positions, one less than the number of units.
+// A lane still takes 16-byte pieces, four positions each, and gets the unit that follows its
+// piece from the next lane (the last lane from the next piece, or from behind the sub-tile).
+template <bool kHalf>
 __device__ __forceinline__ void load_words(const ScanParams& p, u32 sub, u64 span_lo, u64 (&w)[kWpl]) {
   const u32 lane = lane_id();
   const u64 wbase = (u64)sub * kSub;
-  if (wbase + kSub <= p.n_words) {
+  if constexpr (kHalf) {
+    static_assert(kWpl == 8, "two 16-byte pieces of four positions per lane");
+    const u32* h = reinterpret_cast<const u32*>(p.words);
+    if (wbase + kSub <= p.n_words) {  // all 512 positions exist, hence units wbase .. wbase + 512
+      typedef u32 v4u32 __attribute__((ext_vector_type(4)));
+      v4u32 v[2];
+#pragma unroll
+      for (int k = 0; k < 2; ++k)
+        v[k] = __builtin_nontemporal_load(reinterpret_cast<const v4u32*>(h + wbase + (k * 64 + lane) * 4));
+      const u32 behind = h[wbase + kSub];
+      u32 nx[2];
+      nx[0] = __shfl_down(v[0].x, 1);
+      nx[1] = __shfl_down(v[1].x, 1);
+      const u32 first1 = __shfl(v[1].x, 0);
+      if (lane == 63) {
+        nx[0] = first1;
+        nx[1] = behind;
+      }
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        w[4 * k + 0] = (u64)v[k].x | ((u64)v[k].y << 32);
+        w[4 * k + 1] = (u64)v[k].y | ((u64)v[k].z << 32);
+        w[4 * k + 2] = (u64)v[k].z | ((u64)v[k].w << 32);
+        w[4 * k + 3] = (u64)v[k].w | ((u64)nx[k] << 32);
+      }
+    } else {  // the ragged tail, and sub-tiles past the end
+#pragma unroll
+      for (int r = 0; r < kWpl; ++r) {
+        const u64 q = wbase + ((r >> 2) * 64 + lane) * 4 + (r & 3);
+        w[r] = q < p.n_words ? ((u64)h[q] | ((u64)h[q + 1] << 32)) : span_lo - 1;  // outside the span
+      }
+    }
+  } else if (wbase + kSub <= p.n_words) {
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
       // streamed once: non-temporal, so that the table levels keep their place in L2
@@ -413,23 +455,42 @@ __device__ __forceinline__ void load_words(const ScanParams& p, u32 sub, u64 spa
   }
 }
 
+// Register r of a lane holds position (r / kPer * 64 + lane) * kPer + r % kPer of the sub-tile,
+// kPer = 2 words per 16-byte piece, or 4 positions per piece when reading 32-bit units.
+template <bool kHalf>
+__device__ __forceinline__ u32 pos_in_sub(int r, u32 lane) {
+  constexpr int kPer = kHalf ? 4 : 2;
+  return ((u32)(r / kPer) * 64 + lane) * kPer + (u32)(r % kPer);
+}
+
+template <bool kHalf>
 __device__ __forceinline__ void filter_words(const u64 (&w)[kWpl], Filt& t, u64 span_lo, u64 span_len) {
+  constexpr int kPer = kHalf ? 4 : 2;
   const u64 lt = lanemask_lt();
   t.Q = 0;
 #pragma unroll
-  for (int k = 0; k < kLoads; ++k) {
-    t.c[2 * k] = (w[2 * k] - span_lo) < span_len;
-    t.c[2 * k + 1] = (w[2 * k + 1] - span_lo) < span_len;
-    const u64 b0 = ballot(t.c[2 * k]), b1 = ballot(t.c[2 * k + 1]);
-    const u32 pre = t.Q + __popcll(b0 & lt) + __popcll(b1 & lt);
-    t.crank[2 * k] = pre;
-    t.crank[2 * k + 1] = pre + (t.c[2 * k] ? 1u : 0u);
-    t.Q += __popcll(b0) + __popcll(b1);
+  for (int k = 0; k < kWpl / kPer; ++k) {
+    u32 below = t.Q, all = 0;  // candidates of lower lanes in this piece row; of all lanes
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      t.c[kPer * k + j] = (w[kPer * k + j] - span_lo) < span_len;
+      const u64 b = ballot(t.c[kPer * k + j]);
+      below += __popcll(b & lt);
+      all += __popcll(b);
+    }
+    u32 own = 0;  // this lane's earlier candidates of the piece
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      t.crank[kPer * k + j] = below + own;
+      own += t.c[kPer * k + j] ? 1u : 0u;
+    }
+    t.Q += all;
   }
 }
 
 // Candidates with rank in [win, win + wn) go to queue slots qoff + [0, wn); the index stored
 // with each is its word's distance from word 0 of the sub-tile `row` places before this one.
+template <bool kHalf>
 __device__ __forceinline__ void enqueue(const u64 (&w)[kWpl], const Filt& t, u32 row, u32 win, u32 wn,
                                         u32 qoff, u64* qw, unsigned short* qi) {
   const u32 lane = lane_id();
@@ -438,7 +499,7 @@ __device__ __forceinline__ void enqueue(const u64 (&w)[kWpl], const Filt& t, u32
   for (int r = 0; r < kWpl; ++r)
     if (t.c[r] && t.crank[r] - win < wn) {  // unsigned: also false below the window
       qw[qoff + t.crank[r] - win] = w[r];
-      qi[qoff + t.crank[r] - win] = (unsigned short)(row * kSub + ((r >> 1) * 64 + lane) * 2 + (r & 1));
+      qi[qoff + t.crank[r] - win] = (unsigned short)(row * kSub + pos_in_sub<kHalf>(r, lane));
     }
   wave_lds_fence();
 }
@@ -456,6 +517,7 @@ __device__ __forceinline__ void store_reloc(const ScanParams& p, u64 at, u32 wor
 // Dense sub-tile (its wave's group holds more candidates than the register-resident path
 // keeps): windows of queue size; counts when `write` is false, writes from position `pos`
 // otherwise.  Returns hits.
+template <bool kHalf>
 __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt& t, const u32* top,
                           u64 span_lo, u32 shifts, u64* qw, unsigned short* qi, u64 wbase, bool write,
                           u64 pos) {
@@ -464,7 +526,7 @@ __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt&
   u64 H = 0;
   for (u32 win = 0; win < t.Q; win += kQcap) {
     const u32 wn = t.Q - win < (u32)kQcap ? t.Q - win : (u32)kQcap;
-    enqueue(w, t, 0, win, wn, 0, qw, qi);
+    enqueue<kHalf>(w, t, 0, win, wn, 0, qw, qi);
     for (u32 q0 = 0; q0 < wn; q0 += 64) {
       const u32 q = q0 + lane;
       const bool valid = q < wn;
@@ -536,7 +598,7 @@ struct RoundResults {
 };
 
 // Ordered write of one chunk's hits of this wave, given the chunk's exclusive prefix.
-template <int kGroups, int kG>
+template <int kGroups, int kG, bool kHalf>
 __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResults<kGroups, kG>& r,
                                             u64 chunk_excl, const u32* top, u64 span_lo, u64 span_len,
                                             u32 shifts, u64* qw, unsigned short* qi_all) {
@@ -563,15 +625,15 @@ __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResu
         const u32 sub = first_sub + j;
         u64 w[kWpl];
         Filt t;
-        load_words(p, sub, span_lo, w);
-        filter_words(w, t, span_lo, span_len);
-        pos += dense_pass(p, w, t, top, span_lo, shifts, qw, qi, (u64)sub * kSub, true, pos);
+        load_words<kHalf>(p, sub, span_lo, w);
+        filter_words<kHalf>(w, t, span_lo, span_len);
+        pos += dense_pass<kHalf>(p, w, t, top, span_lo, shifts, qw, qi, (u64)sub * kSub, true, pos);
       }
     }
   }
 }
 
-template <int kGroups, int kG>
+template <int kGroups, int kG, bool kHalf>
 __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   constexpr int kUnits = kGroups * kWaves;  // (group, wave) units of a chunk, in word order
   constexpr int kChunk = kUnits * kG;       // sub-tiles a workgroup draws per ticket
@@ -626,7 +688,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
 
   u64 w[kG][kWpl];  // the group of sub-tiles this wave works on next
 #pragma unroll
-  for (int r = 0; r < kG; ++r) load_words(p, base + wave * kG + r, span_lo, w[r]);
+  for (int r = 0; r < kG; ++r) load_words<kHalf>(p, base + wave * kG + r, span_lo, w[r]);
 
   for (u32 round = 0; base < p.n_sub; ++round) {
     const u32 b = round & 1;
@@ -645,14 +707,14 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
 #pragma unroll
       for (int r = 0; r < kG; ++r) {
         Filt t;
-        filter_words(w[r], t, span_lo, span_len);
-        if (Q + t.Q <= (u32)(kGR * 64)) enqueue(w[r], t, r, 0, t.Q, Q, qw, qi);
+        filter_words<kHalf>(w[r], t, span_lo, span_len);
+        if (Q + t.Q <= (u32)(kGR * 64)) enqueue<kHalf>(w[r], t, r, 0, t.Q, Q, qw, qi);
         Q += t.Q;
       }
       {  // the next group's words (this chunk's or the next one's), in flight during the search
         const u32 nsub = g + 1 < kGroups ? first_sub + kWaves * kG : nbase + wave * kG;
 #pragma unroll
-        for (int r = 0; r < kG; ++r) load_words(p, nsub + r, span_lo, w[r]);
+        for (int r = 0; r < kG; ++r) load_words<kHalf>(p, nsub + r, span_lo, w[r]);
       }
 #pragma unroll
       for (int r = 0; r < kGR; ++r) cur.reg[g][r] = kMiss;
@@ -665,9 +727,9 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
         for (int r = 0; r < kG; ++r) {
           u64 dw[kWpl];
           Filt t;
-          load_words(p, first_sub + r, span_lo, dw);
-          filter_words(dw, t, span_lo, span_len);
-          H += dense_pass(p, dw, t, top, span_lo, shifts, qw, qi, (u64)(first_sub + r) * kSub, false, 0);
+          load_words<kHalf>(p, first_sub + r, span_lo, dw);
+          filter_words<kHalf>(dw, t, span_lo, span_len);
+          H += dense_pass<kHalf>(p, dw, t, top, span_lo, shifts, qw, qi, (u64)(first_sub + r) * kSub, false, 0);
         }
       }
       cur.Q[g] = Q;
@@ -704,7 +766,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       const u64 total = __shfl(cur.cnt_incl, 63);  // all lanes take part in the shuffle
       if (closer && lane == 0) st_state(&p.cstate[chunk], (chunk == 0 ? kFlagInc : kFlagAgg) | total);
     }
-    if (have_prev) write_round(p, prev, s_excl[b], top, span_lo, span_len, shifts, qw, qi_all);
+    if (have_prev) write_round<kGroups, kG, kHalf>(p, prev, s_excl[b], top, span_lo, span_len, shifts, qw, qi_all);
     prev = cur;
     have_prev = true;
     base = nbase;
@@ -727,7 +789,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       }
     }
     __syncthreads();
-    write_round(p, prev, s_excl[0], top, span_lo, span_len, shifts, qw, qi_all);
+    write_round<kGroups, kG, kHalf>(p, prev, s_excl[0], top, span_lo, span_len, shifts, qw, qi_all);
   }
 }
 
@@ -841,7 +903,7 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
   u64 w[kFusedG][kWpl];
   if (grp < n_groups) {
 #pragma unroll
-    for (int r = 0; r < kFusedG; ++r) load_words(p, grp * kFusedG + r, span_lo, w[r]);
+    for (int r = 0; r < kFusedG; ++r) load_words<false>(p, grp * kFusedG + r, span_lo, w[r]);
   }
   for (; grp < n_groups; grp += stride) {
     const u32 first_sub = grp * kFusedG;
@@ -850,7 +912,7 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
     u32 Q = 0;
 #pragma unroll
     for (int r = 0; r < kFusedG; ++r) {
-      filter_words(w[r], t[r], span_lo, span_len);
+      filter_words<false>(w[r], t[r], span_lo, span_len);
       qoff[r] = Q;
       Q += t[r].Q;
     }
@@ -859,11 +921,11 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
     u64 nw[kFusedG][kWpl];
     if (more) {
 #pragma unroll
-      for (int r = 0; r < kFusedG; ++r) load_words(p, (grp + stride) * kFusedG + r, span_lo, nw[r]);
+      for (int r = 0; r < kFusedG; ++r) load_words<false>(p, (grp + stride) * kFusedG + r, span_lo, nw[r]);
     }
     if (Q <= kQwave) {
 #pragma unroll
-      for (int r = 0; r < kFusedG; ++r) enqueue(w[r], t[r], r, 0, t[r].Q, qoff[r], qw, qi);
+      for (int r = 0; r < kFusedG; ++r) enqueue<false>(w[r], t[r], r, 0, t[r].Q, qoff[r], qw, qi);
       rebase_queue(p, top, span_lo, shifts, qw, Q, H);
 #pragma unroll
       for (int r = 0; r < kFusedG; ++r) dequeue(w[r], t[r], 0, t[r].Q, qoff[r], qw);
@@ -874,7 +936,7 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
         constexpr int r = decltype(row_c)::value;
         for (u32 win = 0; win < t[r].Q; win += kQwave) {
           const u32 wn = t[r].Q - win < kQwave ? t[r].Q - win : kQwave;
-          enqueue(w[r], t[r], 0, win, wn, 0, qw, qi);
+          enqueue<false>(w[r], t[r], 0, win, wn, 0, qw, qi);
           rebase_queue(p, top, span_lo, shifts, qw, wn, H);
           dequeue(w[r], t[r], win, wn, 0, qw);
         }
@@ -1081,7 +1143,7 @@ extern "C" size_t fdy_scan_workspace_bytes(uint64_t n_words, uint32_t n_alloc) {
 static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
                        uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity, uint64_t* d_count,
                        const uint64_t* d_new_base, uint64_t* d_out, void* d_workspace,
-                       size_t workspace_bytes, uint32_t* d_status, void* hip_stream) {
+                       size_t workspace_bytes, uint32_t* d_status, void* hip_stream, bool half = false) {
   const bool fused = d_out != nullptr;
   if (n_words > kMaxWords) return FDY_ERR_INVALID_ARG;
   if (!d_count) return FDY_ERR_INVALID_ARG;
@@ -1178,7 +1240,8 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
     return FDY_OK;
   }
   const size_t lds = lds0 + (size_t)kWaves * pl.g * kQcap * (8 + 2 * 2 * pl.groups);
-  auto kern = pl.g == kGSmall ? scan_kernel<kGroupsSmall, kGSmall> : scan_kernel<kGroupsBig, kGBig>;
+  auto kern = pl.g == kGSmall ? (half ? scan_kernel<kGroupsSmall, kGSmall, true> : scan_kernel<kGroupsSmall, kGSmall, false>)
+                              : (half ? scan_kernel<kGroupsBig, kGBig, true> : scan_kernel<kGroupsBig, kGBig, false>);
   FDY_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   prof_begin(FDY_PROF_SCAN_MAIN, stream);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), lds, stream, p);
@@ -1193,6 +1256,18 @@ extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, cons
                                  uint32_t* d_status, void* hip_stream) {
   return scan_launch(d_words, n_words, d_table, n_alloc, d_relocs, reloc_capacity, d_count, nullptr, nullptr,
                      d_workspace, workspace_bytes, d_status, hip_stream);
+}
+
+extern "C" int fdy_scan_pointers_stride4(const uint32_t* d_units, uint64_t n_units, const fdy_alloc* d_table,
+                                         uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
+                                         uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
+                                         uint32_t* d_status, void* hip_stream) {
+  // position q pairs unit q with unit q + 1: one position less than units
+  const uint64_t n_pos = n_units >= 2 ? n_units - 1 : 0;
+  if (n_units && !d_units) return FDY_ERR_INVALID_ARG;
+  return scan_launch(reinterpret_cast<const uint64_t*>(d_units), n_pos, d_table, n_alloc, d_relocs,
+                     reloc_capacity, d_count, nullptr, nullptr, d_workspace, workspace_bytes, d_status,
+                     hip_stream, true);
 }
 
 extern "C" int fdy_scan_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,

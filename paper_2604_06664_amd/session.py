@@ -50,6 +50,35 @@ def scan(words, table, capacity=None):
     return run.result()
 
 
+class ScanStride4Run(ScanRun):
+    """fdy_scan_pointers_stride4: `units` is a uint32 array; capacity defaults to one entry per
+    position."""
+
+    def __init__(self, units, table, capacity=None):
+        units = np.ascontiguousarray(units, np.uint32)
+        self.n_units = int(len(units))
+        self.n_alloc = int(len(table))
+        self.capacity = max(self.n_units - 1, 0) if capacity is None else int(capacity)
+        self.d_words = fdy.to_device(units)
+        self.d_table = table if torch.is_tensor(table) else fdy.to_device(table)
+        self.d_relocs = fdy.device_bytes(self.capacity * 16)
+        self.d_count = torch.zeros(1, dtype=torch.int64, device=DEV)
+        self.ws_bytes = fdy.fdy_scan_workspace_bytes(self.n_units, self.n_alloc)
+        self.d_ws = fdy.device_bytes(self.ws_bytes)
+        self.d_status = _status_tensor()
+
+    def launch(self, stream=None):
+        return fdy.fdy_scan_pointers_stride4(self.d_words, self.n_units, self.d_table, self.n_alloc,
+                                             self.d_relocs, self.capacity, self.d_count, self.d_ws,
+                                             self.ws_bytes, self.d_status, stream)
+
+
+def scan_stride4(units, table, capacity=None):
+    run = ScanStride4Run(units, table, capacity)
+    run.launch()
+    return run.result()
+
+
 class ScanRebaseRun:
     """Device-resident inputs, output and workspace of one fdy_scan_rebase problem."""
 

@@ -256,6 +256,86 @@ def test_derive_overrides_archives_and_round_trip(hip, oracle, idx):
     assert status == 0 and np.array_equal(out[0], ar.words)
 
 
+# ------------------------------------------------------------------- scan at 4-byte stride
+def check_scan4(hip, oracle, units, table, capacity=None, tag=""):
+    units = np.ascontiguousarray(units, np.uint32)
+    say(f"[scan stride 4] {tag} units={len(units)} A={len(table)} cap={capacity}")
+    ref, rcnt = oracle.scan_stride4(units, table, capacity)
+    got, cnt, status = hip.scan_stride4(units, table, capacity)
+    assert cnt == rcnt
+    assert np.array_equal(got, ref)
+    cap = max(len(units) - 1, 0) if capacity is None else capacity
+    assert status == (L.ST_CAPACITY if rcnt > cap else 0)
+    return got
+
+
+def units_with_odd_pointers(ar, n_words=None):
+    """The archive's words as 32-bit units, every fifth planted pointer moved half a word up."""
+    n = len(ar.words) if n_words is None else min(n_words, len(ar.words))
+    units = np.ascontiguousarray(ar.words[:n]).view(np.uint32).copy()
+    for j in ar.ptr_word[::5]:
+        if 2 * j + 2 < len(units):
+            units[2 * j + 1], units[2 * j + 2], units[2 * j] = units[2 * j], units[2 * j + 1], 0
+    return units
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_scan_stride4_small_configs(hip, oracle, idx):
+    ar = small(idx)
+    units = units_with_odd_pointers(ar)
+    got = check_scan4(hip, oracle, units, ar.table, tag=ar.name)
+    assert (got["word"] % 2 == 1).sum() > 0 and (got["word"] % 2 == 0).sum() > 0
+    check_scan4(hip, oracle, units[:-1], ar.table, tag=ar.name + " odd unit count")
+
+
+def test_scan_stride4_edge_cases(hip, oracle):
+    import paper_2604_06664_amd as fdy
+
+    ar = small(4)  # 65,536 allocations
+    units = units_with_odd_pointers(ar, 300000)
+    for n in (0, 1, 2, 3, 511, 512, 513, 514, 1024, 1025, 1026, 2049, 4097, 70001, 131073):
+        check_scan4(hip, oracle, units[:n], ar.table, tag="ragged")
+    # a pointer on every seam: the last position of a sub-tile takes its high half from the next
+    # sub-tile, the last lane of a 16-byte piece row from the next row, the last position of all
+    # from the last unit
+    t = mk_table([(0x7000_0000_0000, 0x1000), (0x7000_0010_0000, 0x40)])
+    rng = np.random.default_rng(3)
+    u = rng.integers(0, 1 << 31, 5000, dtype=np.uint32)  # high halves below the table: no stray hit
+    for q, v in ((255, 0x7000_0000_0008), (511, 0x7000_0000_0FFF), (767, 0x7000_0010_0000), (1023, 0x7000_0010_003F),
+                 (1535, 0x7000_0000_0000), (4998, 0x7000_0010_0001)):
+        u[q], u[q + 1] = v & 0xFFFFFFFF, v >> 32
+    got = check_scan4(hip, oracle, u, t, tag="seams")
+    assert got["word"].tolist() == [255, 511, 767, 1023, 1535, 4998]
+    check_scan4(hip, oracle, u, t, capacity=3, tag="capacity 3")
+    # no table: nothing is a pointer
+    got, cnt, status = hip.scan_stride4(u, t[:0])
+    assert cnt == 0 and status == 0
+    # (nearly) every position a hit: the windowed path
+    wide = mk_table([(0, 1 << 63), (1 << 63, (1 << 63) - 1)])
+    check_scan4(hip, oracle, rng.integers(0, 1 << 32, 9001, dtype=np.uint32), wide, tag="all hits")
+    old = fdy.tune_get(fdy.TUNE_SCAN_TOP_LOG2)
+    try:
+        for top_log2 in (3, 9):
+            fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, top_log2)
+            check_scan4(hip, oracle, units[:200001], ar.table, tag=f"top_log2={top_log2}")
+    finally:
+        fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, old)
+    # misaligned array refused on the host
+    run = hip.ScanStride4Run(u, t)
+    rc = fdy.fdy_scan_pointers_stride4(run.d_words.data_ptr() + 4, 100, run.d_table, 2, run.d_relocs, 10,
+                                       run.d_count, run.d_ws, run.ws_bytes, run.d_status, check=False)
+    assert rc == fdy.FDY_ERR_INVALID_ARG
+
+
+def test_scan_stride4_large_input(hip, oracle):
+    """2^23 units against 2^16 allocations: the large-input kernel shape (two groups of two
+    sub-tiles per wave), several chunks per workgroup."""
+    ar = make_config(4, n_words=(1 << 22) + 4096, n_alloc=1 << 16)
+    units = units_with_odd_pointers(ar)
+    got = check_scan4(hip, oracle, units, ar.table, tag="large")
+    assert len(got) > 300_000
+
+
 # ------------------------------------------------------------------- fused scan + rebase
 def oracle_rebase(oracle, words, table, new_base):
     """What fdy_scan_rebase must produce, from the oracle's own scan and materialize: one

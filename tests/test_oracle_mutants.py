@@ -21,6 +21,10 @@ MUTANTS = [
      "std::lower_bound(bases.begin(), bases.end(), w)", ["test_oracle_scan.py"]),
     ("scan: offset from the wrong end", "relocs[K] = Reloc{(uint32_t)j, (uint32_t)i, w - table[i].base};",
      "relocs[K] = Reloc{(uint32_t)j, (uint32_t)i, table[i].base + table[i].size - w};", ["test_oracle_scan.py"]),
+    ("stride-4 scan: halves swapped", "value[q] = (uint64_t)units[q] | ((uint64_t)units[q + 1] << 32);",
+     "value[q] = (uint64_t)units[q + 1] | ((uint64_t)units[q] << 32);", ["test_oracle_scan.py"]),
+    ("stride-4 scan: pairs instead of every position", "for (uint64_t q = 0; q + 1 < n_units; ++q) value[q]",
+     "for (uint64_t q = 0; q + 1 < n_units; q += 2) value[q]", ["test_oracle_scan.py"]),
     ("segment: boundary word counted", "(uint64_t)relocs[c].word < word_off[s]) ++c;",
      "(uint64_t)relocs[c].word <= word_off[s]) ++c;", ["test_oracle_scan.py"]),
     ("validate: touching ranges refused", "t[i - 1].base + t[i - 1].size <= t[i].base;",

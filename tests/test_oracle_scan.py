@@ -136,3 +136,55 @@ def test_reloc_segment(oracle):
     per_graph = np.diff(off.astype(np.int64))
     for t in range(ar.n_templates):
         assert len(set(per_graph[ar.graph_tmpl == t])) == 1
+
+
+# ---- scan at 4-byte stride (variant for pointers at 4-byte alignment) -----------------------
+def test_stride4_worked_example(oracle):
+    # units 0x00000000 0x00000001 0x00000005 0x00000003 0x00000000: the four positions read
+    # 0x1_00000000, 0x5_00000001, 0x3_00000005, 0x0_00000003
+    table = mk_table([(0x1_0000_0000, 0x10), (0x3_0000_0000, 0x20)])
+    relocs, count = oracle.scan_stride4(np.array([0, 1, 5, 3, 0], np.uint32), table)
+    assert count == 2 and as_tuples(relocs) == [(0, 0, 0), (2, 1, 5)]
+    for n in (0, 1):  # fewer than two units: no position at all
+        assert oracle.scan_stride4(np.zeros(n, np.uint32), table)[1] == 0
+    assert oracle.scan_stride4(np.array([0, 1], np.uint32), table)[1] == 1  # exactly one position
+
+
+def test_stride4_python_brute_force(oracle):
+    rng = np.random.default_rng(11)
+    for trial in range(100):
+        A = int(rng.integers(1, 6))
+        bases = np.sort(rng.choice(1 << 12, A, replace=False).astype(np.uint64)) << np.uint64(24)
+        table = mk_table([(int(b), int(rng.integers(1, 1 << 24))) for b in bases])
+        units = rng.integers(0, 1 << 32, int(rng.integers(2, 60)), dtype=np.uint32)
+        # plant values at odd and even positions
+        for _ in range(int(rng.integers(0, 8))):
+            q = int(rng.integers(0, len(units) - 1))
+            i = int(rng.integers(0, A))
+            v = int(table["base"][i]) + int(rng.integers(0, int(table["size"][i])))
+            units[q], units[q + 1] = v & 0xFFFFFFFF, v >> 32
+        vals = [int(units[q]) | (int(units[q + 1]) << 32) for q in range(len(units) - 1)]
+        relocs, count = oracle.scan_stride4(units, table)
+        assert as_tuples(relocs) == py_scan(vals, table) and count == len(relocs)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 4])
+def test_stride4_even_and_odd_positions_are_two_aligned_scans(oracle, idx):
+    """Even positions are the 8-byte words of the array, odd positions the 8-byte words of the
+    array with its first unit dropped: the 4-byte-stride result is the merge of two scans."""
+    ar = small(idx)
+    units = np.ascontiguousarray(ar.words).view(np.uint32)[: 2 * min(len(ar.words), 50000)].copy()
+    # move every fifth planted pointer of the range half a word up, so that odd positions hit too
+    for j in ar.ptr_word[::5]:
+        if 2 * j + 2 < len(units):
+            units[2 * j + 1], units[2 * j + 2], units[2 * j] = units[2 * j], units[2 * j + 1], 0
+    relocs, count = oracle.scan_stride4(units, ar.table)
+    even, _ = oracle.scan(units.view(np.uint64), ar.table)
+    odd, _ = oracle.scan(units[1:-1].copy().view(np.uint64), ar.table)
+    assert count == len(even) + len(odd) and len(odd) > 0
+    got_even = relocs[relocs["word"] % 2 == 0]
+    got_odd = relocs[relocs["word"] % 2 == 1]
+    assert np.array_equal(got_even["word"], 2 * even["word"]) and np.array_equal(got_odd["word"], 2 * odd["word"] + 1)
+    for f in ("region", "offset"):
+        assert np.array_equal(got_even[f], even[f]) and np.array_equal(got_odd[f], odd[f])
+    assert np.all(np.diff(relocs["word"].astype(np.int64)) > 0)
