@@ -56,7 +56,7 @@ def test_install_at_decode_graph_scale():
     print("[install]", msg.value.decode(), flush=True)
     assert rc == 0, msg.value.decode()
     assert stats[5] == 67 * 2 and stats[6] == 2 * 576
-    out = os.path.join(os.path.dirname(HERE), "gpurun_out")
+    out = os.environ.get("FDY_TEST_OUT", "")  # optional folder for the measured figures
     if os.path.isdir(out):
         with open(os.path.join(out, "install_scale.txt"), "w") as f:
             f.write(msg.value.decode() + "\n" + " ".join(f"{v:.4f}" for v in stats) + "\n")
