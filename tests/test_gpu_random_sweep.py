@@ -1,4 +1,5 @@
-"""Seeded random sweep of the scan and the fused scan + rebase against the oracle (GPU).
+"""Seeded random sweep of the scan, the fused scan + rebase and the scan at 4-byte stride against
+the oracle (GPU).
 
 Table shapes the fixed configurations do not have (clusters of tiny allocations, a few huge
 ones, touching ranges, spans from a few KiB to most of the address space), candidate
@@ -82,5 +83,15 @@ def test_random_scan_and_rebase(oracle, case):
         out_ref, _ = oracle_rebase(oracle, words, table, new_base)
         out, ocnt, ostatus = session.scan_rebase(words, table, new_base)
         assert ostatus == 0 and ocnt == rcnt and np.array_equal(out, out_ref)
+        # the same bytes at 4-byte stride, with every third planted value moved half a word up
+        units = words.view(np.uint32).copy()
+        for j in np.flatnonzero((words >= table["base"][0]) & (words <= table["base"][-1]))[::3]:
+            if 2 * j + 2 < len(units):
+                units[2 * j + 1], units[2 * j + 2], units[2 * j] = units[2 * j], units[2 * j + 1], 0
+        if W % 2:
+            units = units[:-1]  # an even and an odd number of units both occur over the cases
+        ref4, rcnt4 = oracle.scan_stride4(units, table)
+        got4, cnt4, status4 = session.scan_stride4(units, table)
+        assert status4 == 0 and cnt4 == rcnt4 and np.array_equal(got4, ref4)
     finally:
         fdy.tune_set(fdy.TUNE_SCAN_TOP_LOG2, old)
