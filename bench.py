@@ -122,12 +122,49 @@ def run_workload(idx, steps, warmup, prof=True, cpu_sample_words=0):
             res["kernels"]["mat_main_kernel"]["avg_ms"] / 1e3)
     if ar.n_graphs == 1 and ar.n_maps == 1 and prof:
         res["fused_scan_rebase"] = fused_variant(ar, run, steps)
+    if len(ar.words) < (1 << 24):  # launch-bound sizes: the same step replayed from a HIP graph
+        res["graph_replay"] = graph_replay(run, steps)
     cpu = None
     if cpu_sample_words:
         cpu = cpu_baseline(ar, run, min(cpu_sample_words, len(ar.words)))
     del run
     torch.cuda.empty_cache()
     return res, cpu
+
+
+def graph_replay(run, steps):
+    """The step captured once into a HIP graph and replayed: for the small archives the eager
+    step is bound by launch latency (eight launches of 5-20 us), which a graph removes.  Not
+    part of `value`.  The replayed output must equal the eager one."""
+    import torch
+
+    try:
+        ref = run.mat.d_out.clone()
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            run.step(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            run.step(side)
+        torch.cuda.synchronize()
+        run.mat.d_out.fill_(0xCD)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        same = bool(torch.equal(run.mat.d_out, ref)) and run.status() == 0
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(steps):
+            graph.replay()
+        ev1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return dict(ms_per_step=round(wall, 5), device_ms_per_step=round(ev0.elapsed_time(ev1) / steps, 5),
+                    equals_eager_output=same)
+    except Exception as e:  # reported, never fatal for the bench line
+        return dict(error=f"{type(e).__name__}: {e}")
 
 
 def fused_variant(ar, run, steps):

@@ -80,7 +80,7 @@ __global__ __launch_bounds__(1024) void derive_prep_kernel(DerParams p) {
       nt = (nw + kDerTile - 1) / kDerTile;
     }
     u64 total;
-    const u64 e = block_excl_scan_1024(nt, s_buf, total);
+    const u64 e = block_excl_scan(nt, s_buf, total);
     if (g < G) p.ws.tile_off[g] = carry + e;
     carry += total;
   }
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(1024) void derive_scan_kernel(DerParams p) {
     const u32 j = j0 + threadIdx.x;
     const u64 c = j < n ? p.ws.tile_cnt[j] : 0;
     u64 total;
-    const u64 e = block_excl_scan_1024(c, s_buf, total);
+    const u64 e = block_excl_scan(c, s_buf, total);
     if (j < n) p.ws.tile_pos[j] = carry + e;
     carry += total;
   }

@@ -67,10 +67,10 @@ __device__ __forceinline__ u32 wave_lower_bound(KeyFn key, u32 lo, u32 hi, u64 t
   return lo;
 }
 
-// Exclusive scan of one u64 per thread over a 1024-thread workgroup; returns the exclusive
-// prefix and sets `total` (same in every thread).  s_buf: 17 u64 of LDS.
-__device__ inline u64 block_excl_scan_1024(u64 v, u64* s_buf, u64& total) {
-  const u32 l = lane_id(), w = threadIdx.x >> 6;
+// Exclusive scan of one u64 per thread over a workgroup of whole waves (at most 1024 threads);
+// returns the exclusive prefix and sets `total` (same in every thread).  s_buf: 17 u64 of LDS.
+__device__ inline u64 block_excl_scan(u64 v, u64* s_buf, u64& total) {
+  const u32 l = lane_id(), w = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
   u64 inc = v;
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
@@ -80,7 +80,7 @@ __device__ inline u64 block_excl_scan_1024(u64 v, u64* s_buf, u64& total) {
   if (l == 63) s_buf[w] = inc;
   __syncthreads();
   if (w == 0) {
-    const u64 x = l < 16 ? s_buf[l] : 0;
+    const u64 x = l < n_waves ? s_buf[l] : 0;
     u64 xi = x;
 #pragma unroll
     for (int d = 1; d < 16; d <<= 1) {

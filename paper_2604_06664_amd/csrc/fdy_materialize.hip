@@ -6,18 +6,23 @@
 // units, bounded by the HBM write of the output:
 //
 //   prep A (one workgroup)   prefix sums over the output graphs: where each graph's words,
-//                            nodes and tiles start; verifies the caller's totals.
+//                            nodes and tiles start; verifies the caller's totals.  A launch
+//                            of its own only above 1024 output graphs: up to there every
+//                            block of prep B computes the sums itself, in LDS.
 //   prep B (one launch)      three kinds of blocks side by side.  Tile blocks (one thread per
 //                            tile) resolve each output tile once, independent of the base map:
 //                            its graph, template, source words, and the sub-ranges of the
 //                            template's relocation list and the graph's override list that
-//                            fall inside the tile.  Patch blocks (one thread per tile and rank)
-//                            do the same for each rank's patch list.  Dims blocks (one thread
-//                            per node) write the launch dimensions of the template with the
-//                            graph's grid overrides.  Plain per-lane binary searches: tens of
-//                            thousands of them run side by side, and one request per halving is
-//                            what the memory system serves best.  One launch rather than three
-//                            because small archives are bound by launch latency.
+//                            fall inside the tile (a thread searches where its tile's ranges
+//                            begin; they end where the next tile's begin).  Patch blocks (one
+//                            thread per tile and rank) do the same for each rank's patch list.
+//                            Dims blocks (one thread per node) write the launch dimensions of
+//                            the template with the graph's grid overrides.  Plain per-lane
+//                            binary searches: tens of thousands of them run side by side, and
+//                            one request per halving is what the memory system serves best;
+//                            the kernel's time is its longest chain of dependent loads.  One
+//                            launch rather than four because small archives are bound by
+//                            launch latency.
 //   main  (tile x map group) stages the template tile in LDS and the tile's relocation entries
 //                            in registers once, then per base map of its group scatters c2
 //                            rebased pointers (new_base[m][region] + offset), c3 32-bit
@@ -68,6 +73,32 @@ struct MatParams {
   u32 map_group;  // consecutive base maps handled by one workgroup of the main kernel
 };
 
+// Word and node counts of output graph g (those of its template).  False, with zero counts, if
+// its template or the template's source graph is out of range or has 2^32 words or more.
+__device__ __forceinline__ bool graph_sizes(const MatParams& p, u32 g, u64& nw, u64& nn) {
+  const fdy_mat_desc& d = p.d;
+  nw = 0;
+  nn = 0;
+  const u32 t = d.graph_tmpl[g];
+  const u32 s = t < d.n_templates ? d.tmpl_graph[t] : 0xffffffffu;
+  if (s >= d.n_src_graphs) return false;
+  nw = d.src_word_off[s + 1] - d.src_word_off[s];
+  if (p.out_dims) nn = d.src_node_off[s + 1] - d.src_node_off[s];
+  if (nw >> 32) {  // a template must stay below 2^32 words
+    nw = 0;
+    nn = 0;
+    return false;
+  }
+  return true;
+}
+
+// Do the totals match what the caller sized the launch and the outputs for?
+__device__ __forceinline__ bool totals_ok(const MatParams& p, u64 words, u64 nodes, u64 tiles) {
+  bool ok = words == p.d.out_words_per_map && tiles <= p.ws.max_tiles;
+  if (p.out_dims && nodes != p.d.out_nodes_total) ok = false;
+  return ok;
+}
+
 __global__ __launch_bounds__(1024) void mat_prep_graphs_kernel(MatParams p) {
   __shared__ u64 s_buf[17];
   const fdy_mat_desc& d = p.d;
@@ -77,26 +108,12 @@ __global__ __launch_bounds__(1024) void mat_prep_graphs_kernel(MatParams p) {
   for (u32 g0 = 0; g0 < G; g0 += 1024) {
     const u32 g = g0 + threadIdx.x;
     u64 nw = 0, nn = 0;
-    if (g < G) {
-      const u32 t = d.graph_tmpl[g];
-      const u32 s = t < d.n_templates ? d.tmpl_graph[t] : 0xffffffffu;
-      if (s < d.n_src_graphs) {
-        nw = d.src_word_off[s + 1] - d.src_word_off[s];
-        if (p.out_dims) nn = d.src_node_off[s + 1] - d.src_node_off[s];
-        if (nw >> 32) {  // a template must stay below 2^32 words
-          nw = 0;
-          nn = 0;
-          bad = true;
-        }
-      } else {
-        bad = true;
-      }
-    }
+    if (g < G && !graph_sizes(p, g, nw, nn)) bad = true;
     const u64 nt = (nw + kMatTile - 1) / kMatTile;
     u64 tw, tn, tt;
-    const u64 ew = block_excl_scan_1024(nw, s_buf, tw);
-    const u64 en = block_excl_scan_1024(nn, s_buf, tn);
-    const u64 et = block_excl_scan_1024(nt, s_buf, tt);
+    const u64 ew = block_excl_scan(nw, s_buf, tw);
+    const u64 en = block_excl_scan(nn, s_buf, tn);
+    const u64 et = block_excl_scan(nt, s_buf, tt);
     if (g < G) {
       p.ws.out_word_off[g] = carry_w + ew;
       p.ws.out_node_off[g] = carry_n + en;
@@ -111,8 +128,7 @@ __global__ __launch_bounds__(1024) void mat_prep_graphs_kernel(MatParams p) {
     p.ws.out_word_off[G] = carry_w;
     p.ws.out_node_off[G] = carry_n;
     p.ws.tile_off[G] = carry_t;
-    bool ok = carry_w == d.out_words_per_map && carry_t <= p.ws.max_tiles;
-    if (p.out_dims && carry_n != d.out_nodes_total) ok = false;
+    const bool ok = totals_ok(p, carry_w, carry_n, carry_t);
     if (!ok) raise_status(p.d_status, FDY_ST_BAD_SIZE);
     p.ws.hdr->n_tiles = ok ? (u32)carry_t : 0u;
     p.ws.hdr->ok = ok ? 1u : 0u;
@@ -132,15 +148,26 @@ __device__ __forceinline__ u32 lane_lower_bound(KeyFn key, u32 lo, u32 hi, u64 t
   return lo;
 }
 
+// The per-graph prefix sums as the tile, patch and dims blocks read them: from the workspace
+// (written by mat_prep_graphs_kernel) or from the block's own LDS copy.
+struct PrepView {
+  const u64* out_word_off;  // [G+1]
+  const u64* out_node_off;  // [G+1]
+  const u64* tile_off;      // [G+1]
+  u32 n_tiles;              // 0 if the totals do not match
+  u32 ok;
+};
+
 // Where tile j (j < n_tiles) lies: its graph, template, source graph, first word inside the
-// graph, word count, first source word.
+// graph, word count, first source word, and whether it is the graph's last tile.
 struct TileGeom {
   u32 g, t, s, n;
   u64 k0, src_word;
+  bool last;
 };
-__device__ __forceinline__ TileGeom tile_geometry(const MatParams& p, u32 j) {
+__device__ __forceinline__ TileGeom tile_geometry(const MatParams& p, const PrepView& v, u32 j) {
   const fdy_mat_desc& d = p.d;
-  const u64* tile_off = p.ws.tile_off;
+  const u64* tile_off = v.tile_off;
   TileGeom q;
   // largest g with tile_off[g] <= j
   q.g = lane_lower_bound([&](u32 i) { return tile_off[i]; }, 0u, d.n_graphs + 1u, (u64)j + 1) - 1;
@@ -151,40 +178,57 @@ __device__ __forceinline__ TileGeom tile_geometry(const MatParams& p, u32 j) {
   q.k0 = ((u64)j - tile_off[q.g]) * kMatTile;
   q.n = (u32)((nw - q.k0) < (u64)kMatTile ? (nw - q.k0) : (u64)kMatTile);
   q.src_word = w0 + q.k0;
+  q.last = q.k0 + q.n == nw;
   return q;
 }
 
-// Thread j: output tile j (independent of the base map).
-__device__ __forceinline__ void prep_tile(const MatParams& p, u32 j) {
+// A block of 256 threads resolves kPrepTiles = 255 consecutive output tiles (independent of the
+// base map).  Every thread finds where its tile's slices of the template's relocation list
+// and of the graph's override list BEGIN; where they end is where the next tile's begin (the
+// next thread's result, through LDS) or, for a graph's last tile, the end of the list.  That
+// halves the chain of dependent loads, which is all this kernel's time.  Thread 255 only
+// supplies the begins of the tile after the block's last.  Both ends stay bounded by the tile
+// size, so a malformed list can never index outside what mat_main_kernel reserves; entries
+// that do not belong to the tile are caught there.
+constexpr u32 kPrepTiles = 255;
+__device__ __forceinline__ void prep_tiles_block(const MatParams& p, const PrepView& v, u32 block, uint2* s_lo) {
   const fdy_mat_desc& d = p.d;
-  if (j >= p.ws.max_tiles) return;
+  const u32 tid = threadIdx.x;
+  const u32 j = block * kPrepTiles + tid;
+  const bool valid = j < v.n_tiles;
+  TileGeom q;
+  u32 rl1 = 0, ov1 = 0, reloc_lo = 0, ovr_lo = 0;
+  if (valid) {
+    q = tile_geometry(p, v, j);
+    const fdy_reloc* relocs = d.relocs;
+    const u32 rl0 = (u32)d.src_reloc_off[q.s];
+    rl1 = (u32)d.src_reloc_off[q.s + 1];
+    reloc_lo = lane_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, rl0, rl1, q.src_word);
+    const fdy_ovr32* ovr = d.ovr;
+    const u32 ov0 = (u32)d.ovr_off[q.g];
+    ov1 = (u32)d.ovr_off[q.g + 1];
+    ovr_lo = lane_lower_bound([&](u32 i) { return (u64)ovr[i].byte_off; }, ov0, ov1, q.k0 * 8);
+  }
+  s_lo[tid] = make_uint2(reloc_lo, ovr_lo);
+  __syncthreads();
+  if (tid >= kPrepTiles || j >= p.ws.max_tiles) return;
   MatTile* ent = &p.ws.tiles[j];
-  if (j >= p.ws.hdr->n_tiles) {
+  if (!valid) {
     ent->n_words = 0;
     return;
   }
-  const TileGeom q = tile_geometry(p, j);
-  const u32 g = q.g, t = q.t, s = q.s, n = q.n;
-  const u64 k0 = q.k0, src_word = q.src_word;
-  const fdy_reloc* relocs = d.relocs;
-  const u32 rl0 = (u32)d.src_reloc_off[s], rl1 = (u32)d.src_reloc_off[s + 1];
-  const u32 reloc_lo = lane_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, rl0, rl1, src_word);
+  // a tile that is not its graph's last is followed by a tile of the same graph (j + 1 < n_tiles)
+  u32 reloc_hi = q.last ? rl1 : s_lo[tid + 1].x;
+  const u32 ovr_hi = q.last ? ov1 : s_lo[tid + 1].y;
   // the list is strictly ascending by word: at most n entries fall inside the tile
-  const u32 cap = rl1 - reloc_lo < n ? rl1 : reloc_lo + n;
-  const u32 reloc_hi =
-      lane_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, reloc_lo, cap, src_word + n);
-  const fdy_ovr32* ovr = d.ovr;
-  const u32 ov0 = (u32)d.ovr_off[g], ov1 = (u32)d.ovr_off[g + 1];
-  const u32 ovr_lo = lane_lower_bound([&](u32 i) { return (u64)ovr[i].byte_off; }, ov0, ov1, k0 * 8);
-  const u32 ovr_hi =
-      lane_lower_bound([&](u32 i) { return (u64)ovr[i].byte_off; }, ovr_lo, ov1, (k0 + n) * 8);
+  if (reloc_hi - reloc_lo > q.n) reloc_hi = reloc_lo + q.n;
   MatTile e;
-  e.src_word = src_word;
-  e.out_word = p.ws.out_word_off[g] + k0;
-  e.n_words = n;
-  e.g = g;
-  e.tmpl = t;
-  e.k0 = (u32)k0;
+  e.src_word = q.src_word;
+  e.out_word = v.out_word_off[q.g] + q.k0;
+  e.n_words = q.n;
+  e.g = q.g;
+  e.tmpl = q.t;
+  e.k0 = (u32)q.k0;
   e.reloc_lo = reloc_lo;
   e.reloc_hi = reloc_hi;
   e.ovr_lo = ovr_lo;
@@ -195,12 +239,12 @@ __device__ __forceinline__ void prep_tile(const MatParams& p, u32 j) {
 
 // Thread i: (output tile, rank) pair i: the slice of the rank's patch list inside the tile.
 // Works from the tile's geometry, not from the tile table, which the same launch is writing.
-__device__ __forceinline__ void prep_patch(const MatParams& p, u64 i) {
+__device__ __forceinline__ void prep_patch(const MatParams& p, const PrepView& v, u64 i) {
   const fdy_mat_desc& d = p.d;
   const u32 R = d.n_ranks;
-  if (i >= (u64)p.ws.hdr->n_tiles * R) return;
+  if (i >= (u64)v.n_tiles * R) return;
   const u32 j = (u32)(i / R), r = (u32)(i % R);
-  const TileGeom e = tile_geometry(p, j);
+  const TileGeom e = tile_geometry(p, v, j);
   const fdy_patch* patch = d.patch;
   const u64 row = (u64)e.t * R + r;
   const u32 p0 = (u32)d.patch_off[row], p1 = (u32)d.patch_off[row + 1];
@@ -341,12 +385,12 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
 }
 
 // Thread i: launch dimensions of output node i.
-__device__ __forceinline__ void write_dims(const MatParams& p, u64 i) {
+__device__ __forceinline__ void write_dims(const MatParams& p, const PrepView& v, u64 i) {
   const fdy_mat_desc& d = p.d;
-  if (!p.ws.hdr->ok) return;
+  if (!v.ok) return;
   if (i >= d.out_nodes_total) return;
   // largest g with out_node_off[g] <= i
-  const u64* off = p.ws.out_node_off;
+  const u64* off = v.out_node_off;
   u32 lo = 0, hi = d.n_graphs;  // answer in [lo, hi)
   while (hi - lo > 1) {
     const u32 mid = lo + (hi - lo) / 2;
@@ -379,11 +423,74 @@ __device__ __forceinline__ void write_dims(const MatParams& p, u64 i) {
 // Everything that only needs the per-graph prefix sums, in one launch (these are small and
 // launch-bound: three launches cost three times one): blocks [0, nb_tiles) resolve tiles,
 // the next nb_patch blocks the (tile, rank) patch slices, the rest write launch dimensions.
+// kOwnSums (at most kOwnSumsMax output graphs): every block computes the prefix sums itself,
+// in LDS, instead of reading what mat_prep_graphs_kernel left in the workspace; that launch
+// is then not needed at all.  Block 0 reports what that kernel would have reported.
+constexpr u32 kOwnSumsMax = 1024;
+template <bool kOwnSums>
 __global__ __launch_bounds__(256) void mat_prep_tiles_kernel(MatParams p, u32 nb_tiles, u32 nb_patch) {
+  __shared__ uint2 s_lo[256];
+  __shared__ u64 s_off[kOwnSums ? 3 : 1][kOwnSums ? kOwnSumsMax + 1 : 1];
+  __shared__ u64 s_buf[17];
+  PrepView v;
+  if constexpr (kOwnSums) {
+    const u32 G = p.d.n_graphs, tid = threadIdx.x;
+    constexpr u32 kPer = kOwnSumsMax / 256;
+    u64 nw[kPer], nn[kPer], sum_w = 0, sum_n = 0, sum_t = 0;
+    bool bad = false;
+#pragma unroll
+    for (u32 i = 0; i < kPer; ++i) {
+      const u32 g = tid * kPer + i;
+      nw[i] = 0;
+      nn[i] = 0;
+      if (g < G && !graph_sizes(p, g, nw[i], nn[i])) bad = true;
+      sum_w += nw[i];
+      sum_n += nn[i];
+      sum_t += (nw[i] + kMatTile - 1) / kMatTile;
+    }
+    u64 tw, tn, tt;
+    u64 ew = block_excl_scan(sum_w, s_buf, tw);
+    u64 en = block_excl_scan(sum_n, s_buf, tn);
+    u64 et = block_excl_scan(sum_t, s_buf, tt);
+#pragma unroll
+    for (u32 i = 0; i < kPer; ++i) {
+      const u32 g = tid * kPer + i;
+      if (g < G) {
+        s_off[0][g] = ew;
+        s_off[1][g] = en;
+        s_off[2][g] = et;
+      }
+      ew += nw[i];
+      en += nn[i];
+      et += (nw[i] + kMatTile - 1) / kMatTile;
+    }
+    if (tid == 0) {
+      s_off[0][G] = tw;
+      s_off[1][G] = tn;
+      s_off[2][G] = tt;
+    }
+    __syncthreads();
+    const bool ok = totals_ok(p, tw, tn, tt);
+    v.out_word_off = s_off[0];
+    v.out_node_off = s_off[1];
+    v.tile_off = s_off[2];
+    v.n_tiles = ok ? (u32)tt : 0u;
+    v.ok = ok ? 1u : 0u;
+    if (blockIdx.x == 0) {
+      if (bad) raise_status(p.d_status, FDY_ST_BAD_INDEX);
+      if (tid == 0 && !ok) raise_status(p.d_status, FDY_ST_BAD_SIZE);
+    }
+  } else {
+    v.out_word_off = p.ws.out_word_off;
+    v.out_node_off = p.ws.out_node_off;
+    v.tile_off = p.ws.tile_off;
+    v.n_tiles = p.ws.hdr->n_tiles;
+    v.ok = p.ws.hdr->ok;
+  }
   const u32 b = blockIdx.x;
-  if (b < nb_tiles) prep_tile(p, b * 256 + threadIdx.x);
-  else if (b < nb_tiles + nb_patch) prep_patch(p, (u64)(b - nb_tiles) * 256 + threadIdx.x);
-  else write_dims(p, (u64)(b - nb_tiles - nb_patch) * 256 + threadIdx.x);
+  if (b < nb_tiles) prep_tiles_block(p, v, b, s_lo);
+  else if (b < nb_tiles + nb_patch) prep_patch(p, v, (u64)(b - nb_tiles) * 256 + threadIdx.x);
+  else write_dims(p, v, (u64)(b - nb_tiles - nb_patch) * 256 + threadIdx.x);
 }
 
 bool desc_ok(const fdy_mat_desc* d) {
@@ -459,17 +566,25 @@ extern "C" int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words
   hipStream_t stream = (hipStream_t)hip_stream;
   (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
 
-  prof_begin(FDY_PROF_MAT_PREP_GRAPHS, stream);
-  hipLaunchKernelGGL(mat_prep_graphs_kernel, dim3(1), dim3(1024), 0, stream, p);
-  prof_end(FDY_PROF_MAT_PREP_GRAPHS, stream);
-  FDY_HIP_TRY(hipGetLastError());
-  const u32 nb_tiles = (p.ws.max_tiles + 255) / 256;
+  const bool own_sums = d.n_graphs <= kOwnSumsMax;
+  if (!own_sums) {
+    prof_begin(FDY_PROF_MAT_PREP_GRAPHS, stream);
+    hipLaunchKernelGGL(mat_prep_graphs_kernel, dim3(1), dim3(1024), 0, stream, p);
+    prof_end(FDY_PROF_MAT_PREP_GRAPHS, stream);
+    FDY_HIP_TRY(hipGetLastError());
+  }
+  u32 nb_tiles = (p.ws.max_tiles + kPrepTiles - 1) / kPrepTiles;
   const u32 nb_patch = p.d.map_rank ? (u32)(((u64)p.ws.max_tiles * p.d.n_ranks + 255) / 256) : 0;
   const u32 nb_dims = (d_out_dims && d.out_nodes_total) ? (u32)((d.out_nodes_total + 255) / 256) : 0;
+  if (own_sums && nb_tiles + nb_patch + nb_dims == 0) nb_tiles = 1;  // someone has to verify the totals
   if (nb_tiles + nb_patch + nb_dims) {
     prof_begin(FDY_PROF_MAT_PREP_TILES, stream);
-    hipLaunchKernelGGL(mat_prep_tiles_kernel, dim3(nb_tiles + nb_patch + nb_dims), dim3(256), 0, stream, p,
-                       nb_tiles, nb_patch);
+    if (own_sums)
+      hipLaunchKernelGGL(mat_prep_tiles_kernel<true>, dim3(nb_tiles + nb_patch + nb_dims), dim3(256), 0, stream,
+                         p, nb_tiles, nb_patch);
+    else
+      hipLaunchKernelGGL(mat_prep_tiles_kernel<false>, dim3(nb_tiles + nb_patch + nb_dims), dim3(256), 0, stream,
+                         p, nb_tiles, nb_patch);
     prof_end(FDY_PROF_MAT_PREP_TILES, stream);
     FDY_HIP_TRY(hipGetLastError());
   }

@@ -583,6 +583,26 @@ def test_materialize_tile_boundaries_and_empty_graphs(hip, oracle):
     check_mat(hip, oracle, mp, tag="tile boundaries", want_dims=False)
 
 
+def replicate_outputs(mp, times):
+    """The same problem with every output graph listed `times` times over (lists repeated)."""
+    kw = {n: getattr(mp, n) for n in MatProblem.ARRAYS}
+    kw["graph_tmpl"] = np.tile(mp.graph_tmpl, times)
+    for lst, off in (("ovr", "ovr_off"), ("govr", "govr_off")):
+        o = getattr(mp, off).astype(np.int64)
+        kw[lst] = np.tile(getattr(mp, lst), times)
+        kw[off] = np.concatenate([[0]] + [o[1:] + k * o[-1] for k in range(times)])
+    return MatProblem(n_ranks=mp.n_ranks, **kw)
+
+
+@pytest.mark.parametrize("idx,times", [(2, 128), (2, 129), (3, 300)])
+def test_materialize_more_than_1024_graphs(hip, oracle, idx, times):
+    """Up to 1024 output graphs the tile launch computes the per-graph prefix sums itself; above
+    that a launch of its own does.  8 x 128 = 1024 graphs is the last case of the first kind,
+    8 x 129 and 5 x 300 are of the second; with launch dimensions, overrides and rank patches."""
+    mp = replicate_outputs(problem(oracle, small(idx), maps=[0, 1] if idx == 3 else None), times)
+    check_mat(hip, oracle, mp, tag=f"{mp.G} graphs")
+
+
 def test_materialize_bad_inputs_are_flagged_not_faulting(hip, oracle):
     import paper_2604_06664_amd as fdy
 
