@@ -661,11 +661,15 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   // level-0 staging lies between them): the workgroups that start together then hold
   // interleaved chunks rather than pairs of neighbours, which keeps chunk order close to the
   // order in time that the look-back counts on.
+  // With no more chunks than workgroups every workgroup's first draw is its only chunk: the
+  // later draws would all come back past the end, and each costs its turn at the one counter
+  // (small inputs are bound by such latencies).
+  const bool single = (u64)gridDim.x * kChunk >= p.n_sub;
   if (tid == 0) s_next[0] = atomicAdd(p.ticket, (u32)kChunk);
   for (u32 i = tid; i < p.top_n; i += kBlock) top[i] = p.top[i];
   for (u32 i = tid; i < n_bst; i += kBlock) bst[i] = p.bstart[i];
   __syncthreads();
-  if (tid == 0) s_next[1] = atomicAdd(p.ticket, (u32)kChunk);
+  if (tid == 0) s_next[1] = single ? p.n_sub : atomicAdd(p.ticket, (u32)kChunk);
   u32 base = s_next[0];
   __syncthreads();
   u32 nbase = s_next[1];
@@ -693,7 +697,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   for (u32 round = 0; base < p.n_sub; ++round) {
     const u32 b = round & 1;
     u32 next = 0;
-    if (tid == 0) next = atomicAdd(p.ticket, (u32)kChunk);  // round + 2's chunk, published at this round's barrier
+    if (tid == 0) next = single ? p.n_sub : atomicAdd(p.ticket, (u32)kChunk);  // round + 2's chunk, published at this round's barrier
     cur.base = base;
     cur.b = b;
 
