@@ -82,7 +82,6 @@ constexpr int kWpl = 2 * kLoads;               // words per lane per sub-tile
 constexpr int kSub = 64 * kWpl;                // words per sub-tile (512)
 constexpr int kGroupsBig = 2, kGBig = 2;       // large inputs: a wave takes 2 groups of 2 sub-tiles per ticket
 constexpr int kGroupsSmall = 1, kGSmall = 1;   // small inputs: more, smaller chunks fill the chip
-constexpr u32 kSmallSubTiles = 256 * kWaves * kGroupsBig * kGBig * 2;  // below this many sub-tiles: small
 constexpr int kQcap = 192;                     // queue entries per wave
 constexpr int kRegRounds = 3;                  // rounds of 64 candidates per sub-tile kept in registers
 constexpr int kMaxMid = 6;                     // packed levels in global memory
@@ -1119,7 +1118,9 @@ bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
   pl->leaf_lines = (levels >= 2 && pl->mid_len[0]) ? (n_alloc + 7) / 8 : 0;
   pl->off_leaf = off;
   off += align256((size_t)pl->leaf_lines * 64);
-  const bool small = pl->n_sub < kSmallSubTiles;
+  // measured crossover: from 4,096 sub-tiles (2 Mi words) on the large chunks win even though
+  // they leave compute units without a chunk; below, more and smaller chunks do
+  const bool small = pl->n_sub < (1u << fdy__tune_get(FDY_TUNE_SCAN_SMALL_LOG2));
   pl->groups = small ? kGroupsSmall : kGroupsBig;
   pl->g = small ? kGSmall : kGBig;
   const u32 chunk = kWaves * pl->groups * pl->g;

@@ -13,6 +13,7 @@ enum {
   FDY_TUNE_SCAN_WG_PER_CU = 1,  /* persistent scan workgroups launched per compute unit    */
   FDY_TUNE_SCAN_SPIN_LIMIT = 2, /* polls of a predecessor tile before giving up            */
   FDY_TUNE_MAT_MAP_GROUP = 3,     /* base maps per materialize workgroup, 0 = automatic      */
+  FDY_TUNE_SCAN_SMALL_LOG2 = 4, /* inputs below 2^this sub-tiles use the small-chunk scan   */
   FDY_TUNE_COUNT = 8
 };
 

@@ -54,7 +54,8 @@ CASES = [  # (words, allocations, shape, density, top_log2)
     (40001, 5000, "clustered", 0.6, 8), (100000, 70000, "uniform", 0.2, 10), (100000, 70000, "huge", 0.4, 12),
     (262144, 200000, "clustered", 0.33, 14), (262145, 200000, "wide", 0.15, 13), (300000, 16385, "uniform", 0.25, 11),
     (1 << 20, 131073, "clustered", 0.1, 14), (1 << 20, 9, "huge", 1.0, 14),
-    (16384 * 512 - 1, 1000, "uniform", 0.02, 14), (16384 * 512 + 513, 300000, "clustered", 0.2, 14),
+    (4096 * 512 - 1, 1000, "uniform", 0.02, 14), (4096 * 512 + 513, 300000, "clustered", 0.2, 14),
+    (16384 * 512 + 513, 70000, "uniform", 0.1, 14),
 ]
 
 
