@@ -271,8 +271,8 @@ __device__ __forceinline__ void stage_tile(u64* buf, const u64* src, u64 src_wor
 // share of the tile's relocation entries (registers; the slice holds at most kMatTile
 // entries, kMatPre per thread).  Per map only the base-map gathers, the scatter into LDS
 // and the store of the tile repeat.  Relocations and overrides hit the same words for every
-// map, so the LDS copy needs no refresh between maps; rank patches differ per map, so with
-// patches the tile is staged again (from L2) for every map after the first.
+// map, so the LDS copy needs no refresh between maps; rank patches differ per map, so the
+// words the previous map's rank patched are given their template values back first.
 constexpr int kMatPre = kMatTile / kMatBlock;
 constexpr int kMatStore = kMatTile / (2 * kMatBlock);  // 16-byte chunks per thread
 
@@ -313,9 +313,15 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
   const bool has_ovr = ent.ovr_lo < ent.ovr_hi;
   const bool has_patch = d.map_rank != nullptr;
   __syncthreads();
+  uint2 undo = make_uint2(0, 0);  // the previous map's patch slice
   for (u32 m = m0; m < m1; ++m) {
     if (has_patch && m != m0) {
-      stage_tile(buf, src, ent.src_word, n, tid);
+      // take the previous rank's patches back out: those words get the template's value again
+      // (relocations and overrides that touch them are applied again below, as for every map)
+      for (u32 q = undo.x + tid; q < undo.y; q += kMatBlock) {
+        const u64 k = (u64)d.patch[q].word - ent.k0;
+        if (k < n) buf[k] = src[k];
+      }
       __syncthreads();
     }
     // c2: rebase
@@ -343,6 +349,7 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
       const u32 rk_m = d.map_rank[m];
       if (rk_m < d.n_ranks) {
         const uint2 pr = p.ws.tile_patch[(u64)j * d.n_ranks + rk_m];
+        undo = pr;
         for (u32 q = pr.x + tid; q < pr.y; q += kMatBlock) {
           const u64x2 raw = *reinterpret_cast<const u64x2*>(&d.patch[q]);
           const u64 k = (u64)(u32)raw.x - ent.k0;
@@ -351,6 +358,7 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
         }
       } else {
         bad = true;
+        undo = make_uint2(0, 0);
       }
     }
     __syncthreads();
@@ -590,9 +598,8 @@ extern "C" int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words
   }
   if (p.ws.max_tiles) {
     prof_begin(FDY_PROF_MAT_MAIN, stream);
-    // Base maps per workgroup.  Measured on MI355X, groups above 2 (4 with rank patches, where
-    // the tile is staged again per map anyway) lose more to the coarser tail of the launch
-    // than they save in repeated loads.
+    // Base maps per workgroup.  Measured on MI355X, groups above 2 (4 with rank patches) lose
+    // more to the coarser tail of the launch than they save in repeated loads.
     u32 mg = (u32)fdy__tune_get(FDY_TUNE_MAT_MAP_GROUP);
     if (mg == 0) mg = d.map_rank ? 4 : 2;
     p.map_group = mg < d.n_maps ? mg : d.n_maps;
