@@ -50,7 +50,7 @@ def test_install_at_decode_graph_scale():
     toy.install_scale_check.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_double),
                                         C.c_char_p, C.c_int]
     msg = C.create_string_buffer(1024)
-    stats = (C.c_double * 8)()
+    stats = (C.c_double * 9)()
     print("[install] 576 nodes x 67 graphs x 2 maps", flush=True)
     rc = toy.install_scale_check(576, 67, 2, stats, msg, 1024)
     print("[install]", msg.value.decode(), flush=True)
