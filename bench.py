@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # profiles/whole_path_config5_kernel_stats_and_traffic.txt and are reported only for the
 # workloads and kernels they were collected on.
 PMC_TRAFFIC_BYTES = {
-    (4, "scan_kernel"): 2_980_048_891 + 216_751_479,
-    (4, "mat_main_kernel"): 2_604_844_926 + 1_073_899_118,
-    (5, "mat_main_kernel"): 71_208_545 + 1_575_492_384,
+    (4, "scan_kernel"): 2_986_553_416 + 216_749_829,
+    (4, "mat_main_kernel"): 2_604_881_000 + 1_073_933_659,
+    (5, "mat_main_kernel"): 71_210_061 + 1_575_536_302,
 }
 
 
