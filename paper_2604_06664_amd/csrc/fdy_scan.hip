@@ -387,6 +387,24 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
 
 // Outcome of the span pre-filter for one sub-tile as a wave holds it (8 words per lane): which
 // words are candidates, and each candidate's rank in word order (load k, lane, half).
+// Stages the level-0 keys and the bucket index in LDS with 16-byte copies.  Both arrays are
+// padded to 256 bytes in the workspace and to 16 bytes in LDS, so whole 16-byte pieces can be
+// copied past their last entry; a top level of two keys (8 bytes) is copied key by key.
+__device__ __forceinline__ void stage_level0(const ScanParams& p, u32* top, unsigned short* bst, u32 n_bst) {
+  const u32 tid = threadIdx.x;
+  if (p.top_n >= 4) {
+    const uint4* src = reinterpret_cast<const uint4*>(p.top);
+    uint4* dst = reinterpret_cast<uint4*>(top);
+    for (u32 i = tid; i < p.top_n / 4; i += kBlock) dst[i] = src[i];
+    const uint4* bsrc = reinterpret_cast<const uint4*>(p.bstart);
+    uint4* bdst = reinterpret_cast<uint4*>(bst);
+    for (u32 i = tid; i < (n_bst * 2 + 15) / 16; i += kBlock) bdst[i] = bsrc[i];
+  } else {
+    for (u32 i = tid; i < p.top_n; i += kBlock) top[i] = p.top[i];
+    for (u32 i = tid; i < n_bst; i += kBlock) bst[i] = p.bstart[i];
+  }
+}
+
 struct Filt {
   bool c[kWpl];
   u32 crank[kWpl];
@@ -665,8 +683,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   // (small inputs are bound by such latencies).
   const bool single = (u64)gridDim.x * kChunk >= p.n_sub;
   if (tid == 0) s_next[0] = atomicAdd(p.ticket, (u32)kChunk);
-  for (u32 i = tid; i < p.top_n; i += kBlock) top[i] = p.top[i];
-  for (u32 i = tid; i < n_bst; i += kBlock) bst[i] = p.bstart[i];
+  stage_level0(p, top, bst, n_bst);
   __syncthreads();
   if (tid == 0) s_next[1] = single ? p.n_sub : atomicAdd(p.ticket, (u32)kChunk);
   u32 base = s_next[0];
@@ -889,8 +906,7 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
   const u32 wave = tid >> 6;
   u64* qw = reinterpret_cast<u64*>(qbase) + wave * kQwave;
   unsigned short* qi = reinterpret_cast<unsigned short*>(qbase + (size_t)kWaves * kQwave * 8) + wave * kQwave;
-  for (u32 i = tid; i < p.top_n; i += kBlock) top[i] = p.top[i];
-  for (u32 i = tid; i < n_bst; i += kBlock) bst[i] = p.bstart[i];
+  stage_level0(p, top, bst, n_bst);
   __syncthreads();
 
   const u64 span_lo = p.table[0].base;
