@@ -315,7 +315,8 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
     }
   }
   // Leaf: 8 consecutive entries of the table.  Large tables are not read directly: a packed
-  // copy holds each line in 64 bytes, {base - first base of the line, size} in 32 bits each,
+  // copy holds each line in 64 bytes, {base - first base of the line, size} in 32 bits each
+  // after a shift by the line's common trailing zeros,
   // which halves what the candidate has to pull through the memory fabric (this fetch is what
   // bounds the scan when the table outgrows L2).  A line whose values do not fit, and the
   // last, partial line, are marked and read from the table itself; so are all lines of small
@@ -343,7 +344,8 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
         const uint4 (&q)[4] = ql[c];
         if (q[0].x != 0xffffffffu) {
           exact = false;
-          const u64 x = w[c] - gb[c];
+          const u32 sh = q[0].x;  // the line's shift (at most 31); the first entry's distance is 0
+          const u64 x = (w[c] - gb[c]) >> sh;  // floor: entry h lies at or below w iff its distance <= x
           u32 d = 0, z = q[0].y, at = 0;
 #pragma unroll
           for (int h = 1; h < 8; ++h) {
@@ -355,8 +357,8 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
               at = h;
             }
           }
-          e[c].x = gb[c] + d;
-          e[c].y = z;
+          e[c].x = gb[c] + ((u64)d << sh);
+          e[c].y = (u64)z << sh;
           n[c] = n[c] * 8 + at;
         }
       }
@@ -1028,23 +1030,35 @@ __global__ void scan_init_kernel(ScanInit a) {
     }
   }
   if (i < a.leaf_lines) {
-    // line i of the packed table: {base - base of the line's first entry, size} per entry in
-    // 32 bits each; first word 0xffffffff: "read this line from the table" (a value does not
-    // fit, or the line is the last, partial one)
+    // line i of the packed table: {(base - base of the line's first entry) >> s, size >> s} per
+    // entry in 32 bits each, s the largest shift that loses no bit of any of the sixteen values
+    // (allocators hand out aligned blocks, so s is usually 9 or more and regions far beyond
+    // 4 GiB still pack).  The first entry's distance is 0 by definition; its slot holds s.
+    // First word 0xffffffff: "read this line from the table" (a value does not fit even
+    // shifted, or the line is the last, partial one).
     const u64 e0 = i * 8;
     u32 d[8] = {0, 0, 0, 0, 0, 0, 0, 0}, z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     bool fits = e0 + 8 <= a.n_alloc;
+    u32 sh = 0;
     if (fits) {
       const u64 b0 = a.table[e0].base;
+      u64 dh[8], zh[8], any = 0;
 #pragma unroll
       for (int h = 0; h < 8; ++h) {
-        const u64 dh = a.table[e0 + h].base - b0, zh = a.table[e0 + h].size;
-        fits = fits && (dh >> 32) == 0 && (zh >> 32) == 0;
-        d[h] = (u32)dh;
-        z[h] = (u32)zh;
+        dh[h] = a.table[e0 + h].base - b0;
+        zh[h] = a.table[e0 + h].size;
+        any |= dh[h] | zh[h];
       }
+      sh = any ? (u32)__ffsll((long long)any) - 1u : 0u;  // trailing zeros common to all values
+      if (sh > 31u) sh = 31u;
+#pragma unroll
+      for (int h = 0; h < 8; ++h) {
+        fits = fits && ((dh[h] >> sh) >> 32) == 0 && ((zh[h] >> sh) >> 32) == 0;
+        d[h] = (u32)(dh[h] >> sh);
+        z[h] = (u32)(zh[h] >> sh);
+      }
+      d[0] = sh;
     }
-    // d[0] is 0 for a packed line, so 0xffffffff there is unambiguous
 #pragma unroll
     for (int h = 0; h < 4; ++h)
       a.leaf[i * 4 + h] = fits ? make_uint4(d[2 * h], z[2 * h], d[2 * h + 1], z[2 * h + 1])

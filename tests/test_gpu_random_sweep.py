@@ -23,12 +23,22 @@ def random_table(rng, A, shape):
     elif shape == "huge":  # sizes and gaps beyond 32 bits: no table line can be packed
         size = rng.integers(1 << 33, 1 << 40, A).astype(np.uint64)
         gap = rng.integers(0, 1 << 36, A).astype(np.uint64)
+    elif shape == "aligned":  # allocator-like: aligned blocks, a few of them far beyond 4 GiB, so
+        # that the packed table copy needs its per-line shift (and some lines several shifts)
+        k = rng.choice([9, 12, 21], A).astype(np.uint64)
+        size = rng.integers(1, 1 << 12, A).astype(np.uint64) << k
+        big = rng.random(A) < 0.05
+        size = np.where(big, rng.integers(1 << 12, 1 << 17, A).astype(np.uint64) << np.uint64(21), size)
+        gap = (rng.integers(0, 4, A).astype(np.uint64) << k)
     else:  # "wide": a span of most of the 64-bit space (key shift at its largest)
         size = rng.integers(1, 1 << 30, A).astype(np.uint64)
         gap = (rng.integers(0, 1 << 62, A) // max(A, 1)).astype(np.uint64)
     start = np.concatenate([[0], np.cumsum(size + gap)[:-1]]).astype(np.uint64)
     t = np.zeros(A, L.ALLOC)
-    t["base"], t["size"] = np.uint64(rng.integers(1, 1 << 40)) + start, size
+    first = np.uint64(rng.integers(1, 1 << 40))
+    if shape == "aligned":
+        first = first >> np.uint64(21) << np.uint64(21)
+    t["base"], t["size"] = first + start, size
     return t
 
 
@@ -56,6 +66,7 @@ CASES = [  # (words, allocations, shape, density, top_log2)
     (1 << 20, 131073, "clustered", 0.1, 14), (1 << 20, 9, "huge", 1.0, 14),
     (4096 * 512 - 1, 1000, "uniform", 0.02, 14), (4096 * 512 + 513, 300000, "clustered", 0.2, 14),
     (16384 * 512 + 513, 70000, "uniform", 0.1, 14),
+    (300000, 70000, "aligned", 0.3, 14), (1 << 20, 200000, "aligned", 0.15, 12), (50000, 40, "aligned", 0.5, 3),
 ]
 
 
