@@ -101,6 +101,8 @@ struct ScanParams {
   u32 bucket_log2;  // log2(n_buckets)
   const u64* mid[kMaxMid];  // mid[j-1] = every 8^j-th base, padded with ~0
   const uint4* leaf;        // packed table, 64 bytes per 8 entries (null: not built)
+  const uint4* cmid;        // compact copy of packed level 1, 32 bytes per node of 8 keys (null: not built)
+  const uint4* cleaf;       // compact copy of the table, 32 bytes per 8 entries (null: not built)
   u64* cstate;     // [n_chunks] per-chunk totals / inclusive prefixes
   u32 n_sub;       // sub-tiles
   u32 top_n;       // power of two
@@ -211,13 +213,130 @@ struct Found {
   u64 offset;
 };
 
+// Level 1's choice (the last key of the node that is not above w: its place, and the key itself in gb)
+// from the 32-byte form of a node: four 64-bit words {key 0; f1 f2 f3; f4 f5 f6;
+// f7 s}, f_h = (key h - key 0) >> s in 21 bits each, s (6 bits, behind f7) the trailing zeros
+// common to the seven distances.  False: the node is marked (last word ~0) because a distance
+// does not fit or a key is padding; nothing is returned then.
+constexpr u32 kCnodeField = (1u << 21) - 1;
+__device__ __forceinline__ bool pick_cnode(const uint4 (&q)[2], u64 w, u32& at, u64& gb) {
+  const u64 a0 = (u64)q[0].x | ((u64)q[0].y << 32), a1 = (u64)q[0].z | ((u64)q[0].w << 32);
+  const u64 a2 = (u64)q[1].x | ((u64)q[1].y << 32), a3 = (u64)q[1].z | ((u64)q[1].w << 32);
+  if (a3 == ~0ull) return false;
+  const u32 s = (u32)(a3 >> 21) & 63u;
+  const u64 x64 = (w - a0) >> s;  // floor: key h lies at or below w iff its distance <= x
+  const u32 x = (x64 >> 32) ? 0xffffffffu : (u32)x64;
+  const u32 f[8] = {0u,
+                    (u32)a1 & kCnodeField,
+                    (u32)(a1 >> 21) & kCnodeField,
+                    (u32)(a1 >> 42) & kCnodeField,
+                    (u32)a2 & kCnodeField,
+                    (u32)(a2 >> 21) & kCnodeField,
+                    (u32)(a2 >> 42) & kCnodeField,
+                    (u32)a3 & kCnodeField};
+  u32 d = 0;
+  at = 0;
+#pragma unroll
+  for (int h = 1; h < 8; ++h)
+    if (f[h] <= x) {
+      at = h;
+      d = f[h];
+    }
+  gb = a0 + ((u64)d << s);
+  return true;
+}
+
+// The entry that w falls at or behind (entry index into n, exact base and size into e) from the
+// 32-byte form of a table line: eight 32-bit words, distance >> sd in the high
+// 12 bits and size >> ss in the low 20; the first entry's distance is 0 and its 12 bits hold
+// sd (low six) and ss.  False: the line is marked (first word ~0).
+__device__ __forceinline__ bool pick_cline(const uint4 (&q)[2], u64 w, u64 gb, u64& n, u64x2& e) {
+  if (q[0].x == 0xffffffffu) return false;
+  const u32 sd = (q[0].x >> 20) & 63u, ss = q[0].x >> 26;
+  const u64 x = (w - gb) >> sd;
+  // entry h lies at or below w iff its distance <= x, i.e. iff its whole word <= x's word with
+  // all size bits set
+  const u32 xt = x >= 4095u ? 0xffffffffu : (((u32)x << 20) | 0xfffffu);
+  const u32 v[8] = {q[0].x & 0xfffffu, q[0].y, q[0].z, q[0].w, q[1].x, q[1].y, q[1].z, q[1].w};
+  u32 pick = v[0], at = 0;
+#pragma unroll
+  for (int h = 1; h < 8; ++h)
+    if (v[h] <= xt) {
+      pick = v[h];
+      at = h;
+    }
+  e.x = gb + ((u64)(pick >> 20) << sd);
+  e.y = (u64)(pick & 0xfffffu) << ss;
+  n = n * 8 + at;
+  return true;
+}
+
+// Three dependent probes inside the table line itself: few registers, rarely taken.
+__device__ __forceinline__ void probe_line(const ScanParams& p, u64 w, u64& n, u64x2& e) {
+  n *= 8;
+  e = *reinterpret_cast<const u64x2*>(&p.table[n]);
+#pragma unroll 1
+  for (u32 step = 4; step; step >>= 1) {
+    if (n + step < p.n_alloc) {
+      const u64x2 q = *reinterpret_cast<const u64x2*>(&p.table[n + step]);
+      if (q.x <= w) {
+        n += step;
+        e = q;
+      }
+    }
+  }
+}
+
+// The 64-byte node or line for the rare candidate whose compact node or line is marked: the
+// place is counted (keys and distances ascend) and the chosen value read again, which needs
+// no node held in registers beside the interleaved chains.
+__device__ __forceinline__ u32 probe_node(const u64* m, u64 first_key, u64 w, u64& gb) {
+  u32 at = 0;
+#pragma unroll
+  for (int h = 1; h < 8; ++h) at += m[first_key + h] <= w ? 1u : 0u;
+  gb = m[first_key + at];
+  return at;
+}
+
+__device__ __forceinline__ bool probe_wide_line(const uint4* leaf, u64 w, u64 gb, u64& n, u64x2& e) {
+  const uint4* line = leaf + n * 4;
+  const uint4 q0 = line[0];
+  if (q0.x == 0xffffffffu) return false;
+  const uint4 q1 = line[1], q2 = line[2], q3 = line[3];
+  const u32 sh = q0.x;
+  const u64 x = (w - gb) >> sh;
+  const u32 at = ((u64)q0.z <= x ? 1u : 0u) + ((u64)q1.x <= x ? 1u : 0u) + ((u64)q1.z <= x ? 1u : 0u) +
+                 ((u64)q2.x <= x ? 1u : 0u) + ((u64)q2.z <= x ? 1u : 0u) + ((u64)q3.x <= x ? 1u : 0u) +
+                 ((u64)q3.z <= x ? 1u : 0u);
+  const uint2 dz = reinterpret_cast<const uint2*>(line)[at];
+  e.x = gb + ((u64)(at ? dz.x : 0u) << sh);
+  e.y = (u64)dz.y << sh;
+  n = n * 8 + at;
+  return true;
+}
+
+// Whether a compact array is worth reading for this table: where most nodes are marked a
+// candidate would pay the compact fetch and then the wide one, so the choice is made per
+// table, from 64 evenly spaced nodes (all lanes of the wave take part).
+__device__ __forceinline__ bool mostly_packed(const uint4* arr, u32 n_nodes, bool node_form) {
+  if (!arr || !n_nodes) return false;
+  const u64 i = ((u64)lane_id() * n_nodes) >> 6;
+  const uint4 q = arr[i * 2 + (node_form ? 1 : 0)];
+  const bool marked = node_form ? (q.z & q.w) == 0xffffffffu : q.x == 0xffffffffu;
+  return __popcll(ballot(marked)) <= 16;
+}
+
+constexpr u32 kUseCmid = 1u << 16, kUseCleaf = 1u << 17;  // flags that travel with the shifts
+
 // Interval search for N candidates per lane at once (each w lies inside the table's span).
 // The N chains are independent; writing every step for all of them lets their LDS and
 // global round trips overlap, which is what the dependent steps of one chain cannot do.
 template <int N>
 __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
-                                       const u64 (&w)[N], Found (&f)[N]) {
-  const u32 key_shift = shifts & 0xffu, bucket_shift = shifts >> 8;
+                                       const u64 (&w)[N], Found (&f)[N], u32& marked) {
+  const u32 key_shift = shifts & 0xffu, bucket_shift = (shifts >> 8) & 0xffu;
+  const uint4* cmid = (shifts & kUseCmid) ? p.cmid : nullptr;
+  const uint4* cleaf = (shifts & kUseCleaf) ? p.cleaf : nullptr;
   u32 kw[N], i[N];
   u64 n[N];
 #pragma unroll
@@ -283,12 +402,33 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
   // about what a single probe does, where three dependent probes cost three round trips and
   // three requests: the vector L1 is far too small to keep a node between two probes of the
   // same lane).  The child is the last key not above w: keys are ascending, padded with ~0,
-  // and the first key of the node is known not to exceed w.
+  // and the first key of the node is known not to exceed w.  Level 1 is read through its
+  // 32-byte copy when the table has one that mostly packs: two loads per candidate instead of
+  // four (a lane's load costs the vector memory unit its turn whether or not the line merges).
   u64 gb[N];  // exact base of the first entry of the candidate's table line (level 1's key)
 #pragma unroll
   for (int c = 0; c < N; ++c) gb[c] = 0;
   for (int j = (int)p.levels - 1; j >= 1; --j) {
     const u64* m = p.mid[j - 1];
+    if (j == 1 && cmid) {
+      uint4 cq[N][2];
+#pragma unroll
+      for (int c = 0; c < N; ++c) {
+        cq[c][0] = cmid[n[c] * 2];
+        cq[c][1] = cmid[n[c] * 2 + 1];
+      }
+      __builtin_amdgcn_sched_barrier(0);  // every chain's node is requested before the first is used
+#pragma unroll
+      for (int c = 0; c < N; ++c) {
+        n[c] *= 8;
+        u32 at;
+        const bool packed = pick_cnode(cq[c], w[c], at, gb[c]);
+        if (!packed) at = probe_node(m, n[c], w[c], gb[c]);  // a marked node
+        marked += (u32)__popcll(ballot(!packed));
+        n[c] += at;
+      }
+      continue;
+    }
     u64x2 k[N][4];
 #pragma unroll
     for (int c = 0; c < N; ++c) {
@@ -318,15 +458,32 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
   // copy holds each line in 64 bytes, {base - first base of the line, size} in 32 bits each
   // after a shift by the line's common trailing zeros,
   // which halves what the candidate has to pull through the memory fabric (this fetch is what
-  // bounds the scan when the table outgrows L2).  A line whose values do not fit, and the
-  // last, partial line, are marked and read from the table itself; so are all lines of small
-  // tables, which stay in L2 anyway.  Either way the whole line is fetched at once, one
-  // candidate after the other (the loads in flight per lane already cover the latency; more
-  // would only cost registers).
+  // bounds the scan when the table outgrows L2), and where the lines mostly allow it a
+  // compact copy holds them in 32 bytes (12-bit distances, 20-bit sizes, a shift for each),
+  // which halves it again and lets most of the copy stay in an XCD's L2.  A line whose values
+  // do not fit the compact form is marked there and read from the 64-byte copy; one that does
+  // not fit that either, and the last, partial line, are marked and read from the table
+  // itself; so are all lines of small tables, which stay in L2 anyway.  Either way the whole
+  // line is fetched at once.
   u64x2 e[N];
   if (p.levels == 0) {
 #pragma unroll
     for (int c = 0; c < N; ++c) e[c] = *reinterpret_cast<const u64x2*>(&p.table[n[c]]);
+  } else if (cleaf) {
+    uint4 cq[N][2];
+#pragma unroll
+    for (int c = 0; c < N; ++c) {
+      cq[c][0] = cleaf[n[c] * 2];
+      cq[c][1] = cleaf[n[c] * 2 + 1];
+    }
+    __builtin_amdgcn_sched_barrier(0);  // every chain's line is requested before the first is used
+#pragma unroll
+    for (int c = 0; c < N; ++c) {
+      const bool packed = pick_cline(cq[c], w[c], gb[c], n[c], e[c]);
+      // a marked line: the 64-byte copy, then the table
+      if (!packed && !probe_wide_line(p.leaf, w[c], gb[c], n[c], e[c])) probe_line(p, w[c], n[c], e[c]);
+      marked += (u32)__popcll(ballot(!packed));
+    }
   } else {
     uint4 ql[N][4];
     if (p.leaf) {
@@ -362,20 +519,9 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
           n[c] = n[c] * 8 + at;
         }
       }
-      if (exact) {  // three dependent probes inside the table line: few registers, rarely taken
-        n[c] *= 8;
-        e[c] = *reinterpret_cast<const u64x2*>(&p.table[n[c]]);
-#pragma unroll 1
-        for (u32 step = 4; step; step >>= 1) {
-          if (n[c] + step < p.n_alloc) {
-            const u64x2 q = *reinterpret_cast<const u64x2*>(&p.table[n[c] + step]);
-            if (q.x <= w[c]) {
-              n[c] += step;
-              e[c] = q;
-            }
-          }
-        }
-      }
+      // one candidate after the other (the loads in flight per lane already cover the
+      // latency; more would only cost registers)
+      if (exact) probe_line(p, w[c], n[c], e[c]);
       __builtin_amdgcn_sched_barrier(0);  // keep the next candidate's loads behind this one's
     }
   }
@@ -539,7 +685,7 @@ __device__ __forceinline__ void store_reloc(const ScanParams& p, u64 at, u32 wor
 template <bool kHalf>
 __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt& t, const u32* top,
                           u64 span_lo, u32 shifts, u64* qw, unsigned short* qi, u64 wbase, bool write,
-                          u64 pos) {
+                          u64 pos, u32& marked) {
   const u32 lane = lane_id();
   const u64 lt = lanemask_lt();
   u64 H = 0;
@@ -551,7 +697,7 @@ __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt&
       const bool valid = q < wn;
       const u64 wv[1] = {valid ? qw[q] : span_lo};
       Found f[1];
-      search<1>(p, top, span_lo, shifts, wv, f);
+      search<1>(p, top, span_lo, shifts, wv, f, marked);
       const bool hit = valid && f[0].hit;
       const u64 b = ballot(hit);
       if (write && hit)
@@ -567,7 +713,7 @@ __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt&
 // result of queue slot 64 k + l.
 template <int N, int R0, int kGR>
 __device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
-                                           const u64* qw, u32 Q, u32 (&reg)[kGR], u64 (&off)[kGR], u64& H) {
+                                           const u64* qw, u32 Q, u32 (&reg)[kGR], u64 (&off)[kGR], u64& H, u32& marked) {
   static_assert(R0 + N <= kGR, "rounds");
   const u32 lane = lane_id();
   u64 wv[N];
@@ -578,7 +724,7 @@ __device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, 
     valid[r] = (R0 + r) * 64 + lane < Q;
     wv[r] = valid[r] ? qw[(R0 + r) * 64 + lane] : span_lo;
   }
-  search<N>(p, top, span_lo, shifts, wv, f);
+  search<N>(p, top, span_lo, shifts, wv, f, marked);
 #pragma unroll
   for (int r = 0; r < N; ++r) {
     const bool hit = valid[r] && f[r].hit;
@@ -591,12 +737,12 @@ __device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, 
 // Rounds [R0, R0 + 3) as far as there are candidates, with as many chains per lane as rounds.
 template <int R0, int kGR>
 __device__ __forceinline__ void run_group(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
-                                          const u64* qw, u32 Q, u32 (&reg)[kGR], u64 (&off)[kGR], u64& H) {
+                                          const u64* qw, u32 Q, u32 (&reg)[kGR], u64 (&off)[kGR], u64& H, u32& marked) {
   if constexpr (R0 + 3 <= kGR) {
     const u32 nr = (Q + 63) >> 6;
-    if (nr >= (u32)R0 + 3) run_rounds<3, R0, kGR>(p, top, span_lo, shifts, qw, Q, reg, off, H);
-    else if (nr == (u32)R0 + 2) run_rounds<2, R0, kGR>(p, top, span_lo, shifts, qw, Q, reg, off, H);
-    else if (nr == (u32)R0 + 1) run_rounds<1, R0, kGR>(p, top, span_lo, shifts, qw, Q, reg, off, H);
+    if (nr >= (u32)R0 + 3) run_rounds<3, R0, kGR>(p, top, span_lo, shifts, qw, Q, reg, off, H, marked);
+    else if (nr == (u32)R0 + 2) run_rounds<2, R0, kGR>(p, top, span_lo, shifts, qw, Q, reg, off, H, marked);
+    else if (nr == (u32)R0 + 1) run_rounds<1, R0, kGR>(p, top, span_lo, shifts, qw, Q, reg, off, H, marked);
   }
 }
 
@@ -646,7 +792,8 @@ __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResu
         Filt t;
         load_words<kHalf>(p, sub, span_lo, w);
         filter_words<kHalf>(w, t, span_lo, span_len);
-        pos += dense_pass<kHalf>(p, w, t, top, span_lo, shifts, qw, qi, (u64)sub * kSub, true, pos);
+        u32 marked = 0;  // not acted upon here
+        pos += dense_pass<kHalf>(p, w, t, top, span_lo, shifts, qw, qi, (u64)sub * kSub, true, pos, marked);
       }
     }
   }
@@ -695,8 +842,15 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   const u64 span_lo = p.table[0].base;
   const u64 span_len = p.table[p.n_alloc - 1].base + p.table[p.n_alloc - 1].size - span_lo;
   // level-0 key shift (low byte) and bucket shift, passed along as one value
-  const u32 shifts = key_shift_for(span_len) |
-                     (bucket_shift_for(span_len, key_shift_for(span_len), p.bucket_log2) << 8);
+  u32 shifts = key_shift_for(span_len) |
+               (bucket_shift_for(span_len, key_shift_for(span_len), p.bucket_log2) << 8) |
+               (mostly_packed(p.cmid, (p.n_alloc + 63) / 64, true) ? kUseCmid : 0u) |
+               (mostly_packed(p.cleaf, (p.n_alloc + 7) / 8, false) ? kUseCleaf : 0u);
+  // Candidates need not spread over the table as its lines do (most pointers of a serving
+  // process point into a few huge regions, whose lines do not pack): a wave counts the marked
+  // nodes and lines its candidates meet and goes back to the 64-byte forms for good once they
+  // are more than a quarter.  Either form gives the same answer.
+  u32 marked = 0, searched = 0;
 
   // The output position of a chunk is looked up one round late: while this round's rows are
   // searched, the previous round's results wait in registers; by the time its prefix is
@@ -742,18 +896,20 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       for (int r = 0; r < kGR; ++r) cur.reg[g][r] = kMiss;
       u64 H = 0;
       if (Q <= (u32)(kGR * 64)) {
-        run_group<0, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H);
-        run_group<3, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H);
-        run_group<6, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H);
+        run_group<0, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H, marked);
+        run_group<3, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H, marked);
+        run_group<6, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H, marked);
       } else {
         for (int r = 0; r < kG; ++r) {
           u64 dw[kWpl];
           Filt t;
           load_words<kHalf>(p, first_sub + r, span_lo, dw);
           filter_words<kHalf>(dw, t, span_lo, span_len);
-          H += dense_pass<kHalf>(p, dw, t, top, span_lo, shifts, qw, qi, (u64)(first_sub + r) * kSub, false, 0);
+          H += dense_pass<kHalf>(p, dw, t, top, span_lo, shifts, qw, qi, (u64)(first_sub + r) * kSub, false, 0, marked);
         }
       }
+      searched += Q;
+      if (marked * 4 > searched + 256) shifts &= ~(kUseCmid | kUseCleaf);
       cur.Q[g] = Q;
       cur.H[g] = (u32)H;
       if (lane == 0) s_cnt[b][g * kWaves + wave] = cur.H[g];
@@ -827,7 +983,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
 // no other wave touches that sub-tile.
 template <int N>
 __device__ __forceinline__ void rebase_rounds(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
-                                              u64* qw, u32 Q, u32 r0, u64& H) {
+                                              u64* qw, u32 Q, u32 r0, u64& H, u32& marked) {
   const u32 lane = lane_id();
   u64 wv[N];
   Found f[N];
@@ -837,7 +993,7 @@ __device__ __forceinline__ void rebase_rounds(const ScanParams& p, const u32* to
     valid[r] = (r0 + r) * 64 + lane < Q;
     wv[r] = valid[r] ? qw[(r0 + r) * 64 + lane] : span_lo;
   }
-  search<N>(p, top, span_lo, shifts, wv, f);
+  search<N>(p, top, span_lo, shifts, wv, f, marked);
   u64 nb[N];
 #pragma unroll
   for (int r = 0; r < N; ++r) nb[r] = valid[r] && f[r].hit ? p.new_base[f[r].region] : 0;
@@ -851,13 +1007,13 @@ __device__ __forceinline__ void rebase_rounds(const ScanParams& p, const u32* to
 
 // Rebases queue entries [0, Q) in place, in rounds of 64, up to three rounds interleaved.
 __device__ __forceinline__ void rebase_queue(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
-                                             u64* qw, u32 Q, u64& H) {
+                                             u64* qw, u32 Q, u64& H, u32& marked) {
   const u32 nr = (Q + 63) >> 6;
   for (u32 r0 = 0; r0 < nr; r0 += 3) {
     const u32 left = nr - r0;
-    if (left >= 3) rebase_rounds<3>(p, top, span_lo, shifts, qw, Q, r0, H);
-    else if (left == 2) rebase_rounds<2>(p, top, span_lo, shifts, qw, Q, r0, H);
-    else rebase_rounds<1>(p, top, span_lo, shifts, qw, Q, r0, H);
+    if (left >= 3) rebase_rounds<3>(p, top, span_lo, shifts, qw, Q, r0, H, marked);
+    else if (left == 2) rebase_rounds<2>(p, top, span_lo, shifts, qw, Q, r0, H, marked);
+    else rebase_rounds<1>(p, top, span_lo, shifts, qw, Q, r0, H, marked);
   }
 }
 
@@ -913,8 +1069,15 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
 
   const u64 span_lo = p.table[0].base;
   const u64 span_len = p.table[p.n_alloc - 1].base + p.table[p.n_alloc - 1].size - span_lo;
-  const u32 shifts = key_shift_for(span_len) |
-                     (bucket_shift_for(span_len, key_shift_for(span_len), p.bucket_log2) << 8);
+  u32 shifts = key_shift_for(span_len) |
+               (bucket_shift_for(span_len, key_shift_for(span_len), p.bucket_log2) << 8) |
+               (mostly_packed(p.cmid, (p.n_alloc + 63) / 64, true) ? kUseCmid : 0u) |
+               (mostly_packed(p.cleaf, (p.n_alloc + 7) / 8, false) ? kUseCleaf : 0u);
+  // Candidates need not spread over the table as its lines do (most pointers of a serving
+  // process point into a few huge regions, whose lines do not pack): a wave counts the marked
+  // nodes and lines its candidates meet and goes back to the 64-byte forms for good once they
+  // are more than a quarter.  Either form gives the same answer.
+  u32 marked = 0, searched = 0;
 
   // consecutive waves of a workgroup take consecutive groups; workgroups stride over the rest
   const u32 n_groups = (p.n_sub + kFusedG - 1) / kFusedG;
@@ -947,7 +1110,7 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
     if (Q <= kQwave) {
 #pragma unroll
       for (int r = 0; r < kFusedG; ++r) enqueue<false>(w[r], t[r], r, 0, t[r].Q, qoff[r], qw, qi);
-      rebase_queue(p, top, span_lo, shifts, qw, Q, H);
+      rebase_queue(p, top, span_lo, shifts, qw, Q, H, marked);
 #pragma unroll
       for (int r = 0; r < kFusedG; ++r) dequeue(w[r], t[r], 0, t[r].Q, qoff[r], qw);
     } else {
@@ -958,7 +1121,7 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
         for (u32 win = 0; win < t[r].Q; win += kQwave) {
           const u32 wn = t[r].Q - win < kQwave ? t[r].Q - win : kQwave;
           enqueue<false>(w[r], t[r], 0, win, wn, 0, qw, qi);
-          rebase_queue(p, top, span_lo, shifts, qw, wn, H);
+          rebase_queue(p, top, span_lo, shifts, qw, wn, H, marked);
           dequeue(w[r], t[r], win, wn, 0, qw);
         }
       };
@@ -966,6 +1129,8 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
       dense_row(std::integral_constant<int, 1>{});
       static_assert(kFusedG == 2, "rows are instantiated by hand");
     }
+    searched += Q;
+    if (marked * 4 > searched + 256) shifts &= ~(kUseCmid | kUseCleaf);
 #pragma unroll
     for (int r = 0; r < kFusedG; ++r) store_words(p, first_sub + r, w[r]);
     if (more) {
@@ -992,6 +1157,9 @@ struct ScanInit {
   u32 mid_len[kMaxMid];
   uint4* leaf;     // packed table lines, or null
   u32 leaf_lines;  // ceil(n_alloc / 8) when built
+  uint4* cleaf;    // compact table lines (as many), or null
+  uint4* cmid;     // compact nodes of packed level 1, or null
+  u32 cmid_nodes;  // ceil(n_alloc / 64) when built
   u32 n_sub;
   u64* cstate;
   u32 n_chunks;
@@ -1036,33 +1204,80 @@ __global__ void scan_init_kernel(ScanInit a) {
     // 4 GiB still pack).  The first entry's distance is 0 by definition; its slot holds s.
     // First word 0xffffffff: "read this line from the table" (a value does not fit even
     // shifted, or the line is the last, partial one).
+    // The compact form of the same line: {distance >> sd : 12 bits, size >> ss : 20 bits} per
+    // entry in one 32-bit word, sd and ss the trailing zeros common to the distances and to the
+    // sizes, kept in the first entry's distance bits (sd low).  First word 0xffffffff (no
+    // packed line has it: sd = ss = 63 leaves no size of 20 set bits): "read the 64-byte line".
     const u64 e0 = i * 8;
-    u32 d[8] = {0, 0, 0, 0, 0, 0, 0, 0}, z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    bool fits = e0 + 8 <= a.n_alloc;
+    u32 d[8] = {0, 0, 0, 0, 0, 0, 0, 0}, z[8] = {0, 0, 0, 0, 0, 0, 0, 0}, cw[8];
+    bool fits = e0 + 8 <= a.n_alloc, cfits = fits;
     u32 sh = 0;
     if (fits) {
       const u64 b0 = a.table[e0].base;
-      u64 dh[8], zh[8], any = 0;
+      u64 dh[8], zh[8], any_d = 0, any_z = 0;
 #pragma unroll
       for (int h = 0; h < 8; ++h) {
         dh[h] = a.table[e0 + h].base - b0;
         zh[h] = a.table[e0 + h].size;
-        any |= dh[h] | zh[h];
+        any_d |= dh[h];
+        any_z |= zh[h];
       }
+      const u64 any = any_d | any_z;
       sh = any ? (u32)__ffsll((long long)any) - 1u : 0u;  // trailing zeros common to all values
       if (sh > 31u) sh = 31u;
+      const u32 sd = any_d ? (u32)__ffsll((long long)any_d) - 1u : 0u;
+      const u32 ss = any_z ? (u32)__ffsll((long long)any_z) - 1u : 0u;
 #pragma unroll
       for (int h = 0; h < 8; ++h) {
         fits = fits && ((dh[h] >> sh) >> 32) == 0 && ((zh[h] >> sh) >> 32) == 0;
         d[h] = (u32)(dh[h] >> sh);
         z[h] = (u32)(zh[h] >> sh);
+        cfits = cfits && ((dh[h] >> sd) >> 12) == 0 && ((zh[h] >> ss) >> 20) == 0;
+        cw[h] = ((u32)(dh[h] >> sd) << 20) | ((u32)(zh[h] >> ss) & 0xfffffu);
       }
       d[0] = sh;
+      cw[0] |= (sd | (ss << 6)) << 20;
     }
 #pragma unroll
     for (int h = 0; h < 4; ++h)
       a.leaf[i * 4 + h] = fits ? make_uint4(d[2 * h], z[2 * h], d[2 * h + 1], z[2 * h + 1])
                                : make_uint4(0xffffffffu, 0, 0xffffffffu, 0);
+    if (a.cleaf) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        a.cleaf[i * 2 + h] = cfits ? make_uint4(cw[4 * h], cw[4 * h + 1], cw[4 * h + 2], cw[4 * h + 3])
+                                   : make_uint4(0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu);
+    }
+  }
+  if (i < a.cmid_nodes) {
+    // node i of packed level 1 (every 8th base, 8 keys) in 32 bytes: {key 0; f1 f2 f3; f4 f5 f6;
+    // f7 s}, f_h = (key h - key 0) >> s in 21 bits each, s the trailing zeros common to the
+    // seven distances.  Last word ~0: "read the 64-byte node" (a distance does not fit, or the
+    // node has padding keys).
+    const u64 k0 = i * 64;
+    bool fits = k0 + 56 < a.n_alloc;
+    u64 f[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    u64 b0 = 0;
+    u32 sh = 0;
+    if (fits) {
+      b0 = a.table[k0].base;
+      u64 any = 0;
+#pragma unroll
+      for (int h = 1; h < 8; ++h) {
+        f[h] = a.table[k0 + 8 * h].base - b0;
+        any |= f[h];
+      }
+      sh = any ? (u32)__ffsll((long long)any) - 1u : 0u;
+#pragma unroll
+      for (int h = 1; h < 8; ++h) {
+        f[h] >>= sh;
+        fits = fits && (f[h] >> 21) == 0;
+      }
+    }
+    const u64 a1 = f[1] | (f[2] << 21) | (f[3] << 42), a2 = f[4] | (f[5] << 21) | (f[6] << 42);
+    const u64 a3 = fits ? (f[7] | ((u64)sh << 21)) : ~0ull;
+    a.cmid[i * 2] = make_uint4((u32)b0, (u32)(b0 >> 32), (u32)a1, (u32)(a1 >> 32));
+    a.cmid[i * 2 + 1] = make_uint4((u32)a2, (u32)(a2 >> 32), (u32)a3, (u32)(a3 >> 32));
   }
   if (i < a.n_chunks) a.cstate[i] = 0;
   if (i == 0) {
@@ -1094,8 +1309,8 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 struct ScanPlan {
   u32 top_n, levels, f0_log2, n_sub, groups, g;
   u32 mid_len[kMaxMid];
-  u32 n_chunks, leaf_lines, sampled, bucket_log2;
-  size_t off_top, off_bst, off_mid[kMaxMid], off_leaf, off_cstate, total;
+  u32 n_chunks, leaf_lines, cmid_nodes, sampled, bucket_log2;
+  size_t off_top, off_bst, off_mid[kMaxMid], off_leaf, off_cleaf, off_cmid, off_cstate, total;
 };
 
 bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
@@ -1148,6 +1363,12 @@ bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
   pl->leaf_lines = (levels >= 2 && pl->mid_len[0]) ? (n_alloc + 7) / 8 : 0;
   pl->off_leaf = off;
   off += align256((size_t)pl->leaf_lines * 64);
+  // the compact copies of the table and of packed level 1 (32 bytes per line / node)
+  pl->cmid_nodes = pl->leaf_lines ? (n_alloc + 63) / 64 : 0;
+  pl->off_cleaf = off;
+  off += align256((size_t)pl->leaf_lines * 32);
+  pl->off_cmid = off;
+  off += align256((size_t)pl->cmid_nodes * 32);
   // measured crossover: from 4,096 sub-tiles (2 Mi words) on the large chunks win even though
   // they leave compute units without a chunk; below, more and smaller chunks do
   const bool small = pl->n_sub < (1u << fdy__tune_get(FDY_TUNE_SCAN_SMALL_LOG2));
@@ -1214,6 +1435,9 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   }
   a.leaf = pl.leaf_lines ? (uint4*)(ws + pl.off_leaf) : nullptr;
   a.leaf_lines = pl.leaf_lines;
+  a.cleaf = pl.leaf_lines ? (uint4*)(ws + pl.off_cleaf) : nullptr;
+  a.cmid = pl.cmid_nodes ? (uint4*)(ws + pl.off_cmid) : nullptr;
+  a.cmid_nodes = pl.cmid_nodes;
   a.n_sub = pl.n_sub;
   a.cstate = (u64*)(ws + pl.off_cstate);
   a.n_chunks = pl.n_chunks;
@@ -1250,6 +1474,8 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   p.bucket_log2 = a.bucket_log2;
   for (int j = 0; j < kMaxMid; ++j) p.mid[j] = a.mid[j];
   p.leaf = a.leaf;
+  p.cmid = a.cmid;
+  p.cleaf = a.cleaf;
   p.cstate = a.cstate;
   p.n_sub = pl.n_sub;
   p.top_n = pl.top_n;

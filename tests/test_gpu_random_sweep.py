@@ -2,7 +2,9 @@
 the oracle (GPU).
 
 Table shapes the fixed configurations do not have (clusters of tiny allocations, a few huge
-ones, touching ranges, spans from a few KiB to most of the address space), candidate
+ones, touching ranges, spans from a few KiB to most of the address space, granule-aligned layouts
+whose lines mostly take the compact forms, with pointers spread evenly or aimed at the lines that
+do not), candidate
 densities from none to all, word counts on both sides of sub-tile, group and chunk
 boundaries and of the small/large kernel variants, and several sizes of the LDS level."""
 import numpy as np
@@ -30,23 +32,36 @@ def random_table(rng, A, shape):
         big = rng.random(A) < 0.05
         size = np.where(big, rng.integers(1 << 12, 1 << 17, A).astype(np.uint64) << np.uint64(21), size)
         gap = (rng.integers(0, 4, A).astype(np.uint64) << k)
+    elif shape.startswith("granular"):  # a layout of whole mapping granules: 2 MiB-aligned bases, sizes in
+        # 512-byte steps up to 64 MiB, which the 32-byte forms of the table lines and of the first key level
+        # hold; a few odd sizes (such a line only fits the 64-byte form) and a few regions of 8 GiB and more
+        # (the table itself) leave marked lines and nodes among the packed ones
+        size = rng.integers(8, 1 << 17, A).astype(np.uint64) << np.uint64(9)
+        size = np.where(rng.random(A) < 0.02, size + rng.integers(1, 512, A).astype(np.uint64), size)
+        size = np.where(rng.random(A) < 0.003, rng.integers(1 << 33, 1 << 36, A).astype(np.uint64), size)
+        gran = np.uint64(1 << 21)
+        gap = (size + gran - np.uint64(1)) // gran * gran - size + (rng.integers(0, 3, A).astype(np.uint64) << np.uint64(21))
     else:  # "wide": a span of most of the 64-bit space (key shift at its largest)
         size = rng.integers(1, 1 << 30, A).astype(np.uint64)
         gap = (rng.integers(0, 1 << 62, A) // max(A, 1)).astype(np.uint64)
     start = np.concatenate([[0], np.cumsum(size + gap)[:-1]]).astype(np.uint64)
     t = np.zeros(A, L.ALLOC)
     first = np.uint64(rng.integers(1, 1 << 40))
-    if shape == "aligned":
+    if shape == "aligned" or shape.startswith("granular"):
         first = first >> np.uint64(21) << np.uint64(21)
     t["base"], t["size"] = first + start, size
     return t
 
 
-def random_words(rng, W, table, density):
+def random_words(rng, W, table, density, skew=False):
     words = rng.integers(0, 1 << 64, W, dtype=np.uint64)
     A = len(table)
     idx = np.flatnonzero(rng.random(W) < density)
     reg = rng.integers(0, A, len(idx))
+    if skew:  # most pointers into the few odd or huge regions (their lines are the marked ones)
+        special = np.flatnonzero((table["size"] % np.uint64(512) != 0) | (table["size"] >= np.uint64(1 << 33)))
+        if len(special):
+            reg = np.where(rng.random(len(idx)) < 0.8, special[rng.integers(0, len(special), len(idx))], reg)
     kind = rng.integers(0, 6, len(idx))
     off = (rng.random(len(idx)) * table["size"][reg]).astype(np.uint64)
     off = np.minimum(off, table["size"][reg] - np.uint64(1))
@@ -67,6 +82,8 @@ CASES = [  # (words, allocations, shape, density, top_log2)
     (4096 * 512 - 1, 1000, "uniform", 0.02, 14), (4096 * 512 + 513, 300000, "clustered", 0.2, 14),
     (16384 * 512 + 513, 70000, "uniform", 0.1, 14),
     (300000, 70000, "aligned", 0.3, 14), (1 << 20, 200000, "aligned", 0.15, 12), (50000, 40, "aligned", 0.5, 3),
+    (1 << 20, 200000, "granular", 0.15, 14), (600000, 150000, "granular_skew", 0.3, 14),
+    (300000, 70000, "granular", 0.3, 10), (200000, 131080, "granular_skew", 0.9, 14),
 ]
 
 
@@ -83,7 +100,7 @@ def test_random_scan_and_rebase(oracle, case):
     rng = np.random.default_rng(1000 + case)
     table = random_table(rng, A, shape)
     assert oracle.table_validate(table)[0] == 0
-    words = random_words(rng, W, table, density)
+    words = random_words(rng, W, table, density, skew=shape.endswith("skew"))
     new_base = rng.integers(0, 1 << 64, A, dtype=np.uint64)
     print(f"[sweep] case {case}: W={W} A={A} {shape} density={density} top_log2={top_log2}", flush=True)
     old = fdy.tune_get(fdy.TUNE_SCAN_TOP_LOG2)
