@@ -162,6 +162,25 @@ int fdy_table_validate(const fdy_alloc* h_table, uint32_t n_alloc, uint32_t* h_b
 int fdy_layout_invert(const fdy_alloc* h_table, const uint64_t* h_new_base, uint32_t n_alloc,
                       fdy_alloc* h_inv_table, uint64_t* h_inv_base, uint32_t* h_inv_region);
 
+/* ---- capture-window replay: a recorded layout placed in a new address range ----------
+ * Section 4.1.1 ("capture-window" allocations recorded at SAVE are issued again at LOAD, so
+ * that every address the graphs expect exists) and Section 5.1: the deterministic layout
+ * keeps every allocation at the same distance from the start of its address range, whatever
+ * that start is.  Given the table that a recording run left (h_recorded[n], in an address
+ * range that started at recorded_start), this places each allocation at the same distance
+ * from new_start in a range of new_capacity bytes whose first new_used bytes are already
+ * taken, and writes h_new_base[i] = new_start + (h_recorded[i].base - recorded_start): the
+ * base map of the recorded table that fdy_materialize and fdy_scan_rebase take.  Host call,
+ * host pointers.
+ *   FDY_ERR_INVALID_ARG  n > 0 and a null pointer
+ *   FDY_ERR_TABLE        h_recorded is not a valid table, or starts below recorded_start
+ *   FDY_ERR_ORDER        the first allocation would start inside the first new_used bytes
+ *   FDY_ERR_CAPACITY     the last allocation would end behind new_capacity bytes, or behind
+ *                        the end of the address space
+ * On any error h_new_base is not written. */
+int fdy_layout_replay(const fdy_alloc* h_recorded, uint32_t n, uint64_t recorded_start, uint64_t new_start,
+                      uint64_t new_capacity, uint64_t new_used, uint64_t* h_new_base);
+
 /* ---- (a1) pointer scan -------------------------------------------------------------
  * Classifies every 8-byte word of d_words against the allocation table and emits the
  * relocation table (Section 4.1.1 and Section 2.2 give the need; the paper itself avoids

@@ -59,6 +59,17 @@ int fdy_arena_table(const fdy_arena* a, fdy_alloc* h_table, uint32_t capacity);
  * again.  Capture-window replay: the same sequence gives the same addresses. */
 int fdy_arena_reset(fdy_arena* a);
 
+/* Capture-window replay from a recording (Section 4.1.1, Section 5.1): h_recorded[n] is the
+ * table of an earlier arena whose base was recorded_base (fdy_arena_table and fdy_arena_base
+ * of the recording run, e.g. out of an archive).  Every recorded allocation is placed in `a`
+ * at the same distance from a's base, appended to a's table, and the bump pointer moves behind
+ * the last one; h_new_base[i] receives the new address of recorded allocation i (the base map
+ * for fdy_materialize / fdy_scan_rebase).  Placement and errors are those of
+ * fdy_layout_replay (fdy.h) with a's base, capacity and bump pointer; on any error nothing
+ * changes.  FDY_ERR_INVALID_ARG also for a null arena. */
+int fdy_arena_replay(fdy_arena* a, const fdy_alloc* h_recorded, uint32_t n, uint64_t recorded_base,
+                     uint64_t* h_new_base);
+
 /* Unmaps and releases everything.  Null is allowed. */
 int fdy_arena_destroy(fdy_arena* a);
 

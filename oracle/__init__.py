@@ -89,6 +89,29 @@ def layout_invert(table, new_base):
     return inv, np.array([p[2] for p in placed], np.uint64), np.array([p[3] for p in placed], np.uint32)
 
 
+def layout_replay(recorded, recorded_start, new_start, new_capacity, new_used=0):
+    """A recorded layout placed in a new address range (Section 4.1.1 capture-window replay,
+    Section 5.1): every allocation keeps its distance from the start of the range.  Returns the
+    new bases, or the name of what is wrong ("table", "order", "capacity").  Plain Python
+    integers; definition written out."""
+    t = _c(recorded, L.ALLOC)
+    rows = [(int(b), int(z)) for b, z in zip(t["base"], t["size"])]
+    if not rows:
+        return np.zeros(0, np.uint64)
+    for k, (b, z) in enumerate(rows):
+        if z < 1 or b + z > (1 << 64) - 1 or (k and b < rows[k - 1][0] + rows[k - 1][1]):
+            return "table"
+    if rows[0][0] < recorded_start:
+        return "table"
+    dist = [b - recorded_start for b, _ in rows]
+    if dist[0] < new_used:
+        return "order"
+    end = dist[-1] + rows[-1][1]
+    if end > new_capacity or new_start + end > (1 << 64) - 1:  # the placed table must be valid too
+        return "capacity"
+    return np.array([new_start + d for d in dist], np.uint64)
+
+
 def _scan(fn, words, table, capacity=None):
     w = _c(words, np.uint64)
     t = _c(table, L.ALLOC)

@@ -6,7 +6,7 @@ missing, importing the binding functions raises.
 
 Entry points keep the names of include/fdy.h: fdy_scan_pointers, fdy_scan_pointers_stride4, fdy_scan_rebase,
 fdy_reloc_segment, fdy_fingerprint, fdy_derive_overrides, fdy_materialize (+ workspace queries,
-fdy_table_validate, fdy_layout_invert, fdy_strerror); include/fdy_archive.h is bound in archive.py.
+fdy_table_validate, fdy_layout_invert, fdy_layout_replay, fdy_strerror); include/fdy_archive.h is bound in archive.py.
 """
 from __future__ import annotations
 
@@ -59,6 +59,9 @@ def lib():
         L.fdy_table_validate.argtypes = [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32)]
         L.fdy_layout_invert.restype = C.c_int
         L.fdy_layout_invert.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.fdy_layout_replay.restype = C.c_int
+        L.fdy_layout_replay.argtypes = [C.c_void_p, C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64,
+                                        C.c_void_p]
         L.fdy_scan_workspace_bytes.restype = C.c_size_t
         L.fdy_scan_workspace_bytes.argtypes = [C.c_uint64, C.c_uint32]
         L.fdy_scan_pointers.restype = C.c_int
@@ -160,6 +163,18 @@ def fdy_layout_invert(h_table, h_new_base, check=True):
     if check:
         _check(rc, "fdy_layout_invert")
     return rc, inv_t, inv_b, inv_r
+
+
+def fdy_layout_replay(h_recorded, recorded_start, new_start, new_capacity, new_used=0, check=True):
+    """h_recorded: fdy_alloc records (host numpy array) -> (rc, new_base uint64 per allocation)."""
+    t = np.ascontiguousarray(h_recorded)
+    assert t.dtype.itemsize == 16
+    nb = np.zeros(len(t), np.uint64)
+    rc = lib().fdy_layout_replay(_ptr(t) if len(t) else None, len(t), int(recorded_start), int(new_start),
+                                 int(new_capacity), int(new_used), _ptr(nb) if len(t) else None)
+    if check:
+        _check(rc, "fdy_layout_replay")
+    return rc, nb
 
 
 def fdy_scan_workspace_bytes(n_words, n_alloc):

@@ -88,6 +88,21 @@ extern "C" int fdy_layout_invert(const fdy_alloc* h_table, const uint64_t* h_new
   return fdy_table_validate(h_inv_table, n_alloc, nullptr) == FDY_OK ? FDY_OK : FDY_ERR_TABLE;
 }
 
+extern "C" int fdy_layout_replay(const fdy_alloc* h_recorded, uint32_t n, uint64_t recorded_start,
+                                 uint64_t new_start, uint64_t new_capacity, uint64_t new_used,
+                                 uint64_t* h_new_base) {
+  if (n == 0) return FDY_OK;
+  if (!h_recorded || !h_new_base) return FDY_ERR_INVALID_ARG;
+  if (fdy_table_validate(h_recorded, n, nullptr) != FDY_OK) return FDY_ERR_TABLE;
+  if (h_recorded[0].base < recorded_start) return FDY_ERR_TABLE;
+  if (h_recorded[0].base - recorded_start < new_used) return FDY_ERR_ORDER;
+  // the table is valid, so the last allocation ends last and its end does not wrap
+  const uint64_t end = h_recorded[n - 1].base + h_recorded[n - 1].size - recorded_start;
+  if (end > new_capacity || new_start + end < new_start) return FDY_ERR_CAPACITY;
+  for (uint32_t i = 0; i < n; ++i) h_new_base[i] = new_start + (h_recorded[i].base - recorded_start);
+  return FDY_OK;
+}
+
 // ---- per-kernel event timing (bench support) -------------------------------------------
 namespace {
 struct ProfSlot {

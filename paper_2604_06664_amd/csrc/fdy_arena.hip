@@ -143,6 +143,19 @@ extern "C" int fdy_arena_reset(fdy_arena* a) {
   return FDY_OK;
 }
 
+extern "C" int fdy_arena_replay(fdy_arena* a, const fdy_alloc* h_recorded, uint32_t n, uint64_t recorded_base,
+                                uint64_t* h_new_base) {
+  if (!a) return FDY_ERR_INVALID_ARG;
+  if (n == 0) return FDY_OK;
+  if (a->table.size() + (size_t)n > 0xffffffffu) return FDY_ERR_CAPACITY;
+  const uint64_t base = (uint64_t)(uintptr_t)a->base;
+  const int rc = fdy_layout_replay(h_recorded, n, recorded_base, base, a->capacity, a->used, h_new_base);
+  if (rc != FDY_OK) return rc;
+  for (uint32_t i = 0; i < n; ++i) a->table.push_back(fdy_alloc{h_new_base[i], h_recorded[i].size});
+  a->used = (size_t)(h_new_base[n - 1] + h_recorded[n - 1].size - base);
+  return FDY_OK;
+}
+
 extern "C" int fdy_arena_destroy(fdy_arena* a) {
   if (!a) return FDY_OK;
   (void)hipGetLastError();

@@ -37,6 +37,9 @@
 //                 stay in L2: one 64-byte node of 8 keys per level, fetched whole;
 //        leaf     8 consecutive {base,size} entries: from the packed copy of the table (64
 //                 bytes per line) when the table is large, else from the table itself;
+//        level 1 and the leaf are read through 32-byte copies (two loads per candidate and
+//        level instead of four, and half the footprint in L2) where the table's nodes and
+//        lines mostly fit them, which layouts made of whole mapping granules do;
 //      region and offset of each candidate stay in registers, its word index in LDS;
 //   4. counts its hits into LDS.
 // One workgroup barrier per chunk makes the counts and the next ticket visible.  The output

@@ -42,7 +42,7 @@ def test_every_declared_symbol_is_exported(fdy):
             "fdy_table_validate", "fdy_scan_workspace_bytes", "fdy_materialize_workspace_bytes",
             "fdy_version", "fdy_strerror", "fdy_scan_rebase", "fdy_derive_overrides",
             "fdy_derive_workspace_bytes", "fdy_arena_create", "fdy_arena_alloc", "fdy_arena_table",
-            "fdy_arena_destroy"} <= set(names)
+            "fdy_arena_destroy", "fdy_arena_replay", "fdy_layout_replay", "fdy_layout_invert"} <= set(names)
     raw = C.CDLL(fdy.LIB_PATH)
     for n in names:
         assert hasattr(raw, n), f"{n} declared in fdy.h but not exported"

@@ -10,7 +10,9 @@
 //   3. the nodes' argument words are rebased for arena B in one pass (fdy_scan_rebase with
 //      A's table and B's bases), installed with hipGraphExecKernelNodeSetParams, replayed:
 //      B's buffers hold the chain's results, A's are untouched;
-//   4. arena A is reset and the sequence replayed: the same addresses come back.
+//   4. arena A is reset and the sequence replayed: the same addresses come back;
+//   (between 1 and 2) a third arena is given A's recorded table alone (fdy_arena_replay): every
+//      allocation lands at the same distance from that arena's base, backed by memory.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -106,6 +108,36 @@ extern "C" int arena_graph_check(char* msg, int msg_len) {
       return 1;
     }
     new_base[i] = tb[i].base;
+  }
+  // capture-window replay from the recording alone: a third arena takes A's table and puts every
+  // allocation at the same distance from its own base, without the sequence being issued again
+  {
+    fdy_arena* R = nullptr;
+    FD(fdy_arena_create(&R, 0x280000000000ull, 4u << 20));
+    const uint64_t base_r = fdy_arena_base(R);
+    std::vector<uint64_t> nb_r(n_alloc);
+    std::vector<fdy_alloc> tr(n_alloc);
+    FD(fdy_arena_replay(R, ta.data(), n_alloc, base_a, nb_r.data()));
+    FD(fdy_arena_table(R, tr.data(), n_alloc));
+    for (uint32_t i = 0; i < n_alloc; ++i) {
+      if (fdy_arena_count(R) != n_alloc || nb_r[i] != base_r + (ta[i].base - base_a) || tr[i].base != nb_r[i] ||
+          tr[i].size != ta[i].size) {
+        snprintf(msg, msg_len, "replayed allocation %u is not where the recording puts it", i);
+        return 1;
+      }
+    }
+    // the replayed range is backed by memory, the next allocation lands behind it, and the
+    // recording cannot be placed a second time over itself
+    CK(hipMemset((void*)(uintptr_t)nb_r[n_alloc - 1], 0x5a, (size_t)ta[n_alloc - 1].size));
+    void* next = nullptr;
+    FD(fdy_arena_alloc(R, 64, 8, &next));
+    if ((uint64_t)(uintptr_t)next < nb_r[n_alloc - 1] + ta[n_alloc - 1].size ||
+        fdy_arena_replay(R, ta.data(), n_alloc, base_a, nb_r.data()) != FDY_ERR_ORDER ||
+        fdy_arena_count(R) != n_alloc + 1) {
+      snprintf(msg, msg_len, "the arena's state after a replay is wrong");
+      return 1;
+    }
+    FD(fdy_arena_destroy(R));
   }
   // chain input in both instances, sentinels elsewhere
   std::vector<uint64_t> init(kN), sentinel(kN, 0xA5A5A5A5A5A5A5A5ull);
