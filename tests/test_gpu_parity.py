@@ -687,3 +687,38 @@ def test_full_config_whole_path(hip, oracle, idx):
         assert np.array_equal(dims, rdims)
     del mrun, srun
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_repeated_runs_give_identical_bytes(hip, idx):
+    """Workgroups draw their chunks in whatever order they start, and hits are placed by a
+    look-back over other workgroups' totals: a race there would show as outputs that differ
+    from run to run.  The whole path runs four times over poisoned outputs and workspaces,
+    with an unrelated kernel in between; every byte of every output must repeat.  (Each
+    configuration's outputs are compared with the oracle in test_full_config_whole_path.)"""
+    import torch
+
+    ar = make_config(idx)
+    say(f"[repeat] config {idx}: W={len(ar.words)} A={ar.n_alloc}")
+    run = hip.PathRun(ar, reloc_capacity=len(ar.ptr_word) + 16)
+    outs = [run.scan.d_relocs, run.scan.d_count, run.d_reloc_off, run.d_keys, run.d_tid, run.d_tg, run.d_nt,
+            run.mat.d_out] + ([run.mat.d_dims] if run.mat.d_dims is not None else [])
+    first = None
+    for rep in range(4):
+        for t in outs + [run.scan.d_ws, run.mat.d_ws]:
+            t.fill_(0x5A + rep)
+        run.step()
+        assert run.status() == 0
+        n = int(run.scan.d_count.item())
+        assert n == len(ar.ptr_word)
+        n_tmpl = int(run.d_nt.item())  # only that many entries of the template list are written
+        cut = {id(run.scan.d_relocs): n * 16, id(run.d_tg): n_tmpl * 4}
+        got = [t[: cut[id(t)]].clone() if id(t) in cut else t.clone() for t in outs]
+        if first is None:
+            first = got
+        else:
+            for a, b in zip(first, got):
+                assert torch.equal(a, b)
+        torch.rand(1 << 20, device="cuda").sum().item()  # something else on the device in between
+    del run, first, got
+    torch.cuda.empty_cache()
