@@ -54,8 +54,11 @@ __device__ __forceinline__ Seg combine(Seg left, Seg right) {
   return Seg{left.v * right.p + right.v, left.p * right.p};
 }
 
+// A launch of one block (an archive of a single graph) also writes the grouping: the graph is
+// its own template, and the grouping kernel's launch is saved.
 __global__ __launch_bounds__(kFpBlock) void fp_key_kernel(const fdy_node* nodes, const u64* node_off,
-                                                          u32 mask, u64* keys) {
+                                                          u32 mask, u64* keys, u32* template_id,
+                                                          u32* tmpl_graph, u32* n_templates) {
   __shared__ Seg s_seg[kFpBlock / 64];
   const u32 g = blockIdx.x, tid = threadIdx.x;
   const u64 n0 = node_off[g], N = node_off[g + 1] - n0;
@@ -83,6 +86,11 @@ __global__ __launch_bounds__(kFpBlock) void fp_key_kernel(const fdy_node* nodes,
     Seg t = s_seg[0];
     for (int w = 1; w < kFpBlock / 64; ++w) t = combine(t, s_seg[w]);
     keys[g] = mix(mix(N) * t.p + t.v);
+    if (gridDim.x == 1) {
+      template_id[0] = 0;
+      if (tmpl_graph) tmpl_graph[0] = 0;
+      *n_templates = 1;
+    }
   }
 }
 
@@ -164,9 +172,11 @@ extern "C" int fdy_fingerprint(const fdy_node* d_nodes, const uint64_t* d_node_o
   if (n_graphs) {
     prof_begin(FDY_PROF_FP_KEYS, stream);
     hipLaunchKernelGGL(fp_key_kernel, dim3(n_graphs), dim3(kFpBlock), 0, stream, d_nodes,
-                       (const u64*)d_node_off, field_mask, (u64*)d_keys);
+                       (const u64*)d_node_off, field_mask, (u64*)d_keys, d_template_id, d_tmpl_graph,
+                       d_n_templates);
     prof_end(FDY_PROF_FP_KEYS, stream);
     FDY_HIP_TRY(hipGetLastError());
+    if (n_graphs == 1) return FDY_OK;  // the key kernel has written the grouping too
   }
   prof_begin(FDY_PROF_FP_GROUP, stream);
   hipLaunchKernelGGL(fp_group_kernel, dim3(1), dim3(1024), 0, stream, (const u64*)d_keys, n_graphs,
