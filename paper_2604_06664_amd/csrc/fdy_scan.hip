@@ -1323,7 +1323,10 @@ bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
   u32 levels = 0, f0_log2 = 0;
   auto sampled_at = [&](u32 lv, u32 f) { return (u32)(((u64)n_alloc + (1ull << (3 * lv + f)) - 1) >> (3 * lv + f)); };
   if (n_alloc > top_cap) {
-    levels = 1;
+    // at least two levels below the LDS level: a single one would read its table lines with
+    // dependent probes (they have no packed copy, which takes the exact first base that the
+    // level above the lines supplies), and that is slower than one more whole-node fetch
+    levels = 2;
     while (sampled_at(levels, f0_log2) > top_cap) {
       if (++f0_log2 == 3) {
         f0_log2 = 0;
