@@ -1318,7 +1318,7 @@ struct ScanPlan {
 
 bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
   const u32 top_cap = 1u << fdy__tune_get(FDY_TUNE_SCAN_TOP_LOG2);
-  // smallest sampling stride 2^f0_log2 * 8^levels (levels >= 1 unless the whole table fits)
+  // smallest sampling stride 2^f0_log2 * 8^levels (levels >= 2 unless the whole table fits)
   // for which the sampled bases fit the LDS level
   u32 levels = 0, f0_log2 = 0;
   auto sampled_at = [&](u32 lv, u32 f) { return (u32)(((u64)n_alloc + (1ull << (3 * lv + f)) - 1) >> (3 * lv + f)); };
