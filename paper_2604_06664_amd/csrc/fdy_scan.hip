@@ -53,9 +53,12 @@
 // registers in ascending word order.
 // The input is read exactly once and the relocation table written exactly once.
 //
-// A group with more than 384 candidates (over a third of its words inside the table's span
-// - never the case for argument blobs, but legal) is handled sub-tile by sub-tile in windows
-// of queue size, searched twice (count, then write); slower, same result.
+// A group with more than 384 candidates (over a third of its words inside the table's span:
+// more than the registers keep results for) is handled sub-tile by sub-tile in windows of
+// queue size, one round at a time; its hits go to a staging area in the workspace as complete
+// entries (each wave has room for one entry per word of the two chunks it has in flight) and
+// are copied to their place when the chunk's position is known.  Slower per candidate than
+// the register path (single rounds, and the entries travel twice), same result.
 //
 // Variant at 4-byte stride (fdy_scan_pointers_stride4): the same kernel with kHalf set reads
 // the array as 32-bit units and treats every unit index as a position whose value is that
@@ -89,6 +92,7 @@ constexpr int kQcap = 192;                     // queue entries per wave
 constexpr int kRegRounds = 3;                  // rounds of 64 candidates per sub-tile kept in registers
 constexpr int kMaxMid = 6;                     // packed levels in global memory
 constexpr u32 kMiss = 0xffffffffu;
+constexpr u32 kStageWgs = 320;                 // most workgroups the scan launches (staging is sized for them)
 
 struct ScanParams {
   const u64* words;
@@ -107,6 +111,7 @@ struct ScanParams {
   const uint4* cmid;        // compact copy of packed level 1, 32 bytes per node of 8 keys (null: not built)
   const uint4* cleaf;       // compact copy of the table, 32 bytes per 8 entries (null: not built)
   u64* cstate;     // [n_chunks] per-chunk totals / inclusive prefixes
+  fdy_reloc* stage;  // [grid][2][sub-tiles of a chunk * kSub]: staged entries of dense groups
   u32 n_sub;       // sub-tiles
   u32 top_n;       // power of two
   u32 levels;      // k: 8-ary levels below level 0, the table line included
@@ -683,12 +688,13 @@ __device__ __forceinline__ void store_reloc(const ScanParams& p, u64 at, u32 wor
 }
 
 // Dense sub-tile (its wave's group holds more candidates than the register-resident path
-// keeps): windows of queue size; counts when `write` is false, writes from position `pos`
-// otherwise.  Returns hits.
+// keeps): windows of queue size, searched one round at a time; the hits go to dst[0 ...) as
+// complete entries in word order (the wave's staging area: the output position is not known
+// yet).  Returns hits.
 template <bool kHalf>
 __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt& t, const u32* top,
-                          u64 span_lo, u32 shifts, u64* qw, unsigned short* qi, u64 wbase, bool write,
-                          u64 pos, u32& marked) {
+                          u64 span_lo, u32 shifts, u64* qw, unsigned short* qi, u64 wbase, fdy_reloc* dst,
+                          u32& marked) {
   const u32 lane = lane_id();
   const u64 lt = lanemask_lt();
   u64 H = 0;
@@ -703,8 +709,13 @@ __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt&
       search<1>(p, top, span_lo, shifts, wv, f, marked);
       const bool hit = valid && f[0].hit;
       const u64 b = ballot(hit);
-      if (write && hit)
-        store_reloc(p, pos + H + __popcll(b & lt), (u32)(wbase + qi[q]), f[0].region, f[0].offset);
+      if (hit) {
+        fdy_reloc o;
+        o.word = (u32)(wbase + qi[q]);
+        o.region = f[0].region;
+        o.offset = f[0].offset;
+        *reinterpret_cast<uint4*>(&dst[H + __popcll(b & lt)]) = *reinterpret_cast<const uint4*>(&o);
+      }
       H += __popcll(b);
     }
   }
@@ -766,10 +777,18 @@ struct RoundResults {
 };
 
 // Ordered write of one chunk's hits of this wave, given the chunk's exclusive prefix.
+// The staging area of a wave's group: entries of the dense groups of chunk parity b.  A unit
+// (group, wave) has room for one entry per word it covers.
+template <int kGroups, int kG>
+__device__ __forceinline__ fdy_reloc* stage_of(const ScanParams& p, u32 b, int g) {
+  constexpr u32 kUnitWords = kG * kSub, kUnits = kGroups * kWaves;
+  const u32 wave = threadIdx.x >> 6;
+  return p.stage + ((u64)blockIdx.x * 2 + b) * (kUnits * kUnitWords) + (u64)(g * kWaves + wave) * kUnitWords;
+}
+
 template <int kGroups, int kG, bool kHalf>
 __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResults<kGroups, kG>& r,
-                                            u64 chunk_excl, const u32* top, u64 span_lo, u64 span_len,
-                                            u32 shifts, u64* qw, unsigned short* qi_all) {
+                                            u64 chunk_excl, unsigned short* qi_all) {
   constexpr int kGR = kG * kRegRounds;
   const u32 wave = threadIdx.x >> 6;
   const u64 lt = lanemask_lt();
@@ -789,14 +808,14 @@ __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResu
         pos += __popcll(bl);
       }
     } else {
-      for (int j = 0; j < kG; ++j) {
-        const u32 sub = first_sub + j;
-        u64 w[kWpl];
-        Filt t;
-        load_words<kHalf>(p, sub, span_lo, w);
-        filter_words<kHalf>(w, t, span_lo, span_len);
-        u32 marked = 0;  // not acted upon here
-        pos += dense_pass<kHalf>(p, w, t, top, span_lo, shifts, qw, qi, (u64)sub * kSub, true, pos, marked);
+      // a dense group: its entries wait in the wave's staging area, complete and in word
+      // order, written a round ago by other lanes of this wave, through the same vector L1
+      // (workgroup scope: a wider fence would write back and invalidate the whole L2)
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      const fdy_reloc* src = stage_of<kGroups, kG>(p, r.b, g);
+      for (u32 i = lane_id(); i < r.H[g]; i += 64) {
+        const uint4 v = *reinterpret_cast<const uint4*>(&src[i]);
+        if (pos + i < p.capacity) *reinterpret_cast<uint4*>(&p.relocs[pos + i]) = v;
       }
     }
   }
@@ -903,13 +922,17 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
         run_group<3, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H, marked);
         run_group<6, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H, marked);
       } else {
+        // more candidates than the registers keep results for: the hits go to the wave's
+        // staging area as complete entries and are copied to their place a round later
+        fdy_reloc* dst = stage_of<kGroups, kG>(p, b, g);
         for (int r = 0; r < kG; ++r) {
           u64 dw[kWpl];
           Filt t;
           load_words<kHalf>(p, first_sub + r, span_lo, dw);
           filter_words<kHalf>(dw, t, span_lo, span_len);
-          H += dense_pass<kHalf>(p, dw, t, top, span_lo, shifts, qw, qi, (u64)(first_sub + r) * kSub, false, 0, marked);
+          H += dense_pass<kHalf>(p, dw, t, top, span_lo, shifts, qw, qi, (u64)(first_sub + r) * kSub, dst + H, marked);
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       }
       searched += Q;
       if (marked * 4 > searched + 256) shifts &= ~(kUseCmid | kUseCleaf);
@@ -947,7 +970,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       const u64 total = __shfl(cur.cnt_incl, 63);  // all lanes take part in the shuffle
       if (closer && lane == 0) st_state(&p.cstate[chunk], (chunk == 0 ? kFlagInc : kFlagAgg) | total);
     }
-    if (have_prev) write_round<kGroups, kG, kHalf>(p, prev, s_excl[b], top, span_lo, span_len, shifts, qw, qi_all);
+    if (have_prev) write_round<kGroups, kG, kHalf>(p, prev, s_excl[b], qi_all);
     prev = cur;
     have_prev = true;
     base = nbase;
@@ -970,7 +993,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       }
     }
     __syncthreads();
-    write_round<kGroups, kG, kHalf>(p, prev, s_excl[0], top, span_lo, span_len, shifts, qw, qi_all);
+    write_round<kGroups, kG, kHalf>(p, prev, s_excl[0], qi_all);
   }
 }
 
@@ -1312,8 +1335,8 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 struct ScanPlan {
   u32 top_n, levels, f0_log2, n_sub, groups, g;
   u32 mid_len[kMaxMid];
-  u32 n_chunks, leaf_lines, cmid_nodes, sampled, bucket_log2;
-  size_t off_top, off_bst, off_mid[kMaxMid], off_leaf, off_cleaf, off_cmid, off_cstate, total;
+  u32 n_chunks, leaf_lines, cmid_nodes, sampled, bucket_log2, stage_wgs;
+  size_t off_top, off_bst, off_mid[kMaxMid], off_leaf, off_cleaf, off_cmid, off_cstate, off_stage, total;
 };
 
 bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
@@ -1384,6 +1407,11 @@ bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
   pl->n_chunks = (pl->n_sub + chunk - 1) / chunk;
   pl->off_cstate = off;
   off += align256((size_t)pl->n_chunks * 8);
+  // staging for the entries of dense groups: per workgroup two chunks' worth (the chunk being
+  // searched and the one waiting for its position), one entry per word
+  pl->stage_wgs = pl->n_chunks < kStageWgs ? pl->n_chunks : kStageWgs;
+  pl->off_stage = off;
+  off += align256((size_t)pl->stage_wgs * 2 * chunk * kSub * sizeof(fdy_reloc));
   pl->total = off;
   return true;
 }
@@ -1425,6 +1453,7 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   const u32 per_cu = (u32)fdy__tune_get(FDY_TUNE_SCAN_WG_PER_CU);
   u32 grid = (u32)n_cu * per_cu;  // persistent workgroups
   if (grid > pl.n_chunks) grid = pl.n_chunks;
+  if (grid > pl.stage_wgs) grid = pl.stage_wgs;
   ScanInit a;
   a.table = d_table;
   a.n_alloc = n_alloc;
@@ -1483,6 +1512,7 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   p.cmid = a.cmid;
   p.cleaf = a.cleaf;
   p.cstate = a.cstate;
+  p.stage = (fdy_reloc*)(ws + pl.off_stage);
   p.n_sub = pl.n_sub;
   p.top_n = pl.top_n;
   p.levels = pl.levels;
