@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # profiles/whole_path_config5_kernel_stats_and_traffic.txt and are reported only for the
 # workloads and kernels they were collected on.
 PMC_TRAFFIC_BYTES = {
-    (4, "scan_kernel"): 1_881_227_826 + 216_192_370,
-    (4, "mat_main_kernel"): 2_296_527_763 + 1_074_071_899,
-    (5, "mat_main_kernel"): 71_215_911 + 1_575_424_727,
+    (4, "scan_kernel"): 1_894_527_093 + 216_736_023,
+    (4, "mat_main_kernel"): 2_296_942_220 + 1_074_064_622,
+    (5, "mat_main_kernel"): 71_216_312 + 1_575_306_023,
 }
 
 
