@@ -197,7 +197,11 @@ int fdy_layout_replay(const fdy_alloc* h_recorded, uint32_t n, uint64_t recorded
  *                    reloc_capacity (then only the first reloc_capacity entries are
  *                    written and FDY_ST_CAPACITY is raised)
  *   d_workspace      device, 256-byte aligned, at least fdy_scan_workspace_bytes() bytes;
- *                    contents on entry are irrelevant, contents on exit are unspecified
+ *                    contents on entry are irrelevant, contents on exit are unspecified.
+ *                    The size is the search hierarchy built from the table (about 14 bytes
+ *                    per allocation beyond 16,384 of them), 8 bytes per 16,384 words, and a
+ *                    staging area of 32 bytes per word up to 160 MiB (word-dense inputs);
+ *                    0 is returned for n_words beyond the limit above
  *   d_status         device uint32_t or NULL
  */
 size_t fdy_scan_workspace_bytes(uint64_t n_words, uint32_t n_alloc);
