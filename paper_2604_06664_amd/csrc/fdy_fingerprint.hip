@@ -16,7 +16,7 @@ namespace fdy {
 namespace {
 
 constexpr u64 kP = 0x9e3779b97f4a7c15ull;
-constexpr int kFpBlock = 256;
+constexpr int kFpBlock = 1024;
 
 __device__ __forceinline__ u64 mix(u64 x) {
   x ^= x >> 30;
