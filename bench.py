@@ -58,7 +58,7 @@ def run_workload(idx, steps, warmup, prof=True, cpu_sample_words=0, timed_events
     import torch
 
     import paper_2604_06664_amd as fdy
-    from paper_2604_06664_amd import session
+    from tests.support import session
     from synth import CONFIG_NAMES, make_config
 
     t0 = time.time()
@@ -174,7 +174,7 @@ def fused_variant(ar, run, steps):
     import torch
 
     import paper_2604_06664_amd as fdy
-    from paper_2604_06664_amd import session
+    from tests.support import session
 
     fr = session.ScanRebaseRun(run.scan.d_words, run.scan.d_table, ar.new_base[0],
                                n_words=len(ar.words), n_alloc=ar.n_alloc)
@@ -257,7 +257,7 @@ def cpu_baseline(ar, run, n):
 
 
 def session_reloc_dtype():
-    from paper_2604_06664_amd import session
+    from tests.support import session
 
     return session.RELOC
 

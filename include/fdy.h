@@ -66,6 +66,9 @@ extern "C" {
                                  equal the sums the device computed; nothing written
                                  (derive: a graph and its template differ in length)     */
 #define FDY_ST_SPIN 0x8u      /* scan: a bounded wait on a predecessor tile ran out      */
+#define FDY_ST_BAD_ORDER 0x10u /* materialize: a relocation, override, grid-override or
+                                 patch list is not strictly ascending by location; the
+                                 output is unspecified (entries may be missing)          */
 
 /* ---- plain-data records ------------------------------------------------------------ */
 
@@ -233,6 +236,28 @@ int fdy_scan_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* 
                     uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
                     uint32_t* d_status, void* hip_stream);
 
+/* ---- scan with rebased output (a1 + c1 + c2 for one layout, relocation table kept) ------
+ * fdy_scan_pointers and fdy_scan_rebase in one pass over the words: the relocation table is
+ * written exactly as by fdy_scan_pointers (ascending, same d_count / capacity / status rules)
+ * AND d_out_words receives what fdy_scan_rebase would write.  This is the whole of (c) for an
+ * archive whose graphs are their own templates and that is instantiated for one new layout
+ * (the inter-rank sense of a template, Section 4.2.2: every rank takes the same captured
+ * blobs): the words are read once instead of once by the scan and once by the
+ * materialization, while the table stays available for further base maps (fdy_materialize)
+ * and for storing with the archive.  Overrides and rank patches are not applied by this call.
+ *
+ *   d_words, d_table, d_relocs, reloc_capacity, d_count, d_workspace, d_status
+ *                    as for fdy_scan_pointers (same size query)
+ *   d_new_base       [n_alloc] device, 8-byte aligned
+ *   d_out_words      [n_words] device, 16-byte aligned, must not overlap d_words
+ *                    (FDY_ERR_INVALID_ARG; in place is what fdy_scan_rebase offers)
+ * A hit beyond reloc_capacity is still rebased in d_out_words. */
+int fdy_scan_pointers_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
+                             uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
+                             uint64_t* d_count, const uint64_t* d_new_base, uint64_t* d_out_words,
+                             void* d_workspace, size_t workspace_bytes, uint32_t* d_status,
+                             void* hip_stream);
+
 /* Variant of fdy_scan_pointers for pointers at 4-byte alignment (argument buffers are opaque
  * byte strings, Section 2.2 / Appendix B: a packed structure may hold a pointer at any
  * 4-byte offset).  The array is read as n_units 32-bit little-endian units; position q
@@ -337,7 +362,11 @@ int fdy_derive_overrides(const uint64_t* d_words, uint64_t n_words_total, const 
  * [src_word_off[s], src_word_off[s+1]) of src_words, nodes [src_node_off[s], ..[s+1]) of
  * src_nodes, relocs [src_reloc_off[s], ..[s+1]) of relocs with reloc.word indexing
  * src_words (exactly what fdy_scan_pointers + fdy_reloc_segment produce for the archive).
- * Each reloc / override / patch list is strictly ascending by location.
+ * Each reloc / override / grid-override / patch list is strictly ascending by location (the
+ * slices of a list that fall into an output tile are found by binary search).  The device
+ * verifies it for every list it reads: a list out of order, or with a location twice, raises
+ * FDY_ST_BAD_ORDER and leaves the output unspecified, without any out-of-bounds access.  The
+ * lists of a template that no output graph uses are not read.
  *
  * Output layout: d_out_words is [n_maps][out_words_per_map], map-major; inside a map the
  * graphs follow in order g = 0..n_graphs-1, each with the word count of its template.

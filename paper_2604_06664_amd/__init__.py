@@ -5,6 +5,7 @@ supplies device memory and streams.  There is no CPU fallback: if the built libr
 missing, importing the binding functions raises.
 
 Entry points keep the names of include/fdy.h: fdy_scan_pointers, fdy_scan_pointers_stride4, fdy_scan_rebase,
+fdy_scan_pointers_rebase,
 fdy_reloc_segment, fdy_fingerprint, fdy_derive_overrides, fdy_materialize (+ workspace queries,
 fdy_table_validate, fdy_layout_invert, fdy_layout_replay, fdy_strerror); include/fdy_archive.h is bound in archive.py.
 """
@@ -74,6 +75,10 @@ def lib():
         L.fdy_scan_rebase.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
                                       C.c_void_p]
+        L.fdy_scan_pointers_rebase.restype = C.c_int
+        L.fdy_scan_pointers_rebase.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p,
+                                               C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                               C.c_size_t, C.c_void_p, C.c_void_p]
         L.fdy_reloc_segment.restype = C.c_int
         L.fdy_reloc_segment.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32,
                                         C.c_void_p, C.c_void_p]
@@ -207,6 +212,16 @@ def fdy_scan_rebase(d_words, n_words, d_table, n_alloc, d_new_base, d_out_words,
     return _check(rc, "fdy_scan_rebase") if check else rc
 
 
+def fdy_scan_pointers_rebase(d_words, n_words, d_table, n_alloc, d_relocs, reloc_capacity, d_count,
+                             d_new_base, d_out_words, d_workspace, workspace_bytes, d_status=None,
+                             stream=None, check=True):
+    rc = lib().fdy_scan_pointers_rebase(_ptr(d_words), int(n_words), _ptr(d_table), int(n_alloc),
+                                        _ptr(d_relocs), int(reloc_capacity), _ptr(d_count),
+                                        _ptr(d_new_base), _ptr(d_out_words), _ptr(d_workspace),
+                                        int(workspace_bytes), _ptr(d_status), _stream(stream))
+    return _check(rc, "fdy_scan_pointers_rebase") if check else rc
+
+
 def fdy_reloc_segment(d_relocs, d_count, reloc_capacity, d_word_off, n_off, d_reloc_off,
                       stream=None, check=True):
     rc = lib().fdy_reloc_segment(_ptr(d_relocs), _ptr(d_count), int(reloc_capacity),
@@ -259,7 +274,7 @@ def tune_set(knob, value):
 PROF_SLOTS = 10
 
 
-PROF_SCAN_MAIN, PROF_MAT_MAIN, PROF_SCAN_REBASE = 0, 7, 9
+PROF_SCAN_MAIN, PROF_MAT_MAIN, PROF_SCAN_OUT, PROF_SCAN_REBASE = 0, 7, 8, 9
 
 
 def prof_enable(n_records, slots=None):

@@ -45,7 +45,8 @@ struct __attribute__((aligned(16))) MatTile {  // 64 B
   u32 n_words;   // 0: unused entry
   u32 g, tmpl, k0;
   u32 reloc_lo, reloc_hi, ovr_lo, ovr_hi;
-  u32 pad[4];
+  u32 reloc_seg;  // first entry of the template's relocation list (order checks stop there)
+  u32 pad[3];
 };
 static_assert(sizeof(MatTile) == 64, "MatTile");
 
@@ -89,6 +90,8 @@ __device__ __forceinline__ bool graph_sizes(const MatParams& p, u32 g, u64& nw, 
     nn = 0;
     return false;
   }
+  // a graph without words has no tile that would meet (and reject) its entries
+  if (nw == 0 && (d.src_reloc_off[s + 1] != d.src_reloc_off[s] || d.ovr_off[g + 1] != d.ovr_off[g])) return false;
   return true;
 }
 
@@ -197,11 +200,11 @@ __device__ __forceinline__ void prep_tiles_block(const MatParams& p, const PrepV
   const u32 j = block * kPrepTiles + tid;
   const bool valid = j < v.n_tiles;
   TileGeom q;
-  u32 rl1 = 0, ov1 = 0, reloc_lo = 0, ovr_lo = 0;
+  u32 rl0 = 0, rl1 = 0, ov1 = 0, reloc_lo = 0, ovr_lo = 0;
   if (valid) {
     q = tile_geometry(p, v, j);
     const fdy_reloc* relocs = d.relocs;
-    const u32 rl0 = (u32)d.src_reloc_off[q.s];
+    rl0 = (u32)d.src_reloc_off[q.s];
     rl1 = (u32)d.src_reloc_off[q.s + 1];
     reloc_lo = lane_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, rl0, rl1, q.src_word);
     const fdy_ovr32* ovr = d.ovr;
@@ -220,8 +223,13 @@ __device__ __forceinline__ void prep_tiles_block(const MatParams& p, const PrepV
   // a tile that is not its graph's last is followed by a tile of the same graph (j + 1 < n_tiles)
   u32 reloc_hi = q.last ? rl1 : s_lo[tid + 1].x;
   const u32 ovr_hi = q.last ? ov1 : s_lo[tid + 1].y;
-  // the list is strictly ascending by word: at most n entries fall inside the tile
-  if (reloc_hi - reloc_lo > q.n) reloc_hi = reloc_lo + q.n;
+  // the list is strictly ascending by word: at most n entries fall inside the tile, and none
+  // lies before the template's first word
+  if (reloc_hi - reloc_lo > q.n) {
+    reloc_hi = reloc_lo + q.n;
+    raise_status(p.d_status, FDY_ST_BAD_ORDER);
+  }
+  if (q.k0 == 0 && reloc_lo != rl0) raise_status(p.d_status, FDY_ST_BAD_INDEX);
   MatTile e;
   e.src_word = q.src_word;
   e.out_word = v.out_word_off[q.g] + q.k0;
@@ -233,7 +241,8 @@ __device__ __forceinline__ void prep_tiles_block(const MatParams& p, const PrepV
   e.reloc_hi = reloc_hi;
   e.ovr_lo = ovr_lo;
   e.ovr_hi = ovr_hi;
-  e.pad[0] = e.pad[1] = e.pad[2] = e.pad[3] = 0;
+  e.reloc_seg = rl0;
+  e.pad[0] = e.pad[1] = e.pad[2] = 0;
   *ent = e;
 }
 
@@ -302,7 +311,7 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
   // archives stay cached for whoever reads them next.
   const bool once = gridDim.y == 1 && gridDim.x >= 4096;
   stage_tile(buf, src, ent.src_word, n, tid, once);  // c1
-  bool bad = false;
+  bool bad = false, disorder = false;
   u32 rk[kMatPre], rr[kMatPre];
   u64 ro[kMatPre];
 #pragma unroll
@@ -311,6 +320,7 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
     rk[i] = 0xffffffffu;
     rr[i] = 0;
     ro[i] = 0;
+    u32 word_q = 0;
     if (q < ent.reloc_hi) {
       u64x2 raw;
       if (once) {
@@ -322,6 +332,7 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
         raw = *reinterpret_cast<const u64x2*>(&d.relocs[q]);
       }
       const u32 word = (u32)raw.x, region = (u32)(raw.x >> 32);
+      word_q = word;
       const u64 k = (u64)word - ent.src_word;
       if (k < n && region < d.n_alloc) {
         rk[i] = (u32)k;
@@ -330,6 +341,15 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
       } else {
         bad = true;
       }
+    }
+    // Strictly ascending by word: every entry of the slice against the one before it in the
+    // template's list (the lower lane holds it; a wave's first lane reads it).  The slices of a
+    // template's tiles cover its list, so a list that passes everywhere is in order, which is
+    // what the slices themselves (found by binary search) rely on.
+    u32 before = __shfl_up(word_q, 1);
+    if (q < ent.reloc_hi && q > ent.reloc_seg) {
+      if (lane_id() == 0) before = d.relocs[q - 1].word;
+      if (before >= word_q) disorder = true;
     }
   }
   const bool has_ovr = ent.ovr_lo < ent.ovr_hi;
@@ -412,6 +432,42 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
     if (tid == 0 && head + 2 * pairs < n) __builtin_nontemporal_store(last, out + n - 1);
   }
   if (bad) raise_status(p.d_status, FDY_ST_BAD_INDEX);
+  if (disorder) raise_status(p.d_status, FDY_ST_BAD_ORDER);
+}
+
+// Order of the short lists (overrides, grid overrides, rank patches): every entry against the
+// one before it, all lists of a kind in one sweep over their concatenation; where the key does
+// not ascend, a new list must begin.  The relocation lists, which are long, are checked where
+// they are read anyway (mat_main_kernel).
+__device__ __forceinline__ void check_lists(const MatParams& p, u32 cb, u32 n_cb) {
+  const fdy_mat_desc& d = p.d;
+  const u64 first = (u64)cb * 256 + threadIdx.x, stride = (u64)n_cb * 256;
+  bool disorder = false;
+  auto sweep = [&](auto key, const u64* off, u32 n_lists) {
+    if (!n_lists) return;
+    const u64 lo = off[0], hi = off[n_lists];
+    for (u64 i = lo + 1 + first; i < hi; i += stride) {
+      if (key(i - 1) < key(i)) continue;
+      u32 a = 0, b = n_lists;  // the last list that begins at or before entry i
+      while (b - a > 1) {
+        const u32 mid = a + (b - a) / 2;
+        if (off[mid] <= i) a = mid;
+        else b = mid;
+      }
+      if (off[a] != i) disorder = true;
+    }
+  };
+  const fdy_ovr32* ovr = d.ovr;
+  sweep([&](u64 i) { return ovr[i].byte_off; }, d.ovr_off, d.n_graphs);
+  if (p.out_dims) {
+    const fdy_grid_ovr* govr = d.govr;
+    sweep([&](u64 i) { return govr[i].node; }, d.govr_off, d.n_graphs);
+  }
+  if (d.map_rank) {
+    const fdy_patch* patch = d.patch;
+    sweep([&](u64 i) { return patch[i].word; }, d.patch_off, d.n_templates * d.n_ranks);
+  }
+  if (disorder) raise_status(p.d_status, FDY_ST_BAD_ORDER);
 }
 
 // Thread i: launch dimensions of output node i.
@@ -457,8 +513,13 @@ __device__ __forceinline__ void write_dims(const MatParams& p, const PrepView& v
 // in LDS, instead of reading what mat_prep_graphs_kernel left in the workspace; that launch
 // is then not needed at all.  Block 0 reports what that kernel would have reported.
 constexpr u32 kOwnSumsMax = 1024;
+constexpr u32 kCheckBlocks = 96;
 template <bool kOwnSums>
 __global__ __launch_bounds__(256) void mat_prep_tiles_kernel(MatParams p, u32 nb_tiles, u32 nb_patch) {
+  if (blockIdx.x >= gridDim.x - kCheckBlocks) {  // the last blocks verify the order of the short lists
+    check_lists(p, blockIdx.x - (gridDim.x - kCheckBlocks), kCheckBlocks);
+    return;
+  }
   __shared__ uint2 s_lo[256];
   __shared__ u64 s_off[kOwnSums ? 3 : 1][kOwnSums ? kOwnSumsMax + 1 : 1];
   __shared__ u64 s_buf[17];
@@ -609,12 +670,11 @@ extern "C" int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words
   if (own_sums && nb_tiles + nb_patch + nb_dims == 0) nb_tiles = 1;  // someone has to verify the totals
   if (nb_tiles + nb_patch + nb_dims) {
     prof_begin(FDY_PROF_MAT_PREP_TILES, stream);
+    const u32 nb = nb_tiles + nb_patch + nb_dims + kCheckBlocks;
     if (own_sums)
-      hipLaunchKernelGGL(mat_prep_tiles_kernel<true>, dim3(nb_tiles + nb_patch + nb_dims), dim3(256), 0, stream,
-                         p, nb_tiles, nb_patch);
+      hipLaunchKernelGGL(mat_prep_tiles_kernel<true>, dim3(nb), dim3(256), 0, stream, p, nb_tiles, nb_patch);
     else
-      hipLaunchKernelGGL(mat_prep_tiles_kernel<false>, dim3(nb_tiles + nb_patch + nb_dims), dim3(256), 0, stream,
-                         p, nb_tiles, nb_patch);
+      hipLaunchKernelGGL(mat_prep_tiles_kernel<false>, dim3(nb), dim3(256), 0, stream, p, nb_tiles, nb_patch);
     prof_end(FDY_PROF_MAT_PREP_TILES, stream);
     FDY_HIP_TRY(hipGetLastError());
   }

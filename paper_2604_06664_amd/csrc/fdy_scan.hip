@@ -118,8 +118,9 @@ struct ScanParams {
   u32 f0_log2;     // level 0 samples every (2^f0_log2 * 8^k)-th base
   u32* d_status;
   u32 spin_limit;
-  const u64* new_base;  // fused scan + rebase only: [n_alloc]
-  u64* out;             // fused scan + rebase only: [n_words]
+  const u64* new_base;  // with a rebased output only: [n_alloc]
+  u64* out;             // with a rebased output only: [n_words]
+  u32 key_bits;         // width of the level-0 keys: 31 (32-bit keys in LDS) or 16 + bucket_log2 (16-bit keys)
 };
 
 constexpr u64 kFlagAgg = 1ull << 62;
@@ -199,12 +200,15 @@ __device__ __forceinline__ u64 wave_incl_scan_u64(u64 v) {
 }
 
 // Level-0 keys are (base - span_lo) >> shift with the smallest shift that makes every key of
-// the span fit 31 bits (0xffffffff pads).  What the truncation leaves ambiguous is settled on
-// the exact bases, so the shift affects speed only.
-__device__ __forceinline__ u32 key_shift_for(u64 span_len) {
+// the span fit key_bits bits (all-ones pads).  What the truncation leaves ambiguous is settled
+// on the exact bases, so the shift affects speed only.  Keys are kept in 32 bits (key_bits =
+// 31), or in 16 bits where LDS is needed for other things: then only a key's low half is
+// stored, key_bits = 16 + bucket_log2 makes a bucket at most 2^16 key values wide, and the keys
+// that a bucket's search compares all share their high half with the candidate.
+__device__ __forceinline__ u32 key_shift_for(u64 span_len, u32 key_bits) {
   const u64 m = span_len - 1;
   const u32 bits = m ? 64u - (u32)__clzll((long long)m) : 0u;
-  return bits > 31u ? bits - 31u : 0u;
+  return bits > key_bits ? bits - key_bits : 0u;
 }
 
 // The level-0 key space is cut into 2^bucket_log2 equal buckets (key >> shift); the shift is the
@@ -213,6 +217,11 @@ __device__ __forceinline__ u32 bucket_shift_for(u64 span_len, u32 key_shift, u32
   const u64 max_key = (span_len - 1) >> key_shift;
   const u32 bits = max_key ? 64u - (u32)__clzll((long long)max_key) : 0u;
   return bits > bucket_log2 ? bits - bucket_log2 : 0u;
+}
+
+// Bytes that the level-0 keys take in LDS, in front of the bucket index (kept 16-byte aligned).
+__device__ __host__ __forceinline__ size_t level0_key_bytes(u32 top_n, bool k16) {
+  return k16 ? (((size_t)top_n * 2 + 15) & ~(size_t)15) : (size_t)top_n * 4;
 }
 
 struct Found {
@@ -339,9 +348,11 @@ constexpr u32 kUseCmid = 1u << 16, kUseCleaf = 1u << 17;  // flags that travel w
 // Interval search for N candidates per lane at once (each w lies inside the table's span).
 // The N chains are independent; writing every step for all of them lets their LDS and
 // global round trips overlap, which is what the dependent steps of one chain cannot do.
-template <int N>
-__device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
+template <int N, bool kK16 = false>
+__device__ __forceinline__ void search(const ScanParams& p, const void* top_v, u64 span_lo, u32 shifts,
                                        const u64 (&w)[N], Found (&f)[N], u32& marked) {
+  typedef typename std::conditional<kK16, unsigned short, u32>::type key_t;
+  const key_t* top = reinterpret_cast<const key_t*>(top_v);
   const u32 key_shift = shifts & 0xffu, bucket_shift = (shifts >> 8) & 0xffu;
   const uint4* cmid = (shifts & kUseCmid) ? p.cmid : nullptr;
   const uint4* cleaf = (shifts & kUseCleaf) ? p.cleaf : nullptr;
@@ -358,13 +369,15 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
   // 7 steps, 4-ary): level 0 was 27 % of the kernel's time, most of it LDS bank conflicts of
   // 64 lanes reading random keys.  Clustered tables degrade towards the plain binary search.
   {
-    const unsigned short* bst = reinterpret_cast<const unsigned short*>(top + p.top_n);
-    u32 lo[N], hi[N];
+    const unsigned short* bst = reinterpret_cast<const unsigned short*>(
+        reinterpret_cast<const unsigned char*>(top_v) + level0_key_bytes(p.top_n, kK16));
+    u32 lo[N], hi[N], kc[N];  // kc: the candidate's key as the stored keys compare with it
 #pragma unroll
     for (int c = 0; c < N; ++c) {
       const u32 bk = kw[c] >> bucket_shift;
       lo[c] = bst[bk];
       hi[c] = bst[bk + 1];
+      kc[c] = kK16 ? (kw[c] & 0xffffu) : kw[c];
     }
     for (;;) {
       bool open = false;
@@ -373,23 +386,26 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
       if (!ballot(open)) break;
       u32 k[N];
 #pragma unroll
-      for (int c = 0; c < N; ++c) k[c] = lo[c] < hi[c] ? top[(lo[c] + hi[c]) >> 1] : 0u;
+      for (int c = 0; c < N; ++c) k[c] = lo[c] < hi[c] ? (u32)top[(lo[c] + hi[c]) >> 1] : 0u;
 #pragma unroll
       for (int c = 0; c < N; ++c)
         if (lo[c] < hi[c]) {
           const u32 mid = (lo[c] + hi[c]) >> 1;
-          if (k[c] <= kw[c]) lo[c] = mid + 1;
+          if (k[c] <= kc[c]) lo[c] = mid + 1;
           else hi[c] = mid;
         }
     }
 #pragma unroll
     for (int c = 0; c < N; ++c) i[c] = lo[c] - 1;  // keys not above kw, minus one; key 0 is 0
+#pragma unroll
+    for (int c = 0; c < N; ++c) kw[c] = kc[c];
   }
 #pragma unroll
   for (int c = 0; c < N; ++c) {
     n[c] = i[c];  // node index at level `levels`: covers table entries [n * 8^levels, ...)
-    if (top[i[c]] == kw[c]) {
-      // equal keys: the sampled base may still lie above w; settle it on exact bases
+    if ((u32)top[i[c]] == kw[c]) {
+      // equal keys: the sampled base may still lie above w; settle it on exact bases (16-bit
+      // keys of another bucket may look equal too: the settling then changes nothing)
       const u32 sh = 3 * p.levels + p.f0_log2;
       while (n[c] > 0 && p.table[n[c] << sh].base > w[c]) --n[c];
     }
@@ -546,9 +562,18 @@ __device__ __forceinline__ void search(const ScanParams& p, const u32* top, u64 
 // Stages the level-0 keys and the bucket index in LDS with 16-byte copies.  Both arrays are
 // padded to 256 bytes in the workspace and to 16 bytes in LDS, so whole 16-byte pieces can be
 // copied past their last entry; a top level of two keys (8 bytes) is copied key by key.
-__device__ __forceinline__ void stage_level0(const ScanParams& p, u32* top, unsigned short* bst, u32 n_bst) {
+__device__ __forceinline__ void stage_level0(const ScanParams& p, void* top_v, unsigned short* bst, u32 n_bst,
+                                             bool k16 = false) {
   const u32 tid = threadIdx.x;
-  if (p.top_n >= 4) {
+  u32* top = reinterpret_cast<u32*>(top_v);
+  if (k16) {  // 16-bit keys: top_n >= 2 of them, padded to 16 bytes in both places
+    const uint4* src = reinterpret_cast<const uint4*>(p.top);
+    uint4* dst = reinterpret_cast<uint4*>(top);
+    for (u32 i = tid; i < (p.top_n * 2 + 15) / 16; i += kBlock) dst[i] = src[i];
+    const uint4* bsrc = reinterpret_cast<const uint4*>(p.bstart);
+    uint4* bdst = reinterpret_cast<uint4*>(bst);
+    for (u32 i = tid; i < (n_bst * 2 + 15) / 16; i += kBlock) bdst[i] = bsrc[i];
+  } else if (p.top_n >= 4) {
     const uint4* src = reinterpret_cast<const uint4*>(p.top);
     uint4* dst = reinterpret_cast<uint4*>(top);
     for (u32 i = tid; i < p.top_n / 4; i += kBlock) dst[i] = src[i];
@@ -663,7 +688,9 @@ __device__ __forceinline__ void filter_words(const u64 (&w)[kWpl], Filt& t, u64 
 
 // Candidates with rank in [win, win + wn) go to queue slots qoff + [0, wn); the index stored
 // with each is its word's distance from word 0 of the sub-tile `row` places before this one.
-template <bool kHalf>
+// kValues false: only the indices are queued (the values are found through them, in the
+// wave's copy of its words in LDS).
+template <bool kHalf, bool kValues = true>
 __device__ __forceinline__ void enqueue(const u64 (&w)[kWpl], const Filt& t, u32 row, u32 win, u32 wn,
                                         u32 qoff, u64* qw, unsigned short* qi) {
   const u32 lane = lane_id();
@@ -671,10 +698,76 @@ __device__ __forceinline__ void enqueue(const u64 (&w)[kWpl], const Filt& t, u32
 #pragma unroll
   for (int r = 0; r < kWpl; ++r)
     if (t.c[r] && t.crank[r] - win < wn) {  // unsigned: also false below the window
-      qw[qoff + t.crank[r] - win] = w[r];
+      if constexpr (kValues) qw[qoff + t.crank[r] - win] = w[r];
       qi[qoff + t.crank[r] - win] = (unsigned short)(row * kSub + pos_in_sub<kHalf>(r, lane));
     }
   wave_lds_fence();
+}
+
+// The wave's copy of a sub-tile in LDS (ordered scan with rebased output): written as loaded,
+// 16 bytes per lane and load, so that word i of the sub-tile lies at index i.
+__device__ __forceinline__ void stash_words(u64* stash, const u64 (&w)[kWpl]) {
+  const u32 lane = lane_id();
+#pragma unroll
+  for (int k = 0; k < kLoads; ++k) {
+    u64x2 v;
+    v.x = w[2 * k];
+    v.y = w[2 * k + 1];
+    *reinterpret_cast<u64x2*>(stash + (k * 64 + lane) * 2) = v;
+  }
+}
+
+// ... and back from LDS to the output array, whole 16-byte pieces, non-temporally (written once).
+__device__ __forceinline__ void unstash_words(const ScanParams& p, u32 sub, const u64* stash) {
+  typedef u64 v2u64 __attribute__((ext_vector_type(2)));
+  const u32 lane = lane_id();
+  const u64 wbase = (u64)sub * kSub;
+  if (wbase + kSub <= p.n_words) {
+    u64x2 v[kLoads];
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) v[k] = *reinterpret_cast<const u64x2*>(stash + (k * 64 + lane) * 2);
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      v2u64 o;
+      o.x = v[k].x;
+      o.y = v[k].y;
+      __builtin_nontemporal_store(o, reinterpret_cast<v2u64*>(p.out + wbase + (k * 64 + lane) * 2));
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const u32 i = (k * 64 + lane) * 2;
+      if (wbase + i < p.n_words) p.out[wbase + i] = stash[i];
+      if (wbase + i + 1 < p.n_words) p.out[wbase + i + 1] = stash[i + 1];
+    }
+  }
+}
+
+// A sub-tile's words as the lanes hold them, to the output: the 16-byte stores a copy would use.
+// kNt: non-temporal (written once, not touched again by this kernel).
+template <bool kNt>
+__device__ __forceinline__ void store_words(const ScanParams& p, u32 sub, const u64 (&w)[kWpl]) {
+  typedef u64 v2u64 __attribute__((ext_vector_type(2)));
+  const u32 lane = lane_id();
+  const u64 wbase = (u64)sub * kSub;
+  if (wbase + kSub <= p.n_words) {
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      v2u64 v;
+      v.x = w[2 * k];
+      v.y = w[2 * k + 1];
+      v2u64* dst = reinterpret_cast<v2u64*>(p.out + wbase + (k * 64 + lane) * 2);
+      if constexpr (kNt) __builtin_nontemporal_store(v, dst);
+      else *dst = v;
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const u64 idx = wbase + (k * 64 + lane) * 2;
+      if (idx < p.n_words) p.out[idx] = w[2 * k];
+      if (idx + 1 < p.n_words) p.out[idx + 1] = w[2 * k + 1];
+    }
+  }
 }
 
 __device__ __forceinline__ void store_reloc(const ScanParams& p, u64 at, u32 word, u32 region, u64 offset) {
@@ -691,8 +784,10 @@ __device__ __forceinline__ void store_reloc(const ScanParams& p, u64 at, u32 wor
 // keeps): windows of queue size, searched one round at a time; the hits go to dst[0 ...) as
 // complete entries in word order (the wave's staging area: the output position is not known
 // yet).  Returns hits.
-template <bool kHalf>
-__device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt& t, const u32* top,
+// kOut: qw is the wave's LDS copy of this sub-tile; candidates are read from it through their
+// indices and a hit's word is replaced by its rebased value there.
+template <bool kHalf, bool kOut>
+__device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt& t, const void* top,
                           u64 span_lo, u32 shifts, u64* qw, unsigned short* qi, u64 wbase, fdy_reloc* dst,
                           u32& marked) {
   const u32 lane = lane_id();
@@ -700,13 +795,13 @@ __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt&
   u64 H = 0;
   for (u32 win = 0; win < t.Q; win += kQcap) {
     const u32 wn = t.Q - win < (u32)kQcap ? t.Q - win : (u32)kQcap;
-    enqueue<kHalf>(w, t, 0, win, wn, 0, qw, qi);
+    enqueue<kHalf, !kOut>(w, t, 0, win, wn, 0, qw, qi);
     for (u32 q0 = 0; q0 < wn; q0 += 64) {
       const u32 q = q0 + lane;
       const bool valid = q < wn;
-      const u64 wv[1] = {valid ? qw[q] : span_lo};
+      const u64 wv[1] = {valid ? qw[kOut ? (u32)qi[q] : q] : span_lo};
       Found f[1];
-      search<1>(p, top, span_lo, shifts, wv, f, marked);
+      search<1, kOut>(p, top, span_lo, shifts, wv, f, marked);
       const bool hit = valid && f[0].hit;
       const u64 b = ballot(hit);
       if (hit) {
@@ -715,6 +810,7 @@ __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt&
         o.region = f[0].region;
         o.offset = f[0].offset;
         *reinterpret_cast<uint4*>(&dst[H + __popcll(b & lt)]) = *reinterpret_cast<const uint4*>(&o);
+        if constexpr (kOut) qw[qi[q]] = p.new_base[o.region] + o.offset;
       }
       H += __popcll(b);
     }
@@ -725,20 +821,23 @@ __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt&
 // Searches queue rounds [R0, R0 + N) (64 entries each), N per lane in flight at once; region
 // (kMiss for "no hit") and offset stay in the caller's registers, round k's lane l holding the
 // result of queue slot 64 k + l.
-template <int N, int R0, int kGR>
-__device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
-                                           const u64* qw, u32 Q, u32 (&reg)[kGR], u64 (&off)[kGR], u64& H, u32& marked) {
+template <int N, int R0, int kGR, bool kOut>
+__device__ __forceinline__ void run_rounds(const ScanParams& p, const void* top, u64 span_lo, u32 shifts,
+                                           u64* qw, u32 Q, u32 (&reg)[kGR], u64 (&off)[kGR], u64& H, u32& marked,
+                                           const unsigned short* qi) {
   static_assert(R0 + N <= kGR, "rounds");
   const u32 lane = lane_id();
   u64 wv[N];
   Found f[N];
   bool valid[N];
+  u32 at[N];  // kOut: where the candidate lies in the wave's LDS copy of the group's words
 #pragma unroll
   for (int r = 0; r < N; ++r) {
     valid[r] = (R0 + r) * 64 + lane < Q;
-    wv[r] = valid[r] ? qw[(R0 + r) * 64 + lane] : span_lo;
+    at[r] = kOut && valid[r] ? (u32)qi[(R0 + r) * 64 + lane] : (u32)((R0 + r) * 64 + lane);
+    wv[r] = valid[r] ? qw[at[r]] : span_lo;
   }
-  search<N>(p, top, span_lo, shifts, wv, f, marked);
+  search<N, kOut>(p, top, span_lo, shifts, wv, f, marked);
 #pragma unroll
   for (int r = 0; r < N; ++r) {
     const bool hit = valid[r] && f[r].hit;
@@ -746,17 +845,27 @@ __device__ __forceinline__ void run_rounds(const ScanParams& p, const u32* top, 
     off[R0 + r] = f[r].offset;
     H += __popcll(ballot(hit));
   }
+  if constexpr (kOut) {
+    // a hit's word in the LDS copy becomes its rebased value; the copy goes out as a whole later
+    u64 nb[N];
+#pragma unroll
+    for (int r = 0; r < N; ++r) nb[r] = reg[R0 + r] != kMiss ? p.new_base[reg[R0 + r]] : 0;
+#pragma unroll
+    for (int r = 0; r < N; ++r)
+      if (reg[R0 + r] != kMiss) qw[at[r]] = nb[r] + off[R0 + r];
+  }
 }
 
 // Rounds [R0, R0 + 3) as far as there are candidates, with as many chains per lane as rounds.
-template <int R0, int kGR>
-__device__ __forceinline__ void run_group(const ScanParams& p, const u32* top, u64 span_lo, u32 shifts,
-                                          const u64* qw, u32 Q, u32 (&reg)[kGR], u64 (&off)[kGR], u64& H, u32& marked) {
+template <int R0, int kGR, bool kOut>
+__device__ __forceinline__ void run_group(const ScanParams& p, const void* top, u64 span_lo, u32 shifts,
+                                          u64* qw, u32 Q, u32 (&reg)[kGR], u64 (&off)[kGR], u64& H, u32& marked,
+                                          const unsigned short* qi) {
   if constexpr (R0 + 3 <= kGR) {
     const u32 nr = (Q + 63) >> 6;
-    if (nr >= (u32)R0 + 3) run_rounds<3, R0, kGR>(p, top, span_lo, shifts, qw, Q, reg, off, H, marked);
-    else if (nr == (u32)R0 + 2) run_rounds<2, R0, kGR>(p, top, span_lo, shifts, qw, Q, reg, off, H, marked);
-    else if (nr == (u32)R0 + 1) run_rounds<1, R0, kGR>(p, top, span_lo, shifts, qw, Q, reg, off, H, marked);
+    if (nr >= (u32)R0 + 3) run_rounds<3, R0, kGR, kOut>(p, top, span_lo, shifts, qw, Q, reg, off, H, marked, qi);
+    else if (nr == (u32)R0 + 2) run_rounds<2, R0, kGR, kOut>(p, top, span_lo, shifts, qw, Q, reg, off, H, marked, qi);
+    else if (nr == (u32)R0 + 1) run_rounds<1, R0, kGR, kOut>(p, top, span_lo, shifts, qw, Q, reg, off, H, marked, qi);
   }
 }
 
@@ -821,26 +930,38 @@ __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResu
   }
 }
 
-template <int kGroups, int kG, bool kHalf>
+// kOut: the scan also writes the rebased copy of the words (p.out, p.new_base).  A wave then
+// keeps the words of its group in LDS instead of queueing the candidates' values (the queue
+// holds their indices only and the search reads them through those); a hit's word is
+// replaced there by new_base[region] + offset right after the search, and the group goes out
+// as whole sub-tiles with the stores a copy would use.  (Copying the words to the output when
+// they are loaded and storing the hits' values over them afterwards was measured at twice the
+// time: by then the lines have left the L2, and 13 M scattered 8-byte stores into memory cost
+// more than the whole scan.)  The 64 KiB this takes come from the level-0 keys, which such a
+// launch keeps in 16 bits each, and from half of the bucket index.
+template <int kGroups, int kG, bool kHalf, bool kOut>
 __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   constexpr int kUnits = kGroups * kWaves;  // (group, wave) units of a chunk, in word order
   constexpr int kChunk = kUnits * kG;       // sub-tiles a workgroup draws per ticket
   constexpr int kGR = kG * kRegRounds;
   constexpr u32 kQwave = kG * kQcap;        // queue entries per wave
   static_assert(kUnits <= 64 && kG * kSub <= 65536, "a chunk's counts fit one wave; 16-bit queue indices");
+  static_assert(!(kOut && kHalf), "the rebased output exists for aligned words only");
   extern __shared__ __align__(16) unsigned char smem_raw[];
   __shared__ u32 s_next[2];         // first sub-tile of the chunk two rounds ahead, per round parity
   __shared__ u32 s_cnt[2][kUnits];  // hit counts of the chunk's units
   __shared__ u64 s_excl[2];         // previous chunk's exclusive prefix, from the closer wave
-  u32* top = reinterpret_cast<u32*>(smem_raw);  // [top_n], then the bucket index behind it
-  unsigned short* bst = reinterpret_cast<unsigned short*>(top + p.top_n);  // [n_buckets + 1]
+  void* top = smem_raw;  // [top_n] keys of 32 (kOut: 16) bits, then the bucket index behind them
+  unsigned short* bst = reinterpret_cast<unsigned short*>(smem_raw + level0_key_bytes(p.top_n, kOut));  // [n_buckets + 1]
   const u32 n_bst = (1u << p.bucket_log2) + 1;
-  unsigned char* qbase = smem_raw + (size_t)p.top_n * 4 + (((size_t)n_bst * 2 + 15) & ~(size_t)15);
+  unsigned char* qbase = smem_raw + level0_key_bytes(p.top_n, kOut) + (((size_t)n_bst * 2 + 15) & ~(size_t)15);
   const u32 tid = threadIdx.x;
   const u32 lane = tid & 63;
   const u32 wave = tid >> 6;
-  u64* qw = reinterpret_cast<u64*>(qbase) + wave * kQwave;  // candidate values
-  unsigned short* qi_all = reinterpret_cast<unsigned short*>(qbase + (size_t)kWaves * kQwave * 8) +
+  // candidate values (kOut: the words of the wave's group, kG sub-tiles)
+  constexpr u32 kVwave = kOut ? (u32)(kG * kSub) : kQwave;
+  u64* qw = reinterpret_cast<u64*>(qbase) + wave * kVwave;
+  unsigned short* qi_all = reinterpret_cast<unsigned short*>(qbase + (size_t)kWaves * kVwave * 8) +
                            wave * (2 * kGroups * kQwave);  // word indices: [round parity][group][slot]
   const bool closer = wave == kWaves - 1;  // one wave per workgroup speaks for the chunk
 
@@ -854,7 +975,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   // (small inputs are bound by such latencies).
   const bool single = (u64)gridDim.x * kChunk >= p.n_sub;
   if (tid == 0) s_next[0] = atomicAdd(p.ticket, (u32)kChunk);
-  stage_level0(p, top, bst, n_bst);
+  stage_level0(p, top, bst, n_bst, kOut);
   __syncthreads();
   if (tid == 0) s_next[1] = single ? p.n_sub : atomicAdd(p.ticket, (u32)kChunk);
   u32 base = s_next[0];
@@ -864,8 +985,8 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   const u64 span_lo = p.table[0].base;
   const u64 span_len = p.table[p.n_alloc - 1].base + p.table[p.n_alloc - 1].size - span_lo;
   // level-0 key shift (low byte) and bucket shift, passed along as one value
-  u32 shifts = key_shift_for(span_len) |
-               (bucket_shift_for(span_len, key_shift_for(span_len), p.bucket_log2) << 8) |
+  u32 shifts = key_shift_for(span_len, p.key_bits) |
+               (bucket_shift_for(span_len, key_shift_for(span_len, p.key_bits), p.bucket_log2) << 8) |
                (mostly_packed(p.cmid, (p.n_alloc + 63) / 64, true) ? kUseCmid : 0u) |
                (mostly_packed(p.cleaf, (p.n_alloc + 7) / 8, false) ? kUseCleaf : 0u);
   // Candidates need not spread over the table as its lines do (most pointers of a serving
@@ -888,7 +1009,8 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
 #pragma unroll
   for (int r = 0; r < kG; ++r) load_words<kHalf>(p, base + wave * kG + r, span_lo, w[r]);
 
-  for (u32 round = 0; base < p.n_sub; ++round) {
+  u32 round = 0;
+  for (; base < p.n_sub; ++round) {
     const u32 b = round & 1;
     u32 next = 0;
     if (tid == 0) next = single ? p.n_sub : atomicAdd(p.ticket, (u32)kChunk);  // round + 2's chunk, published at this round's barrier
@@ -906,9 +1028,11 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       for (int r = 0; r < kG; ++r) {
         Filt t;
         filter_words<kHalf>(w[r], t, span_lo, span_len);
-        if (Q + t.Q <= (u32)(kGR * 64)) enqueue<kHalf>(w[r], t, r, 0, t.Q, Q, qw, qi);
+        if (Q + t.Q <= (u32)(kGR * 64)) enqueue<kHalf, !kOut>(w[r], t, r, 0, t.Q, Q, qw, qi);
         Q += t.Q;
+        if constexpr (kOut) stash_words(qw + r * kSub, w[r]);
       }
+      if constexpr (kOut) wave_lds_fence();
       {  // the next group's words (this chunk's or the next one's), in flight during the search
         const u32 nsub = g + 1 < kGroups ? first_sub + kWaves * kG : nbase + wave * kG;
 #pragma unroll
@@ -918,9 +1042,9 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       for (int r = 0; r < kGR; ++r) cur.reg[g][r] = kMiss;
       u64 H = 0;
       if (Q <= (u32)(kGR * 64)) {
-        run_group<0, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H, marked);
-        run_group<3, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H, marked);
-        run_group<6, kGR>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H, marked);
+        run_group<0, kGR, kOut>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H, marked, qi);
+        run_group<3, kGR, kOut>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H, marked, qi);
+        run_group<6, kGR, kOut>(p, top, span_lo, shifts, qw, Q, cur.reg[g], cur.off[g], H, marked, qi);
       } else {
         // more candidates than the registers keep results for: the hits go to the wave's
         // staging area as complete entries and are copied to their place a round later
@@ -930,9 +1054,15 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
           Filt t;
           load_words<kHalf>(p, first_sub + r, span_lo, dw);
           filter_words<kHalf>(dw, t, span_lo, span_len);
-          H += dense_pass<kHalf>(p, dw, t, top, span_lo, shifts, qw, qi, (u64)(first_sub + r) * kSub, dst + H, marked);
+          H += dense_pass<kHalf, kOut>(p, dw, t, top, span_lo, shifts, kOut ? qw + r * kSub : qw, qi,
+                                       (u64)(first_sub + r) * kSub, dst + H, marked);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      }
+      if constexpr (kOut) {  // the group's words, hits rebased, to the output
+        wave_lds_fence();
+#pragma unroll
+        for (int r = 0; r < kG; ++r) unstash_words(p, first_sub + r, qw + r * kSub);
       }
       searched += Q;
       if (marked * 4 > searched + 256) shifts &= ~(kUseCmid | kUseCleaf);
@@ -977,8 +1107,10 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
     nbase = nnbase;
   }
 
-  // ---- drain: the last chunk this workgroup searched
+  // ---- drain: the last chunk this workgroup searched.  Its prefix goes to the slot that the
+  // last round did not use: a slow wave may still be about to read that round's slot.
   if (have_prev) {
+    const u32 db = round & 1;
     if (closer) {
       const u32 pchunk = prev.base / kChunk;
       const u64 total = __shfl(prev.cnt_incl, 63);
@@ -989,11 +1121,11 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
           *p.d_count = excl + total;
           if (excl + total > p.capacity) raise_status(p.d_status, FDY_ST_CAPACITY);
         }
-        s_excl[0] = excl;
+        s_excl[db] = excl;
       }
     }
     __syncthreads();
-    write_round<kGroups, kG, kHalf>(p, prev, s_excl[0], qi_all);
+    write_round<kGroups, kG, kHalf>(p, prev, s_excl[db], qi_all);
   }
 }
 
@@ -1054,28 +1186,6 @@ __device__ __forceinline__ void dequeue(u64 (&w)[kWpl], const Filt& t, u32 win, 
   wave_lds_fence();
 }
 
-__device__ __forceinline__ void store_words(const ScanParams& p, u32 sub, const u64 (&w)[kWpl]) {
-  typedef u64 v2u64 __attribute__((ext_vector_type(2)));
-  const u32 lane = lane_id();
-  const u64 wbase = (u64)sub * kSub;
-  if (wbase + kSub <= p.n_words) {
-#pragma unroll
-    for (int k = 0; k < kLoads; ++k) {
-      v2u64 v;
-      v.x = w[2 * k];
-      v.y = w[2 * k + 1];
-      __builtin_nontemporal_store(v, reinterpret_cast<v2u64*>(p.out + wbase + (k * 64 + lane) * 2));
-    }
-  } else {
-#pragma unroll
-    for (int k = 0; k < kLoads; ++k) {
-      const u64 idx = wbase + (k * 64 + lane) * 2;
-      if (idx < p.n_words) p.out[idx] = w[2 * k];
-      if (idx + 1 < p.n_words) p.out[idx + 1] = w[2 * k + 1];
-    }
-  }
-}
-
 constexpr int kFusedG = 2;  // sub-tiles per group
 
 __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
@@ -1095,8 +1205,8 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
 
   const u64 span_lo = p.table[0].base;
   const u64 span_len = p.table[p.n_alloc - 1].base + p.table[p.n_alloc - 1].size - span_lo;
-  u32 shifts = key_shift_for(span_len) |
-               (bucket_shift_for(span_len, key_shift_for(span_len), p.bucket_log2) << 8) |
+  u32 shifts = key_shift_for(span_len, p.key_bits) |
+               (bucket_shift_for(span_len, key_shift_for(span_len, p.key_bits), p.bucket_log2) << 8) |
                (mostly_packed(p.cmid, (p.n_alloc + 63) / 64, true) ? kUseCmid : 0u) |
                (mostly_packed(p.cleaf, (p.n_alloc + 7) / 8, false) ? kUseCleaf : 0u);
   // Candidates need not spread over the table as its lines do (most pointers of a serving
@@ -1158,7 +1268,7 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
     searched += Q;
     if (marked * 4 > searched + 256) shifts &= ~(kUseCmid | kUseCleaf);
 #pragma unroll
-    for (int r = 0; r < kFusedG; ++r) store_words(p, first_sub + r, w[r]);
+    for (int r = 0; r < kFusedG; ++r) store_words<true>(p, first_sub + r, w[r]);
     if (more) {
 #pragma unroll
       for (int r = 0; r < kFusedG; ++r)
@@ -1177,6 +1287,7 @@ struct ScanInit {
   u32 sampled;  // level-0 keys that are real (the rest is padding)
   unsigned short* bstart;
   u32 bucket_log2;
+  u32 key_bits;  // 31: keys of 32 bits; less: their low 16 bits only (see key_shift_for)
   u32 levels;
   u32 f0_log2;
   u64* mid[kMaxMid];
@@ -1200,10 +1311,12 @@ __global__ void scan_init_kernel(ScanInit a) {
   const u64 span_lo = a.n_alloc ? a.table[0].base : 0;
   const u64 span_len =
       a.n_alloc ? a.table[a.n_alloc - 1].base + a.table[a.n_alloc - 1].size - span_lo : 1;
-  const u32 key_shift = key_shift_for(span_len);
+  const u32 key_shift = key_shift_for(span_len, a.key_bits);
   if (i < a.top_n) {
     const u64 j = i << (3 * a.levels + a.f0_log2);
-    a.top[i] = j < a.n_alloc ? (u32)((a.table[j].base - span_lo) >> key_shift) : 0xffffffffu;
+    const u32 key = j < a.n_alloc ? (u32)((a.table[j].base - span_lo) >> key_shift) : 0xffffffffu;
+    if (a.key_bits == 31) a.top[i] = key;
+    else reinterpret_cast<unsigned short*>(a.top)[i] = (unsigned short)key;
   }
   if (i <= (1ull << a.bucket_log2)) {
     // bucket i starts at key value i << shift: how many level-0 keys lie below it
@@ -1335,11 +1448,13 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 struct ScanPlan {
   u32 top_n, levels, f0_log2, n_sub, groups, g;
   u32 mid_len[kMaxMid];
-  u32 n_chunks, leaf_lines, cmid_nodes, sampled, bucket_log2, stage_wgs;
+  u32 n_chunks, leaf_lines, cmid_nodes, sampled, bucket_log2, key_bits, stage_wgs;
   size_t off_top, off_bst, off_mid[kMaxMid], off_leaf, off_cleaf, off_cmid, off_cstate, off_stage, total;
 };
 
-bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
+// k16: the level-0 keys take 16 bits each and the bucket index at most 2^13 buckets (the launch
+// needs the LDS for a copy of the words: the ordered scan with rebased output).
+bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl, bool k16 = false) {
   const u32 top_cap = 1u << fdy__tune_get(FDY_TUNE_SCAN_TOP_LOG2);
   // smallest sampling stride 2^f0_log2 * 8^levels (levels >= 2 unless the whole table fits)
   // for which the sampled bases fit the LDS level
@@ -1368,7 +1483,8 @@ bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl) {
   off += align256((size_t)pl->top_n * 4);
   pl->sampled = sampled;
   pl->bucket_log2 = 0;  // one bucket per level-0 key, at most 2^14 (16-bit starts, 32 KiB of LDS)
-  while ((2u << pl->bucket_log2) <= pl->top_n && pl->bucket_log2 < 14) ++pl->bucket_log2;
+  while ((2u << pl->bucket_log2) <= pl->top_n && pl->bucket_log2 < (k16 ? 13u : 14u)) ++pl->bucket_log2;
+  pl->key_bits = k16 ? 16 + pl->bucket_log2 : 31;
   pl->off_bst = off;
   off += align256((((size_t)1 << pl->bucket_log2) + 1) * 2);
   for (int j = 0; j < kMaxMid; ++j) {
@@ -1433,15 +1549,16 @@ extern "C" size_t fdy_scan_workspace_bytes(uint64_t n_words, uint32_t n_alloc) {
 static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
                        uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity, uint64_t* d_count,
                        const uint64_t* d_new_base, uint64_t* d_out, void* d_workspace,
-                       size_t workspace_bytes, uint32_t* d_status, void* hip_stream, bool half = false) {
-  const bool fused = d_out != nullptr;
+                       size_t workspace_bytes, uint32_t* d_status, void* hip_stream, bool half = false,
+                       bool ordered_out = false) {
+  const bool fused = d_out != nullptr && !ordered_out;  // no relocation table, no ordering
   if (n_words > kMaxWords) return FDY_ERR_INVALID_ARG;
   if (!d_count) return FDY_ERR_INVALID_ARG;
   if (n_words && (!d_words || ((uintptr_t)d_words & 15))) return FDY_ERR_INVALID_ARG;
   if (n_alloc && (!d_table || ((uintptr_t)d_table & 15))) return FDY_ERR_INVALID_ARG;
   if (reloc_capacity && (!d_relocs || ((uintptr_t)d_relocs & 15))) return FDY_ERR_INVALID_ARG;
   ScanPlan pl;
-  if (!make_plan(n_words, n_alloc, &pl)) return FDY_ERR_INVALID_ARG;
+  if (!make_plan(n_words, n_alloc, &pl, ordered_out)) return FDY_ERR_INVALID_ARG;
   if (!d_workspace || ((uintptr_t)d_workspace & 255) || workspace_bytes < pl.total)
     return FDY_ERR_WORKSPACE;
   hipStream_t stream = (hipStream_t)hip_stream;
@@ -1462,6 +1579,7 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   a.sampled = pl.sampled;
   a.bstart = (unsigned short*)(ws + pl.off_bst);
   a.bucket_log2 = pl.bucket_log2;
+  a.key_bits = pl.key_bits;
   a.levels = pl.levels;
   a.f0_log2 = pl.f0_log2;
   for (int j = 0; j < kMaxMid; ++j) {
@@ -1490,7 +1608,7 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   FDY_HIP_TRY(hipGetLastError());
   if (pl.n_sub == 0) return FDY_OK;
   if (n_alloc == 0) {  // nothing can be a pointer; the fused form still owes the copy
-    if (fused && d_out != d_words)
+    if (d_out && d_out != d_words)
       FDY_HIP_TRY(hipMemcpyAsync(d_out, d_words, n_words * 8, hipMemcpyDeviceToDevice, stream));
     return FDY_OK;
   }
@@ -1521,8 +1639,9 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   p.spin_limit = (u32)fdy__tune_get(FDY_TUNE_SCAN_SPIN_LIMIT);
   p.new_base = (const u64*)d_new_base;
   p.out = (u64*)d_out;
+  p.key_bits = pl.key_bits;
 
-  const size_t lds0 = (size_t)pl.top_n * 4 + (((((size_t)1 << pl.bucket_log2) + 1) * 2 + 15) & ~(size_t)15);
+  const size_t lds0 = level0_key_bytes(pl.top_n, ordered_out) + (((((size_t)1 << pl.bucket_log2) + 1) * 2 + 15) & ~(size_t)15);
   if (fused) {
     const size_t lds = lds0 + (size_t)kWaves * kFusedG * kQcap * 10;
     const u32 n_groups = (pl.n_sub + kFusedG - 1) / kFusedG;
@@ -1536,13 +1655,21 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
     FDY_HIP_TRY(hipGetLastError());
     return FDY_OK;
   }
-  const size_t lds = lds0 + (size_t)kWaves * pl.g * kQcap * (8 + 2 * 2 * pl.groups);
-  auto kern = pl.g == kGSmall ? (half ? scan_kernel<kGroupsSmall, kGSmall, true> : scan_kernel<kGroupsSmall, kGSmall, false>)
-                              : (half ? scan_kernel<kGroupsBig, kGBig, true> : scan_kernel<kGroupsBig, kGBig, false>);
+  // per wave: the value queue (or, with a rebased output, the words of a group) and the
+  // index queues of two chunks
+  const size_t lds = lds0 + (size_t)kWaves * pl.g * ((ordered_out ? (size_t)kSub : (size_t)kQcap) * 8 +
+                                                      (size_t)kQcap * 2 * 2 * pl.groups);
+  auto kern = pl.g == kGSmall ? (half          ? scan_kernel<kGroupsSmall, kGSmall, true, false>
+                                 : ordered_out ? scan_kernel<kGroupsSmall, kGSmall, false, true>
+                                               : scan_kernel<kGroupsSmall, kGSmall, false, false>)
+                              : (half          ? scan_kernel<kGroupsBig, kGBig, true, false>
+                                 : ordered_out ? scan_kernel<kGroupsBig, kGBig, false, true>
+                                               : scan_kernel<kGroupsBig, kGBig, false, false>);
   FDY_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  prof_begin(FDY_PROF_SCAN_MAIN, stream);
+  const int slot = ordered_out ? FDY_PROF_SCAN_OUT : FDY_PROF_SCAN_MAIN;
+  prof_begin(slot, stream);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), lds, stream, p);
-  prof_end(FDY_PROF_SCAN_MAIN, stream);
+  prof_end(slot, stream);
   FDY_HIP_TRY(hipGetLastError());
   return FDY_OK;
 }
@@ -1584,6 +1711,22 @@ extern "C" int fdy_scan_rebase(const uint64_t* d_words, uint64_t n_words, const 
   }
   return scan_launch(d_words, n_words, d_table, n_alloc, nullptr, 0, d_count, d_new_base, d_out_words,
                      d_workspace, workspace_bytes, d_status, hip_stream);
+}
+
+extern "C" int fdy_scan_pointers_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
+                                        uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
+                                        uint64_t* d_count, const uint64_t* d_new_base, uint64_t* d_out_words,
+                                        void* d_workspace, size_t workspace_bytes, uint32_t* d_status,
+                                        void* hip_stream) {
+  if (n_words && (!d_out_words || ((uintptr_t)d_out_words & 15))) return FDY_ERR_INVALID_ARG;
+  if (n_alloc && (!d_new_base || ((uintptr_t)d_new_base & 7))) return FDY_ERR_INVALID_ARG;
+  if (n_words) {  // the output is written while other workgroups still read the input
+    const uintptr_t a = (uintptr_t)d_words, b = (uintptr_t)d_out_words, len = (uintptr_t)n_words * 8;
+    if (a < b + len && b < a + len) return FDY_ERR_INVALID_ARG;
+  }
+  return scan_launch(d_words, n_words, d_table, n_alloc, d_relocs, reloc_capacity, d_count, d_new_base,
+                     n_words ? d_out_words : nullptr, d_workspace, workspace_bytes, d_status, hip_stream, false,
+                     true);
 }
 
 extern "C" int fdy_reloc_segment(const fdy_reloc* d_relocs, const uint64_t* d_count,

@@ -35,7 +35,7 @@ enum {
   FDY_PROF_MAT_PREP_GRAPHS = 5,
   FDY_PROF_MAT_PREP_TILES = 6,
   FDY_PROF_MAT_MAIN = 7,
-  FDY_PROF_MAT_DIMS = 8,
+  FDY_PROF_SCAN_OUT = 8,
   FDY_PROF_SCAN_REBASE = 9,
   FDY_PROF_SLOTS = 10
 };

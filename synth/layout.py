@@ -38,3 +38,4 @@ ST_CAPACITY = 0x1
 ST_BAD_INDEX = 0x2
 ST_BAD_SIZE = 0x4
 ST_SPIN = 0x8
+ST_BAD_ORDER = 0x10

@@ -1,6 +1,7 @@
-"""Convenience layer over the binding for tests, the smoke check and the bench: uploads host
-arrays, allocates outputs / workspaces with torch, calls the C-ABI entry points and brings
-results back.  Marshalling only - no step of the method is computed here."""
+"""Convenience layer over the binding for tests, the smoke check and the bench (test support,
+not part of the product package): uploads host arrays, allocates outputs / workspaces with
+torch, calls the C-ABI entry points and brings results back.  Marshalling only - no step of
+the method is computed here."""
 from __future__ import annotations
 
 import numpy as np
@@ -107,6 +108,31 @@ class ScanRebaseRun:
                 int(self.d_status.item()))
 
 
+class ScanPointersRebaseRun(ScanRun):
+    """fdy_scan_pointers_rebase: the relocation table and the rebased copy of the words."""
+
+    def __init__(self, words, table, new_base, capacity=None):
+        super().__init__(words, table, capacity)
+        self.d_new_base = new_base if torch.is_tensor(new_base) else fdy.to_device(
+            np.ascontiguousarray(new_base, np.uint64))
+        self.d_out = fdy.device_bytes(self.n_words * 8, fill=0xEE)
+
+    def launch(self, stream=None):
+        return fdy.fdy_scan_pointers_rebase(self.d_words, self.n_words, self.d_table, self.n_alloc,
+                                            self.d_relocs, self.capacity, self.d_count, self.d_new_base,
+                                            self.d_out, self.d_ws, self.ws_bytes, self.d_status, stream)
+
+    def result(self):
+        relocs, count, status = super().result()
+        return relocs, count, status, fdy.to_host(self.d_out, np.uint64, self.n_words)
+
+
+def scan_pointers_rebase(words, table, new_base, capacity=None):
+    run = ScanPointersRebaseRun(words, table, new_base, capacity)
+    run.launch()
+    return run.result()
+
+
 def scan_rebase(words, table, new_base, in_place=False):
     run = ScanRebaseRun(words, table, new_base, in_place)
     run.launch()
@@ -167,7 +193,7 @@ class MatRun:
     `mp` is a synth.MatProblem (host arrays); `device_overrides` may replace uploaded arrays
     by tensors that are already on the device (e.g. relocs straight from a scan)."""
 
-    def __init__(self, mp, want_dims=True, device_overrides=None, poison=True):
+    def __init__(self, mp, want_dims=True, device_overrides=None, poison=True, out=None):
         self.mp = mp
         dev = dict(device_overrides or {})
         for name in mp.ARRAYS:
@@ -180,7 +206,8 @@ class MatRun:
         self.desc = fdy.make_mat_desc(
             dev, n_src_graphs=mp.S, n_templates=mp.T, n_graphs=mp.G, n_maps=mp.M, n_alloc=mp.A,
             n_ranks=mp.n_ranks, out_words_per_map=self.wpm, out_nodes_total=self.nodes_total)
-        self.d_out = fdy.device_bytes(mp.M * self.wpm * 8, fill=0xCD if poison else None)
+        self.d_out = out if out is not None else fdy.device_bytes(mp.M * self.wpm * 8,
+                                                                  fill=0xCD if poison else None)
         self.d_dims = (fdy.device_bytes(self.nodes_total * 24, fill=0xCD if poison else None)
                        if want_dims else None)
         self.ws_bytes = fdy.fdy_materialize_workspace_bytes(self.desc)
@@ -211,14 +238,27 @@ class PathRun:
     `ar` is a synth.Archive; `reloc_capacity` bounds the relocation table (host knowledge:
     at most one entry per word)."""
 
-    def __init__(self, ar, reloc_capacity=None, want_dims=True, maps=None):
+    def __init__(self, ar, reloc_capacity=None, want_dims=True, maps=None, one_pass=None):
+        """one_pass: the scan itself writes the materialized output (fdy_scan_pointers_rebase) and
+        fdy_materialize is not called.  That is the whole of (c) when every graph is its own
+        template and there is one base map and nothing to override or patch; None = use it
+        exactly then."""
         from synth import MatProblem
 
         self.ar = ar
         G = ar.n_graphs
         self.G = G
         cap = len(ar.words) if reloc_capacity is None else int(reloc_capacity)
-        self.scan = ScanRun(ar.words, ar.table, cap)
+        own = (ar.n_templates == G and np.array_equal(ar.graph_tmpl, np.arange(G))
+               and np.array_equal(ar.tmpl_graph, np.arange(G)))
+        can = bool(own and ar.n_maps == 1 and maps is None and len(ar.ovr) == 0 and len(ar.govr) == 0
+                   and len(ar.patch) == 0 and len(ar.nodes) == 0)
+        self.one_pass = can if one_pass is None else bool(one_pass)
+        assert can or not self.one_pass
+        if self.one_pass:
+            self.scan = ScanPointersRebaseRun(ar.words, ar.table, ar.new_base[0], cap)
+        else:
+            self.scan = ScanRun(ar.words, ar.table, cap)
         self.d_word_off = fdy.to_device(ar.word_off)
         self.d_reloc_off = fdy.device_bytes((G + 1) * 8, fill=0xEE)
         self.d_nodes = fdy.to_device(ar.nodes)
@@ -234,7 +274,7 @@ class PathRun:
         self.mat = MatRun(mp, want_dims=want_dims and len(ar.nodes) > 0, device_overrides=dict(
             src_words=self.scan.d_words, relocs=self.scan.d_relocs, src_reloc_off=self.d_reloc_off,
             src_nodes=self.d_nodes, src_node_off=self.d_node_off, graph_tmpl=self.d_tid,
-            tmpl_graph=self.d_tg))
+            tmpl_graph=self.d_tg), out=self.scan.d_out if self.one_pass else None)
 
     def step(self, stream=None):
         ar = self.ar
@@ -243,7 +283,8 @@ class PathRun:
                               self.d_word_off, self.G + 1, self.d_reloc_off, stream)
         fdy.fdy_fingerprint(self.d_nodes, self.d_node_off, self.G, ar.fp_mask, self.d_keys,
                             self.d_tid, self.d_tg, self.d_nt, stream)
-        self.mat.launch(stream)
+        if not self.one_pass:
+            self.mat.launch(stream)
 
     def status(self):
         torch.cuda.synchronize()

@@ -25,7 +25,7 @@ def hip():
 
     assert torch.cuda.is_available(), "gpu tests need a GPU"
     import paper_2604_06664_amd as fdy
-    from paper_2604_06664_amd import session
+    from tests.support import session
 
     fdy.lib()
     return session

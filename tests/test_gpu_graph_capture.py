@@ -19,7 +19,7 @@ def test_captured_step_replays_like_eager(idx):
 
     assert torch.cuda.is_available()
     import paper_2604_06664_amd as fdy
-    from paper_2604_06664_amd import session
+    from tests.support import session
 
     fdy.lib()
     ar = small(idx)

@@ -16,7 +16,7 @@ def hip():
 
     assert torch.cuda.is_available(), "gpu tests need a GPU"
     import paper_2604_06664_amd as fdy
-    from paper_2604_06664_amd import session
+    from tests.support import session
 
     fdy.lib()
     return session
@@ -436,6 +436,62 @@ def test_scan_rebase_there_and_back(hip, oracle, idx):
     assert np.array_equal(relocs["offset"][at], ar.ptr_offset)
 
 
+# ------------------------------------------- scan with rebased output (table and copy in one pass)
+def check_scan_out(hip, oracle, words, table, new_base, capacity=None, tag=""):
+    """fdy_scan_pointers_rebase = the oracle's scan (table) and the oracle's scan + materialize of
+    one own-template graph under one base map (output)."""
+    say(f"[scan_pointers_rebase] {tag} W={len(words)} A={len(table)} cap={capacity}")
+    ref, rcnt = oracle.scan(words, table, capacity)
+    want, _ = oracle_rebase(oracle, words, table, new_base) if len(words) else (np.zeros(0, np.uint64), 0)
+    got, cnt, status, out = hip.scan_pointers_rebase(words, table, new_base, capacity)
+    assert cnt == rcnt
+    assert np.array_equal(got, ref)
+    cap = len(words) if capacity is None else capacity
+    assert status == (L.ST_CAPACITY if rcnt > cap else 0)
+    assert np.array_equal(out, want)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_scan_pointers_rebase_small_configs(hip, oracle, idx):
+    ar = small(idx)
+    check_scan_out(hip, oracle, ar.words, ar.table, ar.new_base[0], tag=ar.name)
+
+
+def test_scan_pointers_rebase_edge_cases(hip, oracle):
+    import paper_2604_06664_amd as fdy
+
+    ar = small(4)  # 65,536 allocations
+    nb = ar.new_base[0]
+    check_scan_out(hip, oracle, np.zeros(0, np.uint64), ar.table, nb, tag="no words")
+    check_scan_out(hip, oracle, ar.words[:1], ar.table, nb, tag="one word")
+    for n in (511, 512, 513, 1023, 1025, 4097, 16384, 16385, 70001):  # sub-tile, group, chunk edges
+        check_scan_out(hip, oracle, ar.words[:n], ar.table, nb, tag="ragged")
+    check_scan_out(hip, oracle, ar.words[:5000], ar.table[:0], nb[:0], tag="no table: a plain copy")
+    check_scan_out(hip, oracle, ar.words[:300000], ar.table, nb, capacity=1000, tag="capacity exceeded")
+    # every word a hit (dense groups: windowed path with staged entries), touching intervals,
+    # extremes, sums that wrap mod 2^64
+    dense = mk_table([(0x1000 + 64 * i, 64) for i in range(300)] + [(2**64 - 0x100, 0xFF)])
+    rng = np.random.default_rng(5)
+    w = (0x1000 + rng.integers(0, 64 * 300, 9000)).astype(np.uint64)
+    w[::97] = np.uint64(2**64 - 1)
+    w[1::97] = np.uint64(2**64 - 2)
+    w[2::97] = np.uint64(0xFFF)
+    dnb = rng.integers(0, 1 << 64, len(dense), dtype=np.uint64)
+    check_scan_out(hip, oracle, w, dense, dnb, tag="all hits")
+    # a large input (the large-chunk kernel) whose first part is dense and whose rest is sparse
+    big = np.concatenate([w] * 40 + [ar.words[:3_000_000]])
+    tb = np.concatenate([dense[:300], ar.table]) if dense["base"][299] < ar.table["base"][0] else ar.table
+    nb2 = rng.integers(0, 1 << 64, len(tb), dtype=np.uint64)
+    check_scan_out(hip, oracle, big, tb, nb2, tag="large, dense head")
+    # overlapping input and output are refused on the host, in place included
+    run = hip.ScanPointersRebaseRun(ar.words[:4096], ar.table, nb)
+    for out in (run.d_words.data_ptr(), run.d_words.data_ptr() + 1024 * 8):
+        rc = fdy.fdy_scan_pointers_rebase(run.d_words, 2048, run.d_table, run.n_alloc, run.d_relocs,
+                                          run.capacity, run.d_count, run.d_new_base, out, run.d_ws,
+                                          run.ws_bytes, run.d_status, check=False)
+        assert rc == fdy.FDY_ERR_INVALID_ARG
+
+
 def test_reloc_segment(hip, oracle):
     ar = small(2)
     run = hip.ScanRun(ar.words, ar.table)
@@ -641,6 +697,65 @@ def test_materialize_bad_inputs_are_flagged_not_faulting(hip, oracle):
                                check=False) == fdy.FDY_ERR_WORKSPACE
     assert fdy.fdy_materialize(run.desc, run.d_out.data_ptr() + 8, None, run.d_ws, run.ws_bytes,
                                run.d_status, check=False) == fdy.FDY_ERR_INVALID_ARG
+
+
+def test_materialize_lists_out_of_order_are_flagged(hip, oracle):
+    """Every list must ascend strictly by location (the tile slices are found by binary search):
+    a swapped pair, or a location twice, in a relocation, override, grid-override or patch list
+    raises FDY_ST_BAD_ORDER on the device, at the start, in the middle and across a tile edge;
+    the oracle refuses the same inputs.  Valid inputs raise nothing."""
+    rng = np.random.default_rng(11)
+    for idx in (2, 3):
+        ar = small(idx)
+        mp = problem(oracle, ar, maps=[0, 1] if idx == 3 else None)
+        base = {n: getattr(mp, n) for n in MatProblem.ARRAYS}
+        _, _, status = hip.materialize(MatProblem(n_ranks=mp.n_ranks, **base))
+        assert status == 0
+
+        def damaged(name, off_name, key, rows, how):
+            """One list of kind `name` (a row of its offset array that has at least 3 entries)
+            with entries i, i+1 swapped or made equal."""
+            arr = getattr(mp, name).copy()
+            off = getattr(mp, off_name).astype(np.int64)
+            rows = [r for r in rows if off[r + 1] - off[r] >= 3]
+            r = rows[int(rng.integers(len(rows)))]
+            n = off[r + 1] - off[r]
+            for where in (0, n // 2, n - 2):
+                a = arr.copy()
+                i = off[r] + where
+                if how == "swap":
+                    a[[i, i + 1]] = a[[i + 1, i]]
+                else:
+                    a[key][i + 1] = a[key][i]
+                yield a
+
+        kinds = [("relocs", "src_reloc_off", "word", [int(s) for s in mp.tmpl_graph]),
+                 ("ovr", "ovr_off", "byte_off", range(mp.G)),
+                 ("govr", "govr_off", "node", range(mp.G))]
+        if mp.map_rank is not None:
+            kinds.append(("patch", "patch_off", "word", range(mp.T * mp.n_ranks)))
+        for name, off_name, key, rows in kinds:
+            for how in ("swap", "equal"):
+                for arr in damaged(name, off_name, key, list(rows), how):
+                    kw = dict(base)
+                    kw[name] = arr
+                    bad = MatProblem(n_ranks=mp.n_ranks, **kw)
+                    say(f"[order] config {idx}: {name} {how}")
+                    with pytest.raises(Exception):
+                        oracle.materialize(bad)
+                    _, _, status = hip.materialize(bad)
+                    assert status & L.ST_BAD_ORDER, (name, how, status)
+    # a long relocation list whose disorder sits exactly at a tile edge (words 2047 | 2048)
+    ar = small(4)
+    mp = problem(oracle, ar)
+    rel = mp.relocs.copy()
+    i = int(np.searchsorted(rel["word"], 2048))
+    assert 0 < i < len(rel) - 1
+    rel[[i - 1, i]] = rel[[i, i - 1]]
+    kw = {n: getattr(mp, n) for n in MatProblem.ARRAYS}
+    kw["relocs"] = rel
+    _, _, status = hip.materialize(MatProblem(n_ranks=0, **kw), want_dims=False)
+    assert status & L.ST_BAD_ORDER
 
 
 # ------------------------------------------------------------------- whole path, full sizes

@@ -93,7 +93,7 @@ def test_random_scan_and_rebase(oracle, case):
 
     assert torch.cuda.is_available()
     import paper_2604_06664_amd as fdy
-    from paper_2604_06664_amd import session
+    from tests.support import session
     from tests.test_gpu_parity import oracle_rebase
 
     W, A, shape, density, top_log2 = CASES[case]
