@@ -70,6 +70,10 @@ extern "C" {
                                  patch list is not strictly ascending by location; the
                                  output is unspecified (entries may be missing)          */
 
+#define FDY_ST_BAD_PREPARED 0x20u /* scan: d_prepared was not made by fdy_scan_table_prepare
+                                    for this table and at least this many words; nothing
+                                    was read from it and no output was written            */
+
 /* ---- plain-data records ------------------------------------------------------------ */
 
 /* One allocation of the deterministic layout: the half-open byte range [base, base+size).
@@ -202,16 +206,49 @@ int fdy_layout_replay(const fdy_alloc* h_recorded, uint32_t n, uint64_t recorded
  *   d_workspace      device, 256-byte aligned, at least fdy_scan_workspace_bytes() bytes;
  *                    contents on entry are irrelevant, contents on exit are unspecified.
  *                    The size is the search hierarchy built from the table (about 14 bytes
- *                    per allocation beyond 16,384 of them), 8 bytes per 16,384 words, and a
- *                    staging area of 32 bytes per word up to 160 MiB (word-dense inputs);
- *                    0 is returned for n_words beyond the limit above
+ *                    per allocation beyond 16,384 of them) and 8 bytes per 4,096 words;
+ *                    0 is returned for n_words beyond the limit above.
+ *                    Optional staging area: where more than 3 words in 8 lie inside the
+ *                    table's span (word-dense inputs), the hits of such a stretch are either
+ *                    staged (a workspace of fdy_scan_workspace_bytes() +
+ *                    fdy_scan_staging_bytes() bytes or more: up to 160 MiB, independent of
+ *                    the table) or found by searching the stretch a second time (any smaller
+ *                    workspace; about 1.6 times slower on inputs that are dense throughout).
+ *                    Same results either way
+ *   d_prepared       NULL, or the table's prepared form (see fdy_scan_table_prepare below)
  *   d_status         device uint32_t or NULL
  */
 size_t fdy_scan_workspace_bytes(uint64_t n_words, uint32_t n_alloc);
+size_t fdy_scan_staging_bytes(uint64_t n_words);
 int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
                       uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
-                      uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
-                      uint32_t* d_status, void* hip_stream);
+                      uint64_t* d_count, const void* d_prepared, void* d_workspace,
+                      size_t workspace_bytes, uint32_t* d_status, void* hip_stream);
+
+/* ---- prepared table (optional; one per allocation table) ------------------------------
+ * The layout, hence the allocation table, is fixed for the life of an archive (Section
+ * 4.1.1), while blobs are scanned many times against it.  What a scan derives from the table
+ * alone (its search hierarchy) can therefore be built once, into a device buffer that the
+ * caller owns, and handed to every scan of that table as d_prepared; such a call launches
+ * one kernel where it otherwise launches two.  The buffer also holds the scan's counters
+ * (work ticket, per-chunk totals), which a scan leaves zeroed behind it:
+ *   - calls that share a prepared table must not overlap in time (one stream, or ordered by
+ *     events); read-only sharing is not possible;
+ *   - after a call that returned FDY_ERR_HIP, or that raised FDY_ST_SPIN, prepare it again;
+ *   - the buffer belongs to the table at d_table (same address and contents), to n_words <=
+ *     max_words and to the process's tuning at the time; the device checks this and raises
+ *     FDY_ST_BAD_PREPARED, writing nothing, when it does not hold.
+ * With d_prepared the workspace only holds the optional staging area of dense inputs
+ * (fdy_scan_staging_bytes; NULL or anything smaller: none).  d_prepared == NULL: the call
+ * builds the hierarchy into its workspace itself.
+ *
+ *   fdy_scan_table_bytes    size of the buffer for a table of n_alloc entries that serves
+ *                           scans of up to max_words words (0: max_words out of range)
+ *   fdy_scan_table_prepare  enqueues the build; d_prepared device, 256-byte aligned
+ */
+size_t fdy_scan_table_bytes(uint32_t n_alloc, uint64_t max_words);
+int fdy_scan_table_prepare(const fdy_alloc* d_table, uint32_t n_alloc, uint64_t max_words,
+                           void* d_prepared, size_t prepared_bytes, void* hip_stream);
 
 /* ---- fused scan + rebase (variant; a1 + c1 + c2 in one pass) ------------------------
  * For one new layout and no templating (a new instance whose addresses differ, Section
@@ -228,13 +265,13 @@ int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, const fdy_alloc
  *   d_out_words      [n_words] device, 16-byte aligned; either d_words itself (in place) or
  *                    an array that does not overlap it (anything else: FDY_ERR_INVALID_ARG)
  *   d_count          device uint64_t: number of hits
- *   d_workspace      as for fdy_scan_pointers (same size query)
- *   d_status         device uint32_t or NULL (no status bit is raised by this call today)
+ *   d_prepared, d_workspace   as for fdy_scan_pointers (same size query)
+ *   d_status         device uint32_t or NULL
  */
 int fdy_scan_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
                     uint32_t n_alloc, const uint64_t* d_new_base, uint64_t* d_out_words,
-                    uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
-                    uint32_t* d_status, void* hip_stream);
+                    uint64_t* d_count, const void* d_prepared, void* d_workspace,
+                    size_t workspace_bytes, uint32_t* d_status, void* hip_stream);
 
 /* ---- scan with rebased output (a1 + c1 + c2 for one layout, relocation table kept) ------
  * fdy_scan_pointers and fdy_scan_rebase in one pass over the words: the relocation table is
@@ -246,7 +283,7 @@ int fdy_scan_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* 
  * materialization, while the table stays available for further base maps (fdy_materialize)
  * and for storing with the archive.  Overrides and rank patches are not applied by this call.
  *
- *   d_words, d_table, d_relocs, reloc_capacity, d_count, d_workspace, d_status
+ *   d_words, d_table, d_relocs, reloc_capacity, d_count, d_prepared, d_workspace, d_status
  *                    as for fdy_scan_pointers (same size query)
  *   d_new_base       [n_alloc] device, 8-byte aligned
  *   d_out_words      [n_words] device, 16-byte aligned, must not overlap d_words
@@ -255,8 +292,8 @@ int fdy_scan_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* 
 int fdy_scan_pointers_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
                              uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
                              uint64_t* d_count, const uint64_t* d_new_base, uint64_t* d_out_words,
-                             void* d_workspace, size_t workspace_bytes, uint32_t* d_status,
-                             void* hip_stream);
+                             const void* d_prepared, void* d_workspace, size_t workspace_bytes,
+                             uint32_t* d_status, void* hip_stream);
 
 /* Variant of fdy_scan_pointers for pointers at 4-byte alignment (argument buffers are opaque
  * byte strings, Section 2.2 / Appendix B: a packed structure may hold a pointer at any
@@ -271,8 +308,8 @@ int fdy_scan_pointers_rebase(const uint64_t* d_words, uint64_t n_words, const fd
  * two positions) and writes the relocation table once. */
 int fdy_scan_pointers_stride4(const uint32_t* d_units, uint64_t n_units, const fdy_alloc* d_table,
                               uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
-                              uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
-                              uint32_t* d_status, void* hip_stream);
+                              uint64_t* d_count, const void* d_prepared, void* d_workspace,
+                              size_t workspace_bytes, uint32_t* d_status, void* hip_stream);
 
 /* ---- (a2) relocation segmentation ---------------------------------------------------
  * For each boundary d_word_off[s], s in [0, n_off): d_reloc_off[s] = number of entries of
@@ -305,11 +342,32 @@ int fdy_reloc_segment(const fdy_reloc* d_relocs, const uint64_t* d_count,
  *   d_template_id    [n_graphs] out
  *   d_tmpl_graph     [n_graphs] out (first *d_n_templates entries meaningful) or NULL
  *   d_n_templates    device uint32_t out
- *   n_graphs         <= 65536
+ *   n_graphs         <= 2^20
+ *   d_workspace      device, 256-byte aligned, >= fdy_fingerprint_workspace_bytes(n_graphs)
+ *                    bytes; only archives of more than 8,192 graphs use it (NULL is accepted
+ *                    up to there); contents on entry are irrelevant
+ * Grouping takes time linear in the number of graphs (a hash table over the keys).
  */
+size_t fdy_fingerprint_workspace_bytes(uint32_t n_graphs);
 int fdy_fingerprint(const fdy_node* d_nodes, const uint64_t* d_node_off, uint32_t n_graphs,
                     uint32_t field_mask, uint64_t* d_keys, uint32_t* d_template_id,
-                    uint32_t* d_tmpl_graph, uint32_t* d_n_templates, void* hip_stream);
+                    uint32_t* d_tmpl_graph, uint32_t* d_n_templates, void* d_workspace,
+                    size_t workspace_bytes, void* hip_stream);
+
+/* (a2) and (b) in one launch: fdy_reloc_segment over the archive's per-graph word offsets
+ * (d_word_off and d_reloc_off are [n_graphs + 1]) and fdy_fingerprint, same results.  The
+ * archives of Section 6.1 (one graph per batch size of a 36- or 94-layer model) are so small
+ * that a LOAD step is bound by the number of launches, not by bandwidth.  With a prepared
+ * table (any buffer made by fdy_scan_table_prepare; its first block holds a counter that this
+ * call finds zero and leaves zero, so calls sharing it must not overlap) and at most 8,192
+ * graphs the grouping runs in the same launch, in the last block to finish; with d_prepared
+ * NULL it is a launch of its own.  Other arguments as for the two plain calls. */
+int fdy_segment_fingerprint(const fdy_reloc* d_relocs, const uint64_t* d_count, uint64_t reloc_capacity,
+                            const uint64_t* d_word_off, uint64_t* d_reloc_off,
+                            const fdy_node* d_nodes, const uint64_t* d_node_off, uint32_t n_graphs,
+                            uint32_t field_mask, uint64_t* d_keys, uint32_t* d_template_id,
+                            uint32_t* d_tmpl_graph, uint32_t* d_n_templates, void* d_prepared,
+                            void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---- override derivation (SAVE side of templating; variant, after (b)) ----------------
  * Within a topology group the graphs differ only in per-node parameters (Section 4.2.1,

@@ -65,26 +65,40 @@ def lib():
                                         C.c_void_p]
         L.fdy_scan_workspace_bytes.restype = C.c_size_t
         L.fdy_scan_workspace_bytes.argtypes = [C.c_uint64, C.c_uint32]
+        L.fdy_scan_staging_bytes.restype = C.c_size_t
+        L.fdy_scan_staging_bytes.argtypes = [C.c_uint64]
         L.fdy_scan_pointers.restype = C.c_int
         L.fdy_scan_pointers.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p,
-                                        C.c_uint64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
-                                        C.c_void_p]
+                                        C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                        C.c_void_p, C.c_void_p]
+        L.fdy_scan_table_bytes.restype = C.c_size_t
+        L.fdy_scan_table_bytes.argtypes = [C.c_uint32, C.c_uint64]
+        L.fdy_scan_table_prepare.restype = C.c_int
+        L.fdy_scan_table_prepare.argtypes = [C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p, C.c_size_t,
+                                             C.c_void_p]
         L.fdy_scan_pointers_stride4.restype = C.c_int
         L.fdy_scan_pointers_stride4.argtypes = L.fdy_scan_pointers.argtypes
         L.fdy_scan_rebase.restype = C.c_int
         L.fdy_scan_rebase.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p,
-                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
-                                      C.c_void_p]
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                      C.c_void_p, C.c_void_p]
         L.fdy_scan_pointers_rebase.restype = C.c_int
         L.fdy_scan_pointers_rebase.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p,
                                                C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                               C.c_size_t, C.c_void_p, C.c_void_p]
+                                               C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.fdy_reloc_segment.restype = C.c_int
         L.fdy_reloc_segment.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32,
                                         C.c_void_p, C.c_void_p]
         L.fdy_fingerprint.restype = C.c_int
         L.fdy_fingerprint.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p,
-                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.fdy_fingerprint_workspace_bytes.restype = C.c_size_t
+        L.fdy_fingerprint_workspace_bytes.argtypes = [C.c_uint32]
+        L.fdy_segment_fingerprint.restype = C.c_int
+        L.fdy_segment_fingerprint.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_size_t, C.c_void_p]
         L.fdy_derive_workspace_bytes.restype = C.c_size_t
         L.fdy_derive_workspace_bytes.argtypes = [C.c_uint64, C.c_uint32]
         L.fdy_derive_overrides.restype = C.c_int
@@ -186,39 +200,56 @@ def fdy_scan_workspace_bytes(n_words, n_alloc):
     return lib().fdy_scan_workspace_bytes(int(n_words), int(n_alloc))
 
 
+def fdy_scan_staging_bytes(n_words):
+    return lib().fdy_scan_staging_bytes(int(n_words))
+
+
+def fdy_scan_table_bytes(n_alloc, max_words):
+    return lib().fdy_scan_table_bytes(int(n_alloc), int(max_words))
+
+
+def fdy_scan_table_prepare(d_table, n_alloc, max_words, d_prepared, prepared_bytes, stream=None,
+                           check=True):
+    rc = lib().fdy_scan_table_prepare(_ptr(d_table), int(n_alloc), int(max_words), _ptr(d_prepared),
+                                      int(prepared_bytes), _stream(stream))
+    return _check(rc, "fdy_scan_table_prepare") if check else rc
+
+
 def fdy_scan_pointers(d_words, n_words, d_table, n_alloc, d_relocs, reloc_capacity, d_count,
-                      d_workspace, workspace_bytes, d_status=None, stream=None, check=True):
+                      d_prepared, d_workspace, workspace_bytes, d_status=None, stream=None, check=True):
     rc = lib().fdy_scan_pointers(_ptr(d_words), int(n_words), _ptr(d_table), int(n_alloc),
-                                 _ptr(d_relocs), int(reloc_capacity), _ptr(d_count),
+                                 _ptr(d_relocs), int(reloc_capacity), _ptr(d_count), _ptr(d_prepared),
                                  _ptr(d_workspace), int(workspace_bytes), _ptr(d_status),
                                  _stream(stream))
     return _check(rc, "fdy_scan_pointers") if check else rc
 
 
 def fdy_scan_pointers_stride4(d_units, n_units, d_table, n_alloc, d_relocs, reloc_capacity, d_count,
-                              d_workspace, workspace_bytes, d_status=None, stream=None, check=True):
+                              d_prepared, d_workspace, workspace_bytes, d_status=None, stream=None,
+                              check=True):
     rc = lib().fdy_scan_pointers_stride4(_ptr(d_units), int(n_units), _ptr(d_table), int(n_alloc),
                                          _ptr(d_relocs), int(reloc_capacity), _ptr(d_count),
-                                         _ptr(d_workspace), int(workspace_bytes), _ptr(d_status),
-                                         _stream(stream))
+                                         _ptr(d_prepared), _ptr(d_workspace), int(workspace_bytes),
+                                         _ptr(d_status), _stream(stream))
     return _check(rc, "fdy_scan_pointers_stride4") if check else rc
 
 
 def fdy_scan_rebase(d_words, n_words, d_table, n_alloc, d_new_base, d_out_words, d_count,
-                    d_workspace, workspace_bytes, d_status=None, stream=None, check=True):
+                    d_prepared, d_workspace, workspace_bytes, d_status=None, stream=None, check=True):
     rc = lib().fdy_scan_rebase(_ptr(d_words), int(n_words), _ptr(d_table), int(n_alloc),
-                               _ptr(d_new_base), _ptr(d_out_words), _ptr(d_count), _ptr(d_workspace),
-                               int(workspace_bytes), _ptr(d_status), _stream(stream))
+                               _ptr(d_new_base), _ptr(d_out_words), _ptr(d_count), _ptr(d_prepared),
+                               _ptr(d_workspace), int(workspace_bytes), _ptr(d_status), _stream(stream))
     return _check(rc, "fdy_scan_rebase") if check else rc
 
 
 def fdy_scan_pointers_rebase(d_words, n_words, d_table, n_alloc, d_relocs, reloc_capacity, d_count,
-                             d_new_base, d_out_words, d_workspace, workspace_bytes, d_status=None,
-                             stream=None, check=True):
+                             d_new_base, d_out_words, d_prepared, d_workspace, workspace_bytes,
+                             d_status=None, stream=None, check=True):
     rc = lib().fdy_scan_pointers_rebase(_ptr(d_words), int(n_words), _ptr(d_table), int(n_alloc),
                                         _ptr(d_relocs), int(reloc_capacity), _ptr(d_count),
-                                        _ptr(d_new_base), _ptr(d_out_words), _ptr(d_workspace),
-                                        int(workspace_bytes), _ptr(d_status), _stream(stream))
+                                        _ptr(d_new_base), _ptr(d_out_words), _ptr(d_prepared),
+                                        _ptr(d_workspace), int(workspace_bytes), _ptr(d_status),
+                                        _stream(stream))
     return _check(rc, "fdy_scan_pointers_rebase") if check else rc
 
 
@@ -229,12 +260,27 @@ def fdy_reloc_segment(d_relocs, d_count, reloc_capacity, d_word_off, n_off, d_re
     return _check(rc, "fdy_reloc_segment") if check else rc
 
 
+def fdy_fingerprint_workspace_bytes(n_graphs):
+    return lib().fdy_fingerprint_workspace_bytes(int(n_graphs))
+
+
 def fdy_fingerprint(d_nodes, d_node_off, n_graphs, field_mask, d_keys, d_template_id, d_tmpl_graph,
-                    d_n_templates, stream=None, check=True):
+                    d_n_templates, stream=None, check=True, d_workspace=None, workspace_bytes=0):
     rc = lib().fdy_fingerprint(_ptr(d_nodes), _ptr(d_node_off), int(n_graphs), int(field_mask),
                                _ptr(d_keys), _ptr(d_template_id), _ptr(d_tmpl_graph),
-                               _ptr(d_n_templates), _stream(stream))
+                               _ptr(d_n_templates), _ptr(d_workspace), int(workspace_bytes), _stream(stream))
     return _check(rc, "fdy_fingerprint") if check else rc
+
+
+def fdy_segment_fingerprint(d_relocs, d_count, reloc_capacity, d_word_off, d_reloc_off, d_nodes, d_node_off,
+                            n_graphs, field_mask, d_keys, d_template_id, d_tmpl_graph, d_n_templates,
+                            d_prepared=None, d_workspace=None, workspace_bytes=0, stream=None, check=True):
+    rc = lib().fdy_segment_fingerprint(_ptr(d_relocs), _ptr(d_count), int(reloc_capacity), _ptr(d_word_off),
+                                       _ptr(d_reloc_off), _ptr(d_nodes), _ptr(d_node_off), int(n_graphs),
+                                       int(field_mask), _ptr(d_keys), _ptr(d_template_id), _ptr(d_tmpl_graph),
+                                       _ptr(d_n_templates), _ptr(d_prepared), _ptr(d_workspace),
+                                       int(workspace_bytes), _stream(stream))
+    return _check(rc, "fdy_segment_fingerprint") if check else rc
 
 
 def fdy_derive_workspace_bytes(n_words_total, n_graphs):

@@ -111,7 +111,14 @@ struct ScanParams {
   const uint4* cmid;        // compact copy of packed level 1, 32 bytes per node of 8 keys (null: not built)
   const uint4* cleaf;       // compact copy of the table, 32 bytes per 8 entries (null: not built)
   u64* cstate;     // [n_chunks] per-chunk totals / inclusive prefixes
-  fdy_reloc* stage;  // [grid][2][sub-tiles of a chunk * kSub]: staged entries of dense groups
+  u32* done;       // workgroups that have finished (the last one resets the state behind it)
+  u64* acc;        // fused scan + rebase: hits so far
+  u32 n_chunks;
+  u32 self_clean;  // the state (ticket, chunk states, counters) is left zeroed for the next call
+  const u64* prepared;  // the caller's prepared table (its header is checked on the device), or null
+  u32 top_log2;         // the tuning that the hierarchy's layout depends on
+  fdy_reloc* stage;  // [grid][2][sub-tiles of a chunk * kSub]: staged entries of dense groups; null:
+                     // no staging area, dense groups are searched twice
   u32 n_sub;       // sub-tiles
   u32 top_n;       // power of two
   u32 levels;      // k: 8-ary levels below level 0, the table line included
@@ -197,6 +204,45 @@ __device__ __forceinline__ u64 wave_incl_scan_u64(u64 v) {
     if (l >= (u32)d) v += o;
   }
   return v;
+}
+
+// A prepared table: magic and what it was made for (four 64-bit words), then the hierarchy,
+// then the state.
+struct PreparedHeader {
+  u64 magic;
+  u32 n_alloc, top_log2;
+  u64 max_words;
+  u64 table_ptr;
+};
+constexpr u64 kPreparedMagic = 0x3159445f4c424154ull;  // "TABL_DY1"
+constexpr size_t kPreparedHeader = 256;
+
+// Is the caller's prepared table one that was made for this table, this tuning and at least
+// this many words?  (The host cannot look into device memory without a round trip.)
+__device__ __forceinline__ bool prepared_ok(const ScanParams& p) {
+  if (!p.prepared) return true;
+  const u64 magic = p.prepared[0], sizes = p.prepared[1], max_words = p.prepared[2], table = p.prepared[3];
+  return magic == kPreparedMagic && (u32)sizes == p.n_alloc && (u32)(sizes >> 32) == p.top_log2 &&
+         p.n_words <= max_words && table == (u64)(uintptr_t)p.table;
+}
+
+// The scan's counters live in memory that outlasts the call when the caller prepared the table
+// once (fdy_scan_table_prepare): then no launch zeroes them beforehand, and the last workgroup
+// to finish leaves them as it found them, zero.  Called by one wave per workgroup, the one that
+// wrote the workgroup's chunk states, after its last look-back: its state stores have been
+// acknowledged (they are write-through, agent scope) before it counts itself done, so nothing
+// of this launch can arrive after the reset.
+__device__ __forceinline__ void finish_and_reset(const ScanParams& p) {
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  u32 n = 0;
+  if (lane_id() == 0) n = __hip_atomic_fetch_add(p.done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  n = __shfl(n, 0);
+  if (n + 1 != gridDim.x) return;
+  for (u32 i = lane_id(); i < p.n_chunks; i += 64) st_state(&p.cstate[i], 0);
+  if (lane_id() == 0) {
+    __hip_atomic_store(p.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p.done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 
 // Level-0 keys are (base - span_lo) >> shift with the smallest shift that makes every key of
@@ -784,24 +830,29 @@ __device__ __forceinline__ void store_reloc(const ScanParams& p, u64 at, u32 wor
 // keeps): windows of queue size, searched one round at a time; the hits go to dst[0 ...) as
 // complete entries in word order (the wave's staging area: the output position is not known
 // yet).  Returns hits.
-// kOut: qw is the wave's LDS copy of this sub-tile; candidates are read from it through their
+// kStash: qw is the wave's LDS copy of this sub-tile; candidates are read from it through their
 // indices and a hit's word is replaced by its rebased value there.
-template <bool kHalf, bool kOut>
+// What becomes of the hits: kDenseStage - complete entries to dst[0 ...) (staging);
+// kDenseCount - nothing, they are only counted (no staging area: the group is searched again
+// when its position is known); kDenseWrite - that second search: entries to the relocation
+// table from position dst_pos on, within its capacity.
+enum { kDenseStage = 0, kDenseCount = 1, kDenseWrite = 2 };
+template <bool kHalf, bool kK16, bool kStash, int kMode>
 __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt& t, const void* top,
                           u64 span_lo, u32 shifts, u64* qw, unsigned short* qi, u64 wbase, fdy_reloc* dst,
-                          u32& marked) {
+                          u64 dst_pos, u32& marked) {
   const u32 lane = lane_id();
   const u64 lt = lanemask_lt();
   u64 H = 0;
   for (u32 win = 0; win < t.Q; win += kQcap) {
     const u32 wn = t.Q - win < (u32)kQcap ? t.Q - win : (u32)kQcap;
-    enqueue<kHalf, !kOut>(w, t, 0, win, wn, 0, qw, qi);
+    enqueue<kHalf, !kStash>(w, t, 0, win, wn, 0, qw, qi);
     for (u32 q0 = 0; q0 < wn; q0 += 64) {
       const u32 q = q0 + lane;
       const bool valid = q < wn;
-      const u64 wv[1] = {valid ? qw[kOut ? (u32)qi[q] : q] : span_lo};
+      const u64 wv[1] = {valid ? qw[kStash ? (u32)qi[q] : q] : span_lo};
       Found f[1];
-      search<1, kOut>(p, top, span_lo, shifts, wv, f, marked);
+      search<1, kK16>(p, top, span_lo, shifts, wv, f, marked);
       const bool hit = valid && f[0].hit;
       const u64 b = ballot(hit);
       if (hit) {
@@ -809,8 +860,10 @@ __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt&
         o.word = (u32)(wbase + qi[q]);
         o.region = f[0].region;
         o.offset = f[0].offset;
-        *reinterpret_cast<uint4*>(&dst[H + __popcll(b & lt)]) = *reinterpret_cast<const uint4*>(&o);
-        if constexpr (kOut) qw[qi[q]] = p.new_base[o.region] + o.offset;
+        if constexpr (kMode == kDenseStage)
+          *reinterpret_cast<uint4*>(&dst[H + __popcll(b & lt)]) = *reinterpret_cast<const uint4*>(&o);
+        if constexpr (kMode == kDenseWrite) store_reloc(p, dst_pos + H + __popcll(b & lt), o.word, o.region, o.offset);
+        if constexpr (kStash) qw[qi[q]] = p.new_base[o.region] + o.offset;
       }
       H += __popcll(b);
     }
@@ -895,9 +948,13 @@ __device__ __forceinline__ fdy_reloc* stage_of(const ScanParams& p, u32 b, int g
   return p.stage + ((u64)blockIdx.x * 2 + b) * (kUnits * kUnitWords) + (u64)(g * kWaves + wave) * kUnitWords;
 }
 
-template <int kGroups, int kG, bool kHalf>
+// A dense group without a staging area is searched a second time here, from the words in
+// memory (scratch: the wave's value queue qw, idle between rounds, and the group's own index
+// queue, which a dense group does not use).
+template <int kGroups, int kG, bool kHalf, bool kK16>
 __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResults<kGroups, kG>& r,
-                                            u64 chunk_excl, unsigned short* qi_all) {
+                                            u64 chunk_excl, unsigned short* qi_all, const void* top, u64 span_lo,
+                                            u64 span_len, u32 shifts, u64* qw, u32& marked) {
   constexpr int kGR = kG * kRegRounds;
   const u32 wave = threadIdx.x >> 6;
   const u64 lt = lanemask_lt();
@@ -915,6 +972,16 @@ __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResu
         if (hit)
           store_reloc(p, pos + __popcll(bl & lt), (u32)(wbase + qi[k * 64 + lane_id()]), r.reg[g][k], r.off[g][k]);
         pos += __popcll(bl);
+      }
+    } else if (!p.stage) {
+      u64 H = 0;
+      for (int row = 0; row < kG; ++row) {
+        u64 dw[kWpl];
+        Filt t;
+        load_words<kHalf>(p, first_sub + row, span_lo, dw);
+        filter_words<kHalf>(dw, t, span_lo, span_len);
+        H += dense_pass<kHalf, kK16, false, kDenseWrite>(p, dw, t, top, span_lo, shifts, qw, qi,
+                                                         (u64)(first_sub + row) * kSub, nullptr, pos + H, marked);
       }
     } else {
       // a dense group: its entries wait in the wave's staging area, complete and in word
@@ -964,6 +1031,10 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   unsigned short* qi_all = reinterpret_cast<unsigned short*>(qbase + (size_t)kWaves * kVwave * 8) +
                            wave * (2 * kGroups * kQwave);  // word indices: [round parity][group][slot]
   const bool closer = wave == kWaves - 1;  // one wave per workgroup speaks for the chunk
+  if (!prepared_ok(p)) {  // every workgroup sees the same: nothing is read or written
+    if (blockIdx.x == 0 && tid == 0) raise_status(p.d_status, FDY_ST_BAD_PREPARED);
+    return;
+  }
 
   // Chunks are drawn two rounds ahead, so that a round knows where the next one reads and can
   // have those loads in flight while it searches.  The first two draws are kept apart (the
@@ -1048,14 +1119,16 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       } else {
         // more candidates than the registers keep results for: the hits go to the wave's
         // staging area as complete entries and are copied to their place a round later
-        fdy_reloc* dst = stage_of<kGroups, kG>(p, b, g);
+        fdy_reloc* dst = p.stage ? stage_of<kGroups, kG>(p, b, g) : nullptr;
         for (int r = 0; r < kG; ++r) {
           u64 dw[kWpl];
           Filt t;
           load_words<kHalf>(p, first_sub + r, span_lo, dw);
           filter_words<kHalf>(dw, t, span_lo, span_len);
-          H += dense_pass<kHalf, kOut>(p, dw, t, top, span_lo, shifts, kOut ? qw + r * kSub : qw, qi,
-                                       (u64)(first_sub + r) * kSub, dst + H, marked);
+          u64* vals = kOut ? qw + r * kSub : qw;
+          const u64 wb = (u64)(first_sub + r) * kSub;
+          if (dst) H += dense_pass<kHalf, kOut, kOut, kDenseStage>(p, dw, t, top, span_lo, shifts, vals, qi, wb, dst + H, 0, marked);
+          else H += dense_pass<kHalf, kOut, kOut, kDenseCount>(p, dw, t, top, span_lo, shifts, vals, qi, wb, nullptr, 0, marked);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       }
@@ -1100,7 +1173,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       const u64 total = __shfl(cur.cnt_incl, 63);  // all lanes take part in the shuffle
       if (closer && lane == 0) st_state(&p.cstate[chunk], (chunk == 0 ? kFlagInc : kFlagAgg) | total);
     }
-    if (have_prev) write_round<kGroups, kG, kHalf>(p, prev, s_excl[b], qi_all);
+    if (have_prev) write_round<kGroups, kG, kHalf, kOut>(p, prev, s_excl[b], qi_all, top, span_lo, span_len, shifts, qw, marked);
     prev = cur;
     have_prev = true;
     base = nbase;
@@ -1125,8 +1198,9 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       }
     }
     __syncthreads();
-    write_round<kGroups, kG, kHalf>(p, prev, s_excl[db], qi_all);
+    write_round<kGroups, kG, kHalf, kOut>(p, prev, s_excl[db], qi_all, top, span_lo, span_len, shifts, qw, marked);
   }
+  if (p.self_clean && closer) finish_and_reset(p);
 }
 
 // ---- fused scan + rebase: out[j] = new_base[region] + offset for a hit, words[j] otherwise.
@@ -1200,6 +1274,10 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
   const u32 wave = tid >> 6;
   u64* qw = reinterpret_cast<u64*>(qbase) + wave * kQwave;
   unsigned short* qi = reinterpret_cast<unsigned short*>(qbase + (size_t)kWaves * kQwave * 8) + wave * kQwave;
+  if (!prepared_ok(p)) {  // every workgroup sees the same: nothing is read or written
+    if (blockIdx.x == 0 && tid == 0) raise_status(p.d_status, FDY_ST_BAD_PREPARED);
+    return;
+  }
   stage_level0(p, top, bst, n_bst);
   __syncthreads();
 
@@ -1276,18 +1354,36 @@ __global__ __launch_bounds__(kBlock) void scan_rebase_kernel(ScanParams p) {
         for (int k = 0; k < kWpl; ++k) w[r][k] = nw[r][k];
     }
   }
-  if (lane == 0 && H) atomicAdd(reinterpret_cast<unsigned long long*>(p.d_count), (unsigned long long)H);
+  // The count: every wave adds its hits to the accumulator in the scan's state; the last
+  // workgroup to finish publishes the sum and leaves the state zeroed for the next call.
+  __shared__ u32 s_last;
+  if (lane == 0 && H)
+    __hip_atomic_fetch_add(p.acc, H, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the addition has been performed
+  __syncthreads();
+  if (tid == 0) s_last = __hip_atomic_fetch_add(p.done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 == gridDim.x;
+  __syncthreads();
+  if (s_last && tid == 0) {
+    *p.d_count = __hip_atomic_load(p.acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p.acc, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p.done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 
 struct ScanInit {
   const fdy_alloc* table;
   u32 n_alloc;
-  u32* top;
+  u32 build;  // 0: only the state is cleared (the table's hierarchy exists already)
   u32 top_n;
   u32 sampled;  // level-0 keys that are real (the rest is padding)
+  // level 0 in its two forms: keys of 32 bits with up to 2^14 buckets, keys of 16 bits with up
+  // to 2^13 (see key_shift_for)
+  u32* top;
   unsigned short* bstart;
   u32 bucket_log2;
-  u32 key_bits;  // 31: keys of 32 bits; less: their low 16 bits only (see key_shift_for)
+  unsigned short* top16;
+  unsigned short* bstart16;
+  u32 bucket16_log2;
   u32 levels;
   u32 f0_log2;
   u64* mid[kMaxMid];
@@ -1297,38 +1393,63 @@ struct ScanInit {
   uint4* cleaf;    // compact table lines (as many), or null
   uint4* cmid;     // compact nodes of packed level 1, or null
   u32 cmid_nodes;  // ceil(n_alloc / 64) when built
-  u32 n_sub;
-  u64* cstate;
+  u64* cstate;   // state to clear (null: none)
   u32 n_chunks;
-  u32* ticket;
-  u64* d_count;
-  u32 zero_count;  // fused scan + rebase: the count is accumulated, so it starts at 0
+  u32* header;   // the 64 counters in front of the chunk states
+  u64* d_count;  // written 0 if not null (calls that find nothing to launch)
+  u64* prepared;  // a prepared table's first block: 32 words, the first four from hdr, the rest 0
+  PreparedHeader hdr;
 };
 
-// Builds the level-0 keys and the packed mid levels, clears the sub-tile states and ticket.
+// Builds the level-0 keys and the packed mid levels, clears the chunk states and counters.
 __global__ void scan_init_kernel(ScanInit a) {
   const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  if (a.cstate && i < a.n_chunks) a.cstate[i] = 0;
+  if (a.header && i < 64) a.header[i] = 0;
+  if (a.d_count && i == 0) *a.d_count = 0;
+  if (a.prepared && i < 32) {
+    const u64 h[4] = {a.hdr.magic, (u64)a.hdr.n_alloc | ((u64)a.hdr.top_log2 << 32), a.hdr.max_words, a.hdr.table_ptr};
+    a.prepared[i] = i < 4 ? h[i] : 0;
+  }
+  if (!a.build) return;
   const u64 span_lo = a.n_alloc ? a.table[0].base : 0;
   const u64 span_len =
       a.n_alloc ? a.table[a.n_alloc - 1].base + a.table[a.n_alloc - 1].size - span_lo : 1;
-  const u32 key_shift = key_shift_for(span_len, a.key_bits);
-  if (i < a.top_n) {
-    const u64 j = i << (3 * a.levels + a.f0_log2);
-    const u32 key = j < a.n_alloc ? (u32)((a.table[j].base - span_lo) >> key_shift) : 0xffffffffu;
-    if (a.key_bits == 31) a.top[i] = key;
-    else reinterpret_cast<unsigned short*>(a.top)[i] = (unsigned short)key;
-  }
-  if (i <= (1ull << a.bucket_log2)) {
-    // bucket i starts at key value i << shift: how many level-0 keys lie below it
-    const u64 target = i << bucket_shift_for(span_len, key_shift, a.bucket_log2);
-    const u32 sh = 3 * a.levels + a.f0_log2;
-    u32 lo = 0, hi = a.sampled;
-    while (lo < hi) {
-      const u32 mid = lo + ((hi - lo) >> 1);
-      if (((a.table[(u64)mid << sh].base - span_lo) >> key_shift) < target) lo = mid + 1;
-      else hi = mid;
+  const u32 sh0 = 3 * a.levels + a.f0_log2;
+  {
+    const u32 key_shift = key_shift_for(span_len, 31);
+    if (i < a.top_n) {
+      const u64 j = i << sh0;
+      a.top[i] = j < a.n_alloc ? (u32)((a.table[j].base - span_lo) >> key_shift) : 0xffffffffu;
     }
-    a.bstart[i] = (unsigned short)lo;
+    if (i <= (1ull << a.bucket_log2)) {
+      // bucket i starts at key value i << shift: how many level-0 keys lie below it
+      const u64 target = i << bucket_shift_for(span_len, key_shift, a.bucket_log2);
+      u32 lo = 0, hi = a.sampled;
+      while (lo < hi) {
+        const u32 mid = lo + ((hi - lo) >> 1);
+        if (((a.table[(u64)mid << sh0].base - span_lo) >> key_shift) < target) lo = mid + 1;
+        else hi = mid;
+      }
+      a.bstart[i] = (unsigned short)lo;
+    }
+  }
+  {
+    const u32 key_shift = key_shift_for(span_len, 16 + a.bucket16_log2);
+    if (i < a.top_n) {
+      const u64 j = i << sh0;
+      a.top16[i] = j < a.n_alloc ? (unsigned short)((a.table[j].base - span_lo) >> key_shift) : (unsigned short)0xffffu;
+    }
+    if (i <= (1ull << a.bucket16_log2)) {
+      const u64 target = i << bucket_shift_for(span_len, key_shift, a.bucket16_log2);
+      u32 lo = 0, hi = a.sampled;
+      while (lo < hi) {
+        const u32 mid = lo + ((hi - lo) >> 1);
+        if (((a.table[(u64)mid << sh0].base - span_lo) >> key_shift) < target) lo = mid + 1;
+        else hi = mid;
+      }
+      a.bstart16[i] = (unsigned short)lo;
+    }
   }
   for (u32 lv = 1; lv <= a.levels; ++lv) {
     if (i < a.mid_len[lv - 1]) {
@@ -1418,11 +1539,6 @@ __global__ void scan_init_kernel(ScanInit a) {
     a.cmid[i * 2] = make_uint4((u32)b0, (u32)(b0 >> 32), (u32)a1, (u32)(a1 >> 32));
     a.cmid[i * 2 + 1] = make_uint4((u32)a2, (u32)(a2 >> 32), (u32)a3, (u32)(a3 >> 32));
   }
-  if (i < a.n_chunks) a.cstate[i] = 0;
-  if (i == 0) {
-    *a.ticket = 0;
-    if (a.n_sub == 0 || a.n_alloc == 0 || a.zero_count) *a.d_count = 0;
-  }
 }
 
 // (a2) one wave per boundary: lower bound of word_off[s] among the reloc words.
@@ -1445,16 +1561,16 @@ u32 pow2_ceil(u32 v) {
 
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-struct ScanPlan {
-  u32 top_n, levels, f0_log2, n_sub, groups, g;
+// The search hierarchy of one table, as it lies in memory (a caller's prepared buffer or the
+// front of a workspace).  Offsets are relative to the block's start.
+struct TablePlan {
+  u32 top_n, levels, f0_log2, sampled, bucket_log2, bucket16_log2;
   u32 mid_len[kMaxMid];
-  u32 n_chunks, leaf_lines, cmid_nodes, sampled, bucket_log2, key_bits, stage_wgs;
-  size_t off_top, off_bst, off_mid[kMaxMid], off_leaf, off_cleaf, off_cmid, off_cstate, off_stage, total;
+  u32 leaf_lines, cmid_nodes;
+  size_t off_top, off_bst, off_top16, off_bst16, off_mid[kMaxMid], off_leaf, off_cleaf, off_cmid, bytes;
 };
 
-// k16: the level-0 keys take 16 bits each and the bucket index at most 2^13 buckets (the launch
-// needs the LDS for a copy of the words: the ordered scan with rebased output).
-bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl, bool k16 = false) {
+bool plan_table(u32 n_alloc, TablePlan* pl) {
   const u32 top_cap = 1u << fdy__tune_get(FDY_TUNE_SCAN_TOP_LOG2);
   // smallest sampling stride 2^f0_log2 * 8^levels (levels >= 2 unless the whole table fits)
   // for which the sampled bases fit the LDS level
@@ -1477,16 +1593,21 @@ bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl, bool k16 = false) {
   pl->top_n = pow2_ceil(sampled < 2 ? 2 : sampled);
   pl->levels = levels;
   pl->f0_log2 = f0_log2;
-  pl->n_sub = (u32)((n_words + kSub - 1) / kSub);
-  size_t off = 256;
+  pl->sampled = sampled;
+  size_t off = 0;
+  // level 0, 32-bit keys: one bucket per key, at most 2^14 (16-bit starts, 32 KiB of LDS)
   pl->off_top = off;
   off += align256((size_t)pl->top_n * 4);
-  pl->sampled = sampled;
-  pl->bucket_log2 = 0;  // one bucket per level-0 key, at most 2^14 (16-bit starts, 32 KiB of LDS)
-  while ((2u << pl->bucket_log2) <= pl->top_n && pl->bucket_log2 < (k16 ? 13u : 14u)) ++pl->bucket_log2;
-  pl->key_bits = k16 ? 16 + pl->bucket_log2 : 31;
+  pl->bucket_log2 = 0;
+  while ((2u << pl->bucket_log2) <= pl->top_n && pl->bucket_log2 < 14u) ++pl->bucket_log2;
   pl->off_bst = off;
   off += align256((((size_t)1 << pl->bucket_log2) + 1) * 2);
+  // level 0, 16-bit keys (launches that need the LDS for a copy of the words): at most 2^13 buckets
+  pl->off_top16 = off;
+  off += align256((size_t)pl->top_n * 2);
+  pl->bucket16_log2 = pl->bucket_log2 < 13u ? pl->bucket_log2 : 13u;
+  pl->off_bst16 = off;
+  off += align256((((size_t)1 << pl->bucket16_log2) + 1) * 2);
   for (int j = 0; j < kMaxMid; ++j) {
     pl->mid_len[j] = 0;
     pl->off_mid[j] = off;
@@ -1514,22 +1635,79 @@ bool make_plan(u64 n_words, u32 n_alloc, ScanPlan* pl, bool k16 = false) {
   off += align256((size_t)pl->leaf_lines * 32);
   pl->off_cmid = off;
   off += align256((size_t)pl->cmid_nodes * 32);
+  pl->bytes = off;
+  return true;
+}
+
+// What depends on the number of words: chunking, and the state that a launch counts in
+// (64 counters of 32 bits, then one state word per chunk; sized for the small chunks, which
+// are the more numerous).
+struct RunPlan {
+  u32 n_sub, groups, g, n_chunks, stage_wgs;
+  size_t stage_bytes;
+};
+
+constexpr size_t kStateHeader = 256;
+size_t state_bytes(u64 n_words) {
+  const u64 n_sub = (n_words + kSub - 1) / kSub;
+  const u64 small_chunk = (u64)kWaves * kGroupsSmall * kGSmall;
+  return kStateHeader + align256((size_t)((n_sub + small_chunk - 1) / small_chunk) * 8);
+}
+
+void plan_run(u64 n_words, RunPlan* rp) {
+  rp->n_sub = (u32)((n_words + kSub - 1) / kSub);
   // measured crossover: from 4,096 sub-tiles (2 Mi words) on the large chunks win even though
   // they leave compute units without a chunk; below, more and smaller chunks do
-  const bool small = pl->n_sub < (1u << fdy__tune_get(FDY_TUNE_SCAN_SMALL_LOG2));
-  pl->groups = small ? kGroupsSmall : kGroupsBig;
-  pl->g = small ? kGSmall : kGBig;
-  const u32 chunk = kWaves * pl->groups * pl->g;
-  pl->n_chunks = (pl->n_sub + chunk - 1) / chunk;
-  pl->off_cstate = off;
-  off += align256((size_t)pl->n_chunks * 8);
+  const bool small = rp->n_sub < (1u << fdy__tune_get(FDY_TUNE_SCAN_SMALL_LOG2));
+  rp->groups = small ? kGroupsSmall : kGroupsBig;
+  rp->g = small ? kGSmall : kGBig;
+  const u32 chunk = kWaves * rp->groups * rp->g;
+  rp->n_chunks = (rp->n_sub + chunk - 1) / chunk;
   // staging for the entries of dense groups: per workgroup two chunks' worth (the chunk being
   // searched and the one waiting for its position), one entry per word
-  pl->stage_wgs = pl->n_chunks < kStageWgs ? pl->n_chunks : kStageWgs;
-  pl->off_stage = off;
-  off += align256((size_t)pl->stage_wgs * 2 * chunk * kSub * sizeof(fdy_reloc));
-  pl->total = off;
-  return true;
+  rp->stage_wgs = rp->n_chunks < kStageWgs ? rp->n_chunks : kStageWgs;
+  rp->stage_bytes = align256((size_t)rp->stage_wgs * 2 * chunk * kSub * sizeof(fdy_reloc));
+}
+
+
+void fill_init(ScanInit* a, const fdy_alloc* d_table, u32 n_alloc, const TablePlan& tp, unsigned char* tb) {
+  a->table = d_table;
+  a->n_alloc = n_alloc;
+  a->build = 1;
+  a->top_n = tp.top_n;
+  a->sampled = tp.sampled;
+  a->top = (u32*)(tb + tp.off_top);
+  a->bstart = (unsigned short*)(tb + tp.off_bst);
+  a->bucket_log2 = tp.bucket_log2;
+  a->top16 = (unsigned short*)(tb + tp.off_top16);
+  a->bstart16 = (unsigned short*)(tb + tp.off_bst16);
+  a->bucket16_log2 = tp.bucket16_log2;
+  a->levels = tp.levels;
+  a->f0_log2 = tp.f0_log2;
+  for (int j = 0; j < kMaxMid; ++j) {
+    a->mid[j] = (u64*)(tb + tp.off_mid[j]);
+    a->mid_len[j] = tp.mid_len[j];
+  }
+  a->leaf = tp.leaf_lines ? (uint4*)(tb + tp.off_leaf) : nullptr;
+  a->leaf_lines = tp.leaf_lines;
+  a->cleaf = tp.leaf_lines ? (uint4*)(tb + tp.off_cleaf) : nullptr;
+  a->cmid = tp.cmid_nodes ? (uint4*)(tb + tp.off_cmid) : nullptr;
+  a->cmid_nodes = tp.cmid_nodes;
+  a->cstate = nullptr;
+  a->n_chunks = 0;
+  a->header = nullptr;
+  a->d_count = nullptr;
+  a->prepared = nullptr;
+  a->hdr = PreparedHeader{};
+}
+
+u32 init_threads(const TablePlan& tp, u32 n_chunks) {
+  u32 n = tp.top_n > n_chunks ? tp.top_n : n_chunks;
+  for (int j = 0; j < kMaxMid; ++j)
+    if (tp.mid_len[j] > n) n = tp.mid_len[j];
+  if (tp.leaf_lines > n) n = tp.leaf_lines;
+  if ((1u << tp.bucket_log2) + 1 > n) n = (1u << tp.bucket_log2) + 1;
+  return n < 64 ? 64 : n;
 }
 
 }  // namespace
@@ -1539,16 +1717,61 @@ using namespace fdy;
 
 extern "C" size_t fdy_scan_workspace_bytes(uint64_t n_words, uint32_t n_alloc) {
   if (n_words > kMaxWords) return 0;
-  ScanPlan pl;
-  if (!make_plan(n_words, n_alloc, &pl)) return 0;
-  return pl.total;
+  TablePlan tp;
+  if (!plan_table(n_alloc, &tp)) return 0;
+  return state_bytes(n_words) + tp.bytes;
 }
 
-// Shared by the scan and the fused scan + rebase (d_out != null): checks, workspace layout,
-// the init kernel, then the main kernel of either.
+extern "C" size_t fdy_scan_staging_bytes(uint64_t n_words) {
+  if (n_words > kMaxWords) return 0;
+  RunPlan rp;
+  plan_run(n_words, &rp);
+  return rp.stage_bytes;
+}
+
+extern "C" size_t fdy_scan_table_bytes(uint32_t n_alloc, uint64_t max_words) {
+  if (max_words > kMaxWords) return 0;
+  TablePlan tp;
+  if (!plan_table(n_alloc, &tp)) return 0;
+  return kPreparedHeader + state_bytes(max_words) + tp.bytes;
+}
+
+extern "C" int fdy_scan_table_prepare(const fdy_alloc* d_table, uint32_t n_alloc, uint64_t max_words,
+                                      void* d_prepared, size_t prepared_bytes, void* hip_stream) {
+  if (max_words > kMaxWords) return FDY_ERR_INVALID_ARG;
+  if (n_alloc && (!d_table || ((uintptr_t)d_table & 15))) return FDY_ERR_INVALID_ARG;
+  TablePlan tp;
+  if (!plan_table(n_alloc, &tp)) return FDY_ERR_INVALID_ARG;
+  const size_t need = kPreparedHeader + state_bytes(max_words) + tp.bytes;
+  if (!d_prepared || ((uintptr_t)d_prepared & 255) || prepared_bytes < need) return FDY_ERR_WORKSPACE;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+  unsigned char* pb = (unsigned char*)d_prepared;
+  ScanInit a;
+  fill_init(&a, d_table, n_alloc, tp, pb + kPreparedHeader);
+  a.prepared = (u64*)pb;
+  a.hdr.magic = kPreparedMagic;
+  a.hdr.n_alloc = n_alloc;
+  a.hdr.top_log2 = (u32)fdy__tune_get(FDY_TUNE_SCAN_TOP_LOG2);
+  a.hdr.max_words = max_words;
+  a.hdr.table_ptr = (u64)(uintptr_t)d_table;
+  a.header = (u32*)(pb + kPreparedHeader + tp.bytes);
+  a.cstate = (u64*)(pb + kPreparedHeader + tp.bytes + kStateHeader);
+  a.n_chunks = (u32)((state_bytes(max_words) - kStateHeader) / 8);
+  a.d_count = nullptr;
+  const u32 n_init = init_threads(tp, a.n_chunks);
+  prof_begin(FDY_PROF_SCAN_INIT, stream);
+  hipLaunchKernelGGL(scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream, a);
+  prof_end(FDY_PROF_SCAN_INIT, stream);
+  FDY_HIP_TRY(hipGetLastError());
+  return FDY_OK;
+}
+
+// Shared by the scans: checks, where hierarchy and state lie (in the caller's prepared table, or
+// built into the workspace by a launch of this call), then the main kernel.
 static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
                        uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity, uint64_t* d_count,
-                       const uint64_t* d_new_base, uint64_t* d_out, void* d_workspace,
+                       const uint64_t* d_new_base, uint64_t* d_out, const void* d_prepared, void* d_workspace,
                        size_t workspace_bytes, uint32_t* d_status, void* hip_stream, bool half = false,
                        bool ordered_out = false) {
   const bool fused = d_out != nullptr && !ordered_out;  // no relocation table, no ordering
@@ -1557,62 +1780,66 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   if (n_words && (!d_words || ((uintptr_t)d_words & 15))) return FDY_ERR_INVALID_ARG;
   if (n_alloc && (!d_table || ((uintptr_t)d_table & 15))) return FDY_ERR_INVALID_ARG;
   if (reloc_capacity && (!d_relocs || ((uintptr_t)d_relocs & 15))) return FDY_ERR_INVALID_ARG;
-  ScanPlan pl;
-  if (!make_plan(n_words, n_alloc, &pl, ordered_out)) return FDY_ERR_INVALID_ARG;
-  if (!d_workspace || ((uintptr_t)d_workspace & 255) || workspace_bytes < pl.total)
-    return FDY_ERR_WORKSPACE;
+  if (d_prepared && ((uintptr_t)d_prepared & 255)) return FDY_ERR_INVALID_ARG;
+  TablePlan tp;
+  if (!plan_table(n_alloc, &tp)) return FDY_ERR_INVALID_ARG;
+  RunPlan rp;
+  plan_run(n_words, &rp);
+  // where things lie
+  unsigned char* ws = (unsigned char*)d_workspace;
+  unsigned char *state, *tb, *stage;
+  if (d_prepared) {
+    // the caller vouches for the buffer (made by fdy_scan_table_prepare for this table and at
+    // least this many words, under the same tuning); only the staging comes from the workspace
+    unsigned char* pb = (unsigned char*)const_cast<void*>(d_prepared);
+    tb = pb + kPreparedHeader;
+    state = tb + tp.bytes;
+    if (ws && ((uintptr_t)ws & 255)) return FDY_ERR_WORKSPACE;
+    stage = ws && workspace_bytes >= rp.stage_bytes ? ws : nullptr;
+  } else {
+    const size_t need = state_bytes(n_words) + tp.bytes;
+    if (!ws || ((uintptr_t)ws & 255) || workspace_bytes < need) return FDY_ERR_WORKSPACE;
+    state = ws;
+    tb = ws + state_bytes(n_words);
+    stage = workspace_bytes >= need + rp.stage_bytes ? tb + tp.bytes : nullptr;
+  }
   hipStream_t stream = (hipStream_t)hip_stream;
   (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
-  unsigned char* ws = (unsigned char*)d_workspace;
   int dev = 0, n_cu = 256;
   FDY_HIP_TRY(hipGetDevice(&dev));
   FDY_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
   const u32 per_cu = (u32)fdy__tune_get(FDY_TUNE_SCAN_WG_PER_CU);
   u32 grid = (u32)n_cu * per_cu;  // persistent workgroups
-  if (grid > pl.n_chunks) grid = pl.n_chunks;
-  if (grid > pl.stage_wgs) grid = pl.stage_wgs;
+  if (grid > rp.n_chunks) grid = rp.n_chunks;
+  if (grid > rp.stage_wgs) grid = rp.stage_wgs;  // kStageWgs bounds every launch: the staging is sized for it
+  const bool nothing = rp.n_sub == 0 || n_alloc == 0;  // no word can be a pointer
   ScanInit a;
-  a.table = d_table;
-  a.n_alloc = n_alloc;
-  a.top = (u32*)(ws + pl.off_top);
-  a.top_n = pl.top_n;
-  a.sampled = pl.sampled;
-  a.bstart = (unsigned short*)(ws + pl.off_bst);
-  a.bucket_log2 = pl.bucket_log2;
-  a.key_bits = pl.key_bits;
-  a.levels = pl.levels;
-  a.f0_log2 = pl.f0_log2;
-  for (int j = 0; j < kMaxMid; ++j) {
-    a.mid[j] = (u64*)(ws + pl.off_mid[j]);
-    a.mid_len[j] = pl.mid_len[j];
+  fill_init(&a, d_table, n_alloc, tp, tb);
+  if (d_prepared) {
+    if (nothing) {  // only the count is owed
+      ScanInit z = ScanInit{};
+      z.d_count = (u64*)d_count;
+      hipLaunchKernelGGL(scan_init_kernel, dim3(1), dim3(64), 0, stream, z);
+      FDY_HIP_TRY(hipGetLastError());
+    }
+  } else {
+    a.header = (u32*)state;
+    a.cstate = (u64*)(state + kStateHeader);
+    a.n_chunks = rp.n_chunks;
+    a.d_count = nothing ? (u64*)d_count : nullptr;
+    const u32 n_init = init_threads(tp, rp.n_chunks);
+    prof_begin(FDY_PROF_SCAN_INIT, stream);
+    hipLaunchKernelGGL(scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream, a);
+    prof_end(FDY_PROF_SCAN_INIT, stream);
+    FDY_HIP_TRY(hipGetLastError());
   }
-  a.leaf = pl.leaf_lines ? (uint4*)(ws + pl.off_leaf) : nullptr;
-  a.leaf_lines = pl.leaf_lines;
-  a.cleaf = pl.leaf_lines ? (uint4*)(ws + pl.off_cleaf) : nullptr;
-  a.cmid = pl.cmid_nodes ? (uint4*)(ws + pl.off_cmid) : nullptr;
-  a.cmid_nodes = pl.cmid_nodes;
-  a.n_sub = pl.n_sub;
-  a.cstate = (u64*)(ws + pl.off_cstate);
-  a.n_chunks = pl.n_chunks;
-  a.ticket = (u32*)ws;
-  a.d_count = (u64*)d_count;
-  a.zero_count = fused ? 1u : 0u;
-  u32 n_init = pl.top_n > pl.n_chunks ? pl.top_n : pl.n_chunks;
-  for (int j = 0; j < kMaxMid; ++j)
-    if (pl.mid_len[j] > n_init) n_init = pl.mid_len[j];
-  if (pl.leaf_lines > n_init) n_init = pl.leaf_lines;
-  if ((1u << pl.bucket_log2) + 1 > n_init) n_init = (1u << pl.bucket_log2) + 1;
-  prof_begin(FDY_PROF_SCAN_INIT, stream);
-  hipLaunchKernelGGL(scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream, a);
-  prof_end(FDY_PROF_SCAN_INIT, stream);
-  FDY_HIP_TRY(hipGetLastError());
-  if (pl.n_sub == 0) return FDY_OK;
-  if (n_alloc == 0) {  // nothing can be a pointer; the fused form still owes the copy
+  if (rp.n_sub == 0) return FDY_OK;
+  if (n_alloc == 0) {  // nothing can be a pointer; forms with an output still owe the copy
     if (d_out && d_out != d_words)
       FDY_HIP_TRY(hipMemcpyAsync(d_out, d_words, n_words * 8, hipMemcpyDeviceToDevice, stream));
     return FDY_OK;
   }
-
+  
   ScanParams p;
   p.words = (const u64*)d_words;
   p.n_words = n_words;
@@ -1621,30 +1848,38 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   p.relocs = d_relocs;
   p.capacity = reloc_capacity;
   p.d_count = (u64*)d_count;
-  p.ticket = a.ticket;
-  p.top = a.top;
-  p.bstart = a.bstart;
-  p.bucket_log2 = a.bucket_log2;
+  // state: counter 0 = ticket, 1 = finished workgroups, 2..3 = hit accumulator (64 bits)
+  p.ticket = (u32*)state;
+  p.done = (u32*)state + 1;
+  p.acc = (u64*)state + 1;
+  p.cstate = (u64*)(state + kStateHeader);
+  p.n_chunks = rp.n_chunks;
+  p.self_clean = d_prepared ? 1u : 0u;
+  p.prepared = (const u64*)d_prepared;
+  p.top_log2 = (u32)fdy__tune_get(FDY_TUNE_SCAN_TOP_LOG2);
+  // level 0 in the form this launch stages in LDS
+  p.top = ordered_out ? (const u32*)a.top16 : a.top;
+  p.bstart = ordered_out ? a.bstart16 : a.bstart;
+  p.bucket_log2 = ordered_out ? a.bucket16_log2 : a.bucket_log2;
+  p.key_bits = ordered_out ? 16 + a.bucket16_log2 : 31;
   for (int j = 0; j < kMaxMid; ++j) p.mid[j] = a.mid[j];
   p.leaf = a.leaf;
   p.cmid = a.cmid;
   p.cleaf = a.cleaf;
-  p.cstate = a.cstate;
-  p.stage = (fdy_reloc*)(ws + pl.off_stage);
-  p.n_sub = pl.n_sub;
-  p.top_n = pl.top_n;
-  p.levels = pl.levels;
-  p.f0_log2 = pl.f0_log2;
+  p.stage = (fdy_reloc*)stage;
+  p.n_sub = rp.n_sub;
+  p.top_n = tp.top_n;
+  p.levels = tp.levels;
+  p.f0_log2 = tp.f0_log2;
   p.d_status = d_status;
   p.spin_limit = (u32)fdy__tune_get(FDY_TUNE_SCAN_SPIN_LIMIT);
   p.new_base = (const u64*)d_new_base;
   p.out = (u64*)d_out;
-  p.key_bits = pl.key_bits;
 
-  const size_t lds0 = level0_key_bytes(pl.top_n, ordered_out) + (((((size_t)1 << pl.bucket_log2) + 1) * 2 + 15) & ~(size_t)15);
+  const size_t lds0 = level0_key_bytes(tp.top_n, ordered_out) + (((((size_t)1 << p.bucket_log2) + 1) * 2 + 15) & ~(size_t)15);
   if (fused) {
     const size_t lds = lds0 + (size_t)kWaves * kFusedG * kQcap * 10;
-    const u32 n_groups = (pl.n_sub + kFusedG - 1) / kFusedG;
+    const u32 n_groups = (rp.n_sub + kFusedG - 1) / kFusedG;
     u32 fgrid = (u32)n_cu;  // one workgroup per compute unit (256 registers per lane)
     if (fgrid > (n_groups + kWaves - 1) / kWaves) fgrid = (n_groups + kWaves - 1) / kWaves;
     FDY_HIP_TRY(hipFuncSetAttribute((const void*)scan_rebase_kernel,
@@ -1657,9 +1892,9 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   }
   // per wave: the value queue (or, with a rebased output, the words of a group) and the
   // index queues of two chunks
-  const size_t lds = lds0 + (size_t)kWaves * pl.g * ((ordered_out ? (size_t)kSub : (size_t)kQcap) * 8 +
-                                                      (size_t)kQcap * 2 * 2 * pl.groups);
-  auto kern = pl.g == kGSmall ? (half          ? scan_kernel<kGroupsSmall, kGSmall, true, false>
+  const size_t lds = lds0 + (size_t)kWaves * rp.g * ((ordered_out ? (size_t)kSub : (size_t)kQcap) * 8 +
+                                                      (size_t)kQcap * 2 * 2 * rp.groups);
+  auto kern = rp.g == kGSmall ? (half          ? scan_kernel<kGroupsSmall, kGSmall, true, false>
                                  : ordered_out ? scan_kernel<kGroupsSmall, kGSmall, false, true>
                                                : scan_kernel<kGroupsSmall, kGSmall, false, false>)
                               : (half          ? scan_kernel<kGroupsBig, kGBig, true, false>
@@ -1676,33 +1911,36 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
 
 extern "C" int fdy_scan_pointers(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
                                  uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
-                                 uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
+                                 uint64_t* d_count, const void* d_prepared, void* d_workspace,
+                                 size_t workspace_bytes,
                                  uint32_t* d_status, void* hip_stream) {
   return scan_launch(d_words, n_words, d_table, n_alloc, d_relocs, reloc_capacity, d_count, nullptr, nullptr,
-                     d_workspace, workspace_bytes, d_status, hip_stream);
+                     d_prepared, d_workspace, workspace_bytes, d_status, hip_stream);
 }
 
 extern "C" int fdy_scan_pointers_stride4(const uint32_t* d_units, uint64_t n_units, const fdy_alloc* d_table,
                                          uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
-                                         uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
+                                         uint64_t* d_count, const void* d_prepared, void* d_workspace,
+                                 size_t workspace_bytes,
                                          uint32_t* d_status, void* hip_stream) {
   // position q pairs unit q with unit q + 1: one position less than units
   const uint64_t n_pos = n_units >= 2 ? n_units - 1 : 0;
   if (n_units && !d_units) return FDY_ERR_INVALID_ARG;
   return scan_launch(reinterpret_cast<const uint64_t*>(d_units), n_pos, d_table, n_alloc, d_relocs,
-                     reloc_capacity, d_count, nullptr, nullptr, d_workspace, workspace_bytes, d_status,
+                     reloc_capacity, d_count, nullptr, nullptr, d_prepared, d_workspace, workspace_bytes, d_status,
                      hip_stream, true);
 }
 
 extern "C" int fdy_scan_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
                                uint32_t n_alloc, const uint64_t* d_new_base, uint64_t* d_out_words,
-                               uint64_t* d_count, void* d_workspace, size_t workspace_bytes,
+                               uint64_t* d_count, const void* d_prepared, void* d_workspace,
+                                 size_t workspace_bytes,
                                uint32_t* d_status, void* hip_stream) {
   if (n_words && (!d_out_words || ((uintptr_t)d_out_words & 15))) return FDY_ERR_INVALID_ARG;
   if (n_alloc && (!d_new_base || ((uintptr_t)d_new_base & 7))) return FDY_ERR_INVALID_ARG;
   if (n_words == 0) {  // nothing to write; keep the count defined
     if (!d_count) return FDY_ERR_INVALID_ARG;
-    return scan_launch(d_words, 0, d_table, n_alloc, nullptr, 0, d_count, nullptr, nullptr, d_workspace,
+    return scan_launch(d_words, 0, d_table, n_alloc, nullptr, 0, d_count, nullptr, nullptr, d_prepared, d_workspace,
                        workspace_bytes, d_status, hip_stream);
   }
   if (d_out_words != d_words) {  // exactly the same array, or disjoint
@@ -1710,13 +1948,13 @@ extern "C" int fdy_scan_rebase(const uint64_t* d_words, uint64_t n_words, const 
     if (a < b + len && b < a + len) return FDY_ERR_INVALID_ARG;
   }
   return scan_launch(d_words, n_words, d_table, n_alloc, nullptr, 0, d_count, d_new_base, d_out_words,
-                     d_workspace, workspace_bytes, d_status, hip_stream);
+                     d_prepared, d_workspace, workspace_bytes, d_status, hip_stream);
 }
 
 extern "C" int fdy_scan_pointers_rebase(const uint64_t* d_words, uint64_t n_words, const fdy_alloc* d_table,
                                         uint32_t n_alloc, fdy_reloc* d_relocs, uint64_t reloc_capacity,
                                         uint64_t* d_count, const uint64_t* d_new_base, uint64_t* d_out_words,
-                                        void* d_workspace, size_t workspace_bytes, uint32_t* d_status,
+                                        const void* d_prepared, void* d_workspace, size_t workspace_bytes, uint32_t* d_status,
                                         void* hip_stream) {
   if (n_words && (!d_out_words || ((uintptr_t)d_out_words & 15))) return FDY_ERR_INVALID_ARG;
   if (n_alloc && (!d_new_base || ((uintptr_t)d_new_base & 7))) return FDY_ERR_INVALID_ARG;
@@ -1725,7 +1963,7 @@ extern "C" int fdy_scan_pointers_rebase(const uint64_t* d_words, uint64_t n_word
     if (a < b + len && b < a + len) return FDY_ERR_INVALID_ARG;
   }
   return scan_launch(d_words, n_words, d_table, n_alloc, d_relocs, reloc_capacity, d_count, d_new_base,
-                     n_words ? d_out_words : nullptr, d_workspace, workspace_bytes, d_status, hip_stream, false,
+                     n_words ? d_out_words : nullptr, d_prepared, d_workspace, workspace_bytes, d_status, hip_stream, false,
                      true);
 }
 

@@ -73,14 +73,30 @@ class Archive:
 # ------------------------------------------------------------------------------------
 # allocation tables and base maps
 # ------------------------------------------------------------------------------------
-def make_table(rng, n_alloc, size_lo, size_hi, base0=OLD_BASE0):
+def make_table(rng, n_alloc, size_lo, size_hi, base0=OLD_BASE0, kind="granule"):
     """Deterministic-layout style table: ascending from base0, 2 MiB aligned bases,
     sizes log-uniform in [size_lo, size_hi] rounded up to 512 B, and always a gap of at
     least 2 MiB - (size mod 2 MiB) > 0 bytes after each allocation, so that base-1 and
-    base+size lie in no allocation."""
+    base+size lie in no allocation.
+    kind "huge": the same with every 100th region 8 GiB (weights, KV cache).
+    kind "bytes": a caching allocator's blocks instead: byte-granular sizes, 16-byte aligned
+    bases, gaps of 16..1008 bytes."""
     size = np.exp(rng.uniform(np.log(size_lo), np.log(size_hi), n_alloc))
+    if kind == "bytes":
+        size = np.clip(size.astype(np.uint64), size_lo, size_hi).astype(np.uint64)
+        step = (size + U64(15)) // U64(16) * U64(16) + rng.integers(1, 64, n_alloc).astype(np.uint64) * U64(16)
+        base = np.empty(n_alloc, np.uint64)
+        base[0] = base0
+        if n_alloc > 1:
+            base[1:] = U64(base0) + np.cumsum(step[:-1], dtype=np.uint64)
+        t = np.empty(n_alloc, L.ALLOC)
+        t["base"] = base
+        t["size"] = size
+        return t
     size = (np.ceil(size / 512.0).astype(np.uint64) * U64(512)).astype(np.uint64)
     size = np.clip(size, size_lo, size_hi).astype(np.uint64)
+    if kind == "huge":
+        size[::100] = U64(8 << 30)
     k = rng.integers(0, 4, n_alloc).astype(np.uint64)
     aligned = (size + U64(ALIGN - 1)) // U64(ALIGN) * U64(ALIGN)
     k = np.where((aligned == size) & (k == 0), U64(1), k)  # never touch the next base
@@ -184,14 +200,16 @@ def _blob_lens(rng, kpl, mean_target=160.0):
 
 def make_model_archive(name, seed, layers, kpl, n_alloc, size_hi, batch_sizes, n_maps,
                        map_kind, comm_slots=(), n_ranks=0, size_lo=4096, p_ptr=0.25,
-                       p_decoy=0.05):
+                       p_decoy=0.05, bucket_edges=(8, 128)):
     rng = np.random.default_rng(seed)
     table = make_table(rng, n_alloc, size_lo, size_hi)
     G = len(batch_sizes)
     N = layers * kpl
-    # --- three topology buckets by batch size
+    # --- topology buckets by batch size (three by default: <= 8, <= 128, above)
+    edges = sorted(bucket_edges)
+
     def bucket(bs):
-        return 0 if bs <= 8 else (1 if bs <= 128 else 2)
+        return int(np.searchsorted(edges, bs, side="left"))
 
     bs_slots = (2 % kpl, (kpl // 2 + 1) % kpl)
     slot_kid = rng.integers(1, 1 << 63, kpl, dtype=np.uint64)
@@ -205,14 +223,14 @@ def make_model_archive(name, seed, layers, kpl, n_alloc, size_hi, batch_sizes, n
     for s in comm_slots:
         slot_flags[s] |= 1
     shapes = []
-    for b in range(3):
+    for b in range(len(edges) + 1):
         kid, ln = slot_kid.copy(), slot_len.copy()
         if b > 0:
             free = [s for s in range(kpl) if s not in comm_slots and s not in bs_slots]
             ch = rng.choice(free, size=min(3, len(free)), replace=False)
             kid[ch[:2]] = rng.integers(1, 1 << 63, len(ch[:2]), dtype=np.uint64)
             if len(ch) > 2:
-                ln[ch[2]] = int(np.clip(ln[ch[2]] + 8 * b, 16, 1024))
+                ln[ch[2]] = int(np.clip(ln[ch[2]] + 8 * min(b, 2), 16, 1024))
         shapes.append((kid, ln))
 
     # --- per-bucket base blob
@@ -365,9 +383,9 @@ def make_model_archive(name, seed, layers, kpl, n_alloc, size_hi, batch_sizes, n
 # flat archives (configs 1, 4): one graph
 # ------------------------------------------------------------------------------------
 def make_flat_archive(name, seed, n_alloc, size_hi, p_ptr, p_decoy, rest, n_nodes=0,
-                      n_words=0, map_kind="shift", size_lo=4096):
+                      n_words=0, map_kind="shift", size_lo=4096, table_kind="granule"):
     rng = np.random.default_rng(seed)
-    table = make_table(rng, n_alloc, size_lo, size_hi)
+    table = make_table(rng, n_alloc, size_lo, size_hi, kind=table_kind)
     if n_nodes:
         lens = rng.integers(1, 33, n_nodes).astype(np.int64) * 8  # 8..256 B
         nd = np.zeros(n_nodes, L.NODE)
@@ -409,7 +427,8 @@ CONFIG_NAMES = {1: "tiny", 2: "dense_decode", 3: "moe_decode", 4: "scan_stress",
 
 def make_config(idx, **kw):
     """Config 1..5 at full size; keyword overrides shrink it (same structure, same seed).
-    Recognised overrides: n_alloc, n_words (4), n_nodes (1), layers, batch_sizes, n_maps."""
+    Recognised overrides: n_alloc, n_words (4), n_nodes (1), layers, batch_sizes, n_maps,
+    bucket_edges (2: batch sizes up to which each topology bucket reaches), table_kind (4)."""
     seed = SEED0 + idx
     if idx == 1:
         return make_flat_archive("tiny", seed, kw.get("n_alloc", 256), 64 * MiB, 0.25, 0.05, "mix",
@@ -418,7 +437,8 @@ def make_config(idx, **kw):
         return make_model_archive("dense_decode", seed, kw.get("layers", 36), 16,
                                   kw.get("n_alloc", 4096), kw.get("size_hi", 1024 * MiB),
                                   kw.get("batch_sizes", default_batch_sizes()),
-                                  kw.get("n_maps", 1), "permute")
+                                  kw.get("n_maps", 1), "permute",
+                                  bucket_edges=kw.get("bucket_edges", (8, 128)))
     if idx == 3:
         return make_model_archive("moe_decode", seed, kw.get("layers", 94), 28,
                                   kw.get("n_alloc", 16384), 64 * MiB,
@@ -428,7 +448,7 @@ def make_config(idx, **kw):
     if idx == 4:
         return make_flat_archive("scan_stress", seed, kw.get("n_alloc", 1 << 20), 64 * MiB, 0.10,
                                  0.05, "rand64", n_words=kw.get("n_words", 1 << 27),
-                                 map_kind="region_shift")
+                                 map_kind="region_shift", table_kind=kw.get("table_kind", "granule"))
     if idx == 5:
         # same template set as config 2 (same seed => same table, graphs, overrides)
         return make_model_archive("fleet", SEED0 + 2, kw.get("layers", 36), 16,

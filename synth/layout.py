@@ -39,3 +39,4 @@ ST_BAD_INDEX = 0x2
 ST_BAD_SIZE = 0x4
 ST_SPIN = 0x8
 ST_BAD_ORDER = 0x10
+ST_BAD_PREPARED = 0x20

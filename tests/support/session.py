@@ -17,10 +17,15 @@ def _status_tensor():
     return torch.zeros(1, dtype=torch.int32, device=DEV)
 
 
+def _scan_ws_bytes(n_words, n_alloc, staging=True):
+    """Workspace of a scan: hierarchy and state, plus (staging) the optional staging area."""
+    return fdy.fdy_scan_workspace_bytes(n_words, n_alloc) + (fdy.fdy_scan_staging_bytes(n_words) if staging else 0)
+
+
 class ScanRun:
     """Device-resident inputs, outputs and workspace of one fdy_scan_pointers problem."""
 
-    def __init__(self, words, table, capacity=None):
+    def __init__(self, words, table, capacity=None, prepared=False, staging=True):
         self.n_words = int(len(words))
         self.n_alloc = int(len(table))
         self.capacity = self.n_words if capacity is None else int(capacity)
@@ -28,14 +33,24 @@ class ScanRun:
         self.d_table = table if torch.is_tensor(table) else fdy.to_device(table)
         self.d_relocs = fdy.device_bytes(self.capacity * 16)
         self.d_count = torch.zeros(1, dtype=torch.int64, device=DEV)
-        self.ws_bytes = fdy.fdy_scan_workspace_bytes(self.n_words, self.n_alloc)
+        self.ws_bytes = _scan_ws_bytes(self.n_words, self.n_alloc, staging)
         self.d_ws = fdy.device_bytes(self.ws_bytes)
         self.d_status = _status_tensor()
+        self.d_prepared = None
+        if prepared:
+            self.prepare(self.n_words)
+
+    def prepare(self, max_words):
+        """Builds the table's prepared form (fdy_scan_table_prepare); later launches pass it."""
+        self.prepared_bytes = fdy.fdy_scan_table_bytes(self.n_alloc, max_words)
+        self.d_prepared = fdy.device_bytes(self.prepared_bytes, fill=0xA7)
+        fdy.fdy_scan_table_prepare(self.d_table, self.n_alloc, max_words, self.d_prepared,
+                                   self.prepared_bytes)
 
     def launch(self, stream=None):
         return fdy.fdy_scan_pointers(self.d_words, self.n_words, self.d_table, self.n_alloc,
-                                     self.d_relocs, self.capacity, self.d_count, self.d_ws,
-                                     self.ws_bytes, self.d_status, stream)
+                                     self.d_relocs, self.capacity, self.d_count, self.d_prepared,
+                                     self.d_ws, self.ws_bytes, self.d_status, stream)
 
     def result(self):
         torch.cuda.synchronize()
@@ -45,8 +60,8 @@ class ScanRun:
         return relocs, count, status
 
 
-def scan(words, table, capacity=None):
-    run = ScanRun(words, table, capacity)
+def scan(words, table, capacity=None, prepared=False, staging=True):
+    run = ScanRun(words, table, capacity, prepared=prepared, staging=staging)
     run.launch()
     return run.result()
 
@@ -55,7 +70,7 @@ class ScanStride4Run(ScanRun):
     """fdy_scan_pointers_stride4: `units` is a uint32 array; capacity defaults to one entry per
     position."""
 
-    def __init__(self, units, table, capacity=None):
+    def __init__(self, units, table, capacity=None, prepared=False, staging=True):
         units = np.ascontiguousarray(units, np.uint32)
         self.n_units = int(len(units))
         self.n_alloc = int(len(table))
@@ -64,18 +79,21 @@ class ScanStride4Run(ScanRun):
         self.d_table = table if torch.is_tensor(table) else fdy.to_device(table)
         self.d_relocs = fdy.device_bytes(self.capacity * 16)
         self.d_count = torch.zeros(1, dtype=torch.int64, device=DEV)
-        self.ws_bytes = fdy.fdy_scan_workspace_bytes(self.n_units, self.n_alloc)
+        self.ws_bytes = _scan_ws_bytes(self.n_units, self.n_alloc, staging)
         self.d_ws = fdy.device_bytes(self.ws_bytes)
         self.d_status = _status_tensor()
+        self.d_prepared = None
+        if prepared:
+            self.prepare(self.n_units)
 
     def launch(self, stream=None):
         return fdy.fdy_scan_pointers_stride4(self.d_words, self.n_units, self.d_table, self.n_alloc,
-                                             self.d_relocs, self.capacity, self.d_count, self.d_ws,
-                                             self.ws_bytes, self.d_status, stream)
+                                             self.d_relocs, self.capacity, self.d_count, self.d_prepared,
+                                             self.d_ws, self.ws_bytes, self.d_status, stream)
 
 
-def scan_stride4(units, table, capacity=None):
-    run = ScanStride4Run(units, table, capacity)
+def scan_stride4(units, table, capacity=None, prepared=False, staging=True):
+    run = ScanStride4Run(units, table, capacity, prepared=prepared, staging=staging)
     run.launch()
     return run.result()
 
@@ -83,7 +101,7 @@ def scan_stride4(units, table, capacity=None):
 class ScanRebaseRun:
     """Device-resident inputs, output and workspace of one fdy_scan_rebase problem."""
 
-    def __init__(self, words, table, new_base, in_place=False, n_words=None, n_alloc=None):
+    def __init__(self, words, table, new_base, in_place=False, n_words=None, n_alloc=None, prepared=False):
         # n_words / n_alloc: record counts when words / table are device byte tensors
         self.n_words = int(len(words) if n_words is None else n_words)
         self.n_alloc = int(len(table) if n_alloc is None else n_alloc)
@@ -93,13 +111,16 @@ class ScanRebaseRun:
             np.ascontiguousarray(new_base, np.uint64))
         self.d_out = self.d_words if in_place else fdy.device_bytes(self.n_words * 8, fill=0xEE)
         self.d_count = torch.full((1,), -1, dtype=torch.int64, device=DEV)
-        self.ws_bytes = fdy.fdy_scan_workspace_bytes(self.n_words, self.n_alloc)
+        self.ws_bytes = _scan_ws_bytes(self.n_words, self.n_alloc, True)
         self.d_ws = fdy.device_bytes(self.ws_bytes)
         self.d_status = _status_tensor()
+        self.d_prepared = None
+        if prepared:
+            ScanRun.prepare(self, self.n_words)
 
     def launch(self, stream=None):
         return fdy.fdy_scan_rebase(self.d_words, self.n_words, self.d_table, self.n_alloc,
-                                   self.d_new_base, self.d_out, self.d_count, self.d_ws,
+                                   self.d_new_base, self.d_out, self.d_count, self.d_prepared, self.d_ws,
                                    self.ws_bytes, self.d_status, stream)
 
     def result(self):
@@ -111,8 +132,8 @@ class ScanRebaseRun:
 class ScanPointersRebaseRun(ScanRun):
     """fdy_scan_pointers_rebase: the relocation table and the rebased copy of the words."""
 
-    def __init__(self, words, table, new_base, capacity=None):
-        super().__init__(words, table, capacity)
+    def __init__(self, words, table, new_base, capacity=None, prepared=False, staging=True):
+        super().__init__(words, table, capacity, prepared=prepared, staging=staging)
         self.d_new_base = new_base if torch.is_tensor(new_base) else fdy.to_device(
             np.ascontiguousarray(new_base, np.uint64))
         self.d_out = fdy.device_bytes(self.n_words * 8, fill=0xEE)
@@ -120,21 +141,22 @@ class ScanPointersRebaseRun(ScanRun):
     def launch(self, stream=None):
         return fdy.fdy_scan_pointers_rebase(self.d_words, self.n_words, self.d_table, self.n_alloc,
                                             self.d_relocs, self.capacity, self.d_count, self.d_new_base,
-                                            self.d_out, self.d_ws, self.ws_bytes, self.d_status, stream)
+                                            self.d_out, self.d_prepared, self.d_ws, self.ws_bytes,
+                                            self.d_status, stream)
 
     def result(self):
         relocs, count, status = super().result()
         return relocs, count, status, fdy.to_host(self.d_out, np.uint64, self.n_words)
 
 
-def scan_pointers_rebase(words, table, new_base, capacity=None):
-    run = ScanPointersRebaseRun(words, table, new_base, capacity)
+def scan_pointers_rebase(words, table, new_base, capacity=None, prepared=False, staging=True):
+    run = ScanPointersRebaseRun(words, table, new_base, capacity, prepared=prepared, staging=staging)
     run.launch()
     return run.result()
 
 
-def scan_rebase(words, table, new_base, in_place=False):
-    run = ScanRebaseRun(words, table, new_base, in_place)
+def scan_rebase(words, table, new_base, in_place=False, prepared=False):
+    run = ScanRebaseRun(words, table, new_base, in_place, prepared=prepared)
     run.launch()
     return run.result()
 
@@ -155,7 +177,10 @@ def fingerprint(nodes, node_off, mask, want_tmpl_graph=True):
     d_tid = fdy.device_bytes(G * 4, fill=0xEE)
     d_tg = fdy.device_bytes(G * 4, fill=0xEE) if want_tmpl_graph else None
     d_nt = torch.full((1,), -1, dtype=torch.int32, device=DEV)
-    fdy.fdy_fingerprint(d_nodes, d_off, G, mask, d_keys, d_tid, d_tg, d_nt)
+    ws_bytes = fdy.fdy_fingerprint_workspace_bytes(G)
+    d_ws = fdy.device_bytes(ws_bytes, fill=0x3C)
+    fdy.fdy_fingerprint(d_nodes, d_off, G, mask, d_keys, d_tid, d_tg, d_nt, d_workspace=d_ws,
+                        workspace_bytes=ws_bytes)
     torch.cuda.synchronize()
     nt = int(d_nt.item())
     keys = fdy.to_host(d_keys, np.uint64, G)
@@ -238,11 +263,13 @@ class PathRun:
     `ar` is a synth.Archive; `reloc_capacity` bounds the relocation table (host knowledge:
     at most one entry per word)."""
 
-    def __init__(self, ar, reloc_capacity=None, want_dims=True, maps=None, one_pass=None):
+    def __init__(self, ar, reloc_capacity=None, want_dims=True, maps=None, one_pass=None, prepared=True):
         """one_pass: the scan itself writes the materialized output (fdy_scan_pointers_rebase) and
         fdy_materialize is not called.  That is the whole of (c) when every graph is its own
         template and there is one base map and nothing to override or patch; None = use it
-        exactly then."""
+        exactly then.  prepared: the allocation table's search hierarchy is built once, here
+        (fdy_scan_table_prepare), not by every step; relocation segmentation and fingerprint
+        are then one launch (fdy_segment_fingerprint)."""
         from synth import MatProblem
 
         self.ar = ar
@@ -255,10 +282,11 @@ class PathRun:
                    and len(ar.patch) == 0 and len(ar.nodes) == 0)
         self.one_pass = can if one_pass is None else bool(one_pass)
         assert can or not self.one_pass
+        self.prepared = bool(prepared)
         if self.one_pass:
-            self.scan = ScanPointersRebaseRun(ar.words, ar.table, ar.new_base[0], cap)
+            self.scan = ScanPointersRebaseRun(ar.words, ar.table, ar.new_base[0], cap, prepared=prepared)
         else:
-            self.scan = ScanRun(ar.words, ar.table, cap)
+            self.scan = ScanRun(ar.words, ar.table, cap, prepared=prepared)
         self.d_word_off = fdy.to_device(ar.word_off)
         self.d_reloc_off = fdy.device_bytes((G + 1) * 8, fill=0xEE)
         self.d_nodes = fdy.to_device(ar.nodes)
@@ -279,10 +307,16 @@ class PathRun:
     def step(self, stream=None):
         ar = self.ar
         self.scan.launch(stream)
-        fdy.fdy_reloc_segment(self.scan.d_relocs, self.scan.d_count, self.scan.capacity,
-                              self.d_word_off, self.G + 1, self.d_reloc_off, stream)
-        fdy.fdy_fingerprint(self.d_nodes, self.d_node_off, self.G, ar.fp_mask, self.d_keys,
-                            self.d_tid, self.d_tg, self.d_nt, stream)
+        if self.prepared:
+            fdy.fdy_segment_fingerprint(self.scan.d_relocs, self.scan.d_count, self.scan.capacity,
+                                        self.d_word_off, self.d_reloc_off, self.d_nodes, self.d_node_off,
+                                        self.G, ar.fp_mask, self.d_keys, self.d_tid, self.d_tg, self.d_nt,
+                                        d_prepared=self.scan.d_prepared, stream=stream)
+        else:
+            fdy.fdy_reloc_segment(self.scan.d_relocs, self.scan.d_count, self.scan.capacity,
+                                  self.d_word_off, self.G + 1, self.d_reloc_off, stream)
+            fdy.fdy_fingerprint(self.d_nodes, self.d_node_off, self.G, ar.fp_mask, self.d_keys,
+                                self.d_tid, self.d_tg, self.d_nt, stream)
         if not self.one_pass:
             self.mat.launch(stream)
 

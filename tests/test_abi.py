@@ -87,11 +87,17 @@ def test_table_validate_agrees_with_oracle(fdy, oracle):
 def test_workspace_sizes(fdy):
     assert fdy.fdy_scan_workspace_bytes(0, 0) >= 256
     a = fdy.fdy_scan_workspace_bytes(1 << 27, 1 << 20)
-    # table hierarchy (about 14 MiB for 2^20 allocations) + staging for dense groups, which is
-    # bounded by the workgroups in flight (160 MiB), not by the input
-    assert 0 < a < 192 << 20 and a % 256 == 0
-    assert fdy.fdy_scan_workspace_bytes(1 << 31, 1 << 20) - a < 1 << 20  # 16 times the words: chunk states only
-    assert fdy.fdy_scan_workspace_bytes(1 << 17, 256) < 8 << 20  # small inputs: small staging
+    # table hierarchy (about 14 MiB for 2^20 allocations) and chunk states; the staging area of
+    # dense inputs is optional, queried apart, and bounded by the workgroups in flight (160 MiB)
+    assert 0 < a < 32 << 20 and a % 256 == 0
+    assert 0 < fdy.fdy_scan_staging_bytes(1 << 27) <= 160 << 20
+    assert fdy.fdy_scan_staging_bytes(1 << 31) == fdy.fdy_scan_staging_bytes(1 << 27)
+    assert fdy.fdy_scan_workspace_bytes(1 << 31, 1 << 20) - a < 8 << 20  # 16 times the words: chunk states only
+    assert fdy.fdy_scan_workspace_bytes(1 << 17, 256) + fdy.fdy_scan_staging_bytes(1 << 17) < 8 << 20
+    t = fdy.fdy_scan_table_bytes(1 << 20, 1 << 27)
+    assert 0 < t < 32 << 20 and t % 256 == 0 and fdy.fdy_scan_table_bytes(16, 1 << 32) == 0
+    assert fdy.fdy_fingerprint_workspace_bytes(67) == 256 and fdy.fdy_fingerprint_workspace_bytes((1 << 20) + 1) == 0
+    assert fdy.fdy_fingerprint_workspace_bytes(1 << 20) == 8 << 20
     assert fdy.fdy_scan_workspace_bytes(1 << 32, 16) == 0  # word index must fit 32 bits
     d = fdy.fdy_mat_desc()
     d.n_graphs, d.n_maps, d.out_words_per_map = 67, 256, 761364
@@ -103,9 +109,9 @@ def test_workspace_sizes(fdy):
 
 def test_argument_checks_that_need_no_gpu(fdy):
     # all of these return before any HIP call is made
-    assert fdy.lib().fdy_scan_pointers(None, 8, None, 0, None, 0, None, None, 0, None, None) == fdy.FDY_ERR_INVALID_ARG
-    assert fdy.lib().fdy_fingerprint(None, None, 70000, L.FP_ALL, None, None, None, None, None) == fdy.FDY_ERR_INVALID_ARG
-    assert fdy.lib().fdy_fingerprint(None, None, 1, 0x80, None, None, None, None, None) == fdy.FDY_ERR_INVALID_ARG
+    assert fdy.lib().fdy_scan_pointers(None, 8, None, 0, None, 0, None, None, None, 0, None, None) == fdy.FDY_ERR_INVALID_ARG
+    assert fdy.lib().fdy_fingerprint(None, None, (1 << 20) + 1, L.FP_ALL, None, None, None, None, None, 0, None) == fdy.FDY_ERR_INVALID_ARG
+    assert fdy.lib().fdy_fingerprint(None, None, 1, 0x80, None, None, None, None, None, 0, None) == fdy.FDY_ERR_INVALID_ARG
     d = fdy.fdy_mat_desc()
     d.n_graphs, d.n_maps = 1, 1
     assert fdy.lib().fdy_materialize(C.byref(d), None, None, None, 0, None, None) == fdy.FDY_ERR_INVALID_ARG

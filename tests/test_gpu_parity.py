@@ -33,15 +33,20 @@ def say(msg):
     print(msg, flush=True)
 
 
+MODES = ((False, True), (True, True), (False, False), (True, False))  # (prepared table, staging area)
+
+
 # ------------------------------------------------------------------------------------ scan
 def check_scan(hip, oracle, words, table, capacity=None, tag=""):
     say(f"[scan] {tag} W={len(words)} A={len(table)} cap={capacity}")
     ref, rcnt = oracle.scan(words, table, capacity)
-    got, cnt, status = hip.scan(words, table, capacity)
-    assert cnt == rcnt
-    assert np.array_equal(got, ref)
     cap = len(words) if capacity is None else capacity
-    assert status == (L.ST_CAPACITY if rcnt > cap else 0)
+    # hierarchy built by the call / by fdy_scan_table_prepare; dense groups staged / searched twice
+    for prepared, staging in MODES:
+        got, cnt, status = hip.scan(words, table, capacity, prepared=prepared, staging=staging)
+        assert cnt == rcnt
+        assert np.array_equal(got, ref)
+        assert status == (L.ST_CAPACITY if rcnt > cap else 0)
     return got
 
 
@@ -164,6 +169,64 @@ def test_scan_large_input_dense_groups_and_wide_lines(hip, oracle):
     assert len(got) > 1_000_000
 
 
+def test_prepared_table_is_reused_and_checked(hip, oracle):
+    """One prepared table serves calls of every scan entry point one after the other (each call
+    must leave the counters it used zeroed), for inputs of different sizes, including inputs of
+    no words; a table prepared for something else is refused on the device."""
+    import paper_2604_06664_amd as fdy
+    import torch
+
+    ar = small(4)  # 65,536 allocations, 2^20 words
+    nb = ar.new_base[0]
+    base = hip.ScanPointersRebaseRun(ar.words, ar.table, nb, prepared=True)
+    sizes = [len(ar.words), 70001, 0, 16384, 5000, 1 << 19]
+    for rep in range(2):
+        for n in sizes:
+            say(f"[prepared] rep {rep} n={n}")
+            ref, rcnt = oracle.scan(ar.words[:n], ar.table)
+            want = oracle_rebase(oracle, ar.words[:n], ar.table, nb)[0] if n else np.zeros(0, np.uint64)
+            for kind in ("scan", "out", "rebase"):
+                base.n_words = n
+                base.d_count.fill_(-1)
+                base.d_status.zero_()
+                base.d_out.fill_(0xEE)
+                base.d_relocs.fill_(0xEE)
+                if kind == "scan":
+                    fdy.fdy_scan_pointers(base.d_words, n, base.d_table, base.n_alloc, base.d_relocs,
+                                          base.capacity, base.d_count, base.d_prepared, base.d_ws,
+                                          base.ws_bytes, base.d_status)
+                elif kind == "out":
+                    base.launch()
+                else:
+                    fdy.fdy_scan_rebase(base.d_words, n, base.d_table, base.n_alloc, base.d_new_base,
+                                        base.d_out, base.d_count, base.d_prepared, base.d_ws, base.ws_bytes,
+                                        base.d_status)
+                torch.cuda.synchronize()
+                assert int(base.d_status.item()) == 0 and int(base.d_count.item()) == rcnt, kind
+                if kind != "rebase":
+                    assert np.array_equal(fdy.to_host(base.d_relocs, hip.RELOC, rcnt), ref), kind
+                if kind != "scan":
+                    assert np.array_equal(fdy.to_host(base.d_out, np.uint64, n), want), kind
+    # the counters are zero again (header of the state: 64 counters behind the hierarchy)
+    # refused: more words than prepared for, another table address, another table size
+    other = fdy.to_device(ar.table)
+    for words, table, n_alloc in ((len(ar.words) + 1, base.d_table, base.n_alloc),
+                                  (1000, other, base.n_alloc), (1000, base.d_table, base.n_alloc - 8)):
+        base.d_status.zero_()
+        base.d_relocs.fill_(0xEE)
+        big = fdy.device_bytes((len(ar.words) + 1) * 8)
+        fdy.fdy_scan_pointers(big, words, table, n_alloc, base.d_relocs, base.capacity, base.d_count,
+                              base.d_prepared, base.d_ws, base.ws_bytes, base.d_status)
+        torch.cuda.synchronize()
+        assert int(base.d_status.item()) == L.ST_BAD_PREPARED
+        assert bool((base.d_relocs[:4096] == 0xEE).all())
+    # and still good afterwards
+    got, cnt, status, out = (base.__setattr__("n_words", len(ar.words)), base.d_status.zero_(), base.launch(),
+                             base.result())[-1]
+    ref, rcnt = oracle.scan(ar.words, ar.table)
+    assert status == 0 and cnt == rcnt and np.array_equal(got, ref)
+
+
 def test_scan_bounded_wait_is_reported_not_hung(hip):
     """Host-forced error path: with a spin limit of 0 a workgroup that finds its predecessor
     unfinished gives up at once, raises FDY_ST_SPIN and still terminates."""
@@ -187,14 +250,15 @@ def test_scan_argument_errors(hip):
     ar = small(1)
     run = hip.ScanRun(ar.words, ar.table)
     bad = fdy.fdy_scan_pointers(run.d_words.data_ptr() + 8, run.n_words - 1, run.d_table, run.n_alloc,
-                                run.d_relocs, run.capacity, run.d_count, run.d_ws, run.ws_bytes,
+                                run.d_relocs, run.capacity, run.d_count, None, run.d_ws, run.ws_bytes,
                                 run.d_status, check=False)
     assert bad == fdy.FDY_ERR_INVALID_ARG
     assert fdy.fdy_scan_pointers(run.d_words, run.n_words, run.d_table, run.n_alloc, run.d_relocs,
-                                 run.capacity, run.d_count, run.d_ws, run.ws_bytes - 1, run.d_status,
+                                 run.capacity, run.d_count, None, run.d_ws,
+                                 fdy.fdy_scan_workspace_bytes(run.n_words, run.n_alloc) - 1, run.d_status,
                                  check=False) == fdy.FDY_ERR_WORKSPACE
     assert fdy.fdy_scan_pointers(run.d_words, 1 << 32, run.d_table, run.n_alloc, run.d_relocs,
-                                 run.capacity, run.d_count, run.d_ws, run.ws_bytes, run.d_status,
+                                 run.capacity, run.d_count, None, run.d_ws, run.ws_bytes, run.d_status,
                                  check=False) == fdy.FDY_ERR_INVALID_ARG
     torch.cuda.synchronize()
 
@@ -261,11 +325,12 @@ def check_scan4(hip, oracle, units, table, capacity=None, tag=""):
     units = np.ascontiguousarray(units, np.uint32)
     say(f"[scan stride 4] {tag} units={len(units)} A={len(table)} cap={capacity}")
     ref, rcnt = oracle.scan_stride4(units, table, capacity)
-    got, cnt, status = hip.scan_stride4(units, table, capacity)
-    assert cnt == rcnt
-    assert np.array_equal(got, ref)
     cap = max(len(units) - 1, 0) if capacity is None else capacity
-    assert status == (L.ST_CAPACITY if rcnt > cap else 0)
+    for prepared, staging in MODES:
+        got, cnt, status = hip.scan_stride4(units, table, capacity, prepared=prepared, staging=staging)
+        assert cnt == rcnt
+        assert np.array_equal(got, ref)
+        assert status == (L.ST_CAPACITY if rcnt > cap else 0)
     return got
 
 
@@ -323,7 +388,7 @@ def test_scan_stride4_edge_cases(hip, oracle):
     # misaligned array refused on the host
     run = hip.ScanStride4Run(u, t)
     rc = fdy.fdy_scan_pointers_stride4(run.d_words.data_ptr() + 4, 100, run.d_table, 2, run.d_relocs, 10,
-                                       run.d_count, run.d_ws, run.ws_bytes, run.d_status, check=False)
+                                       run.d_count, None, run.d_ws, run.ws_bytes, run.d_status, check=False)
     assert rc == fdy.FDY_ERR_INVALID_ARG
 
 
@@ -356,9 +421,10 @@ def oracle_rebase(oracle, words, table, new_base):
 def check_rebase(hip, oracle, words, table, new_base, tag="", in_place=False):
     say(f"[scan_rebase] {tag} W={len(words)} A={len(table)} in_place={in_place}")
     ref, rcnt = oracle_rebase(oracle, words, table, new_base) if len(words) else (np.zeros(0, np.uint64), 0)
-    got, cnt, status = hip.scan_rebase(words, table, new_base, in_place=in_place)
-    assert cnt == rcnt and status == 0
-    assert np.array_equal(got, ref)
+    for prepared in (False, True):
+        got, cnt, status = hip.scan_rebase(words, table, new_base, in_place=in_place, prepared=prepared)
+        assert cnt == rcnt and status == 0
+        assert np.array_equal(got, ref)
 
 
 @pytest.mark.parametrize("idx", [1, 2, 3, 4])
@@ -402,7 +468,7 @@ def test_scan_rebase_edge_cases(hip, oracle):
     # overlapping, non-identical input and output ranges are refused on the host
     run = hip.ScanRebaseRun(ar.words[:4096], ar.table, nb)
     rc = fdy.fdy_scan_rebase(run.d_words, 2048, run.d_table, run.n_alloc, run.d_new_base,
-                             run.d_words.data_ptr() + 1024 * 8, run.d_count, run.d_ws, run.ws_bytes,
+                             run.d_words.data_ptr() + 1024 * 8, run.d_count, None, run.d_ws, run.ws_bytes,
                              run.d_status, check=False)
     assert rc == fdy.FDY_ERR_INVALID_ARG
 
@@ -443,12 +509,14 @@ def check_scan_out(hip, oracle, words, table, new_base, capacity=None, tag=""):
     say(f"[scan_pointers_rebase] {tag} W={len(words)} A={len(table)} cap={capacity}")
     ref, rcnt = oracle.scan(words, table, capacity)
     want, _ = oracle_rebase(oracle, words, table, new_base) if len(words) else (np.zeros(0, np.uint64), 0)
-    got, cnt, status, out = hip.scan_pointers_rebase(words, table, new_base, capacity)
-    assert cnt == rcnt
-    assert np.array_equal(got, ref)
     cap = len(words) if capacity is None else capacity
-    assert status == (L.ST_CAPACITY if rcnt > cap else 0)
-    assert np.array_equal(out, want)
+    for prepared, staging in MODES:
+        got, cnt, status, out = hip.scan_pointers_rebase(words, table, new_base, capacity, prepared=prepared,
+                                                         staging=staging)
+        assert cnt == rcnt
+        assert np.array_equal(got, ref)
+        assert status == (L.ST_CAPACITY if rcnt > cap else 0)
+        assert np.array_equal(out, want)
 
 
 @pytest.mark.parametrize("idx", [1, 2, 3, 4])
@@ -487,7 +555,7 @@ def test_scan_pointers_rebase_edge_cases(hip, oracle):
     run = hip.ScanPointersRebaseRun(ar.words[:4096], ar.table, nb)
     for out in (run.d_words.data_ptr(), run.d_words.data_ptr() + 1024 * 8):
         rc = fdy.fdy_scan_pointers_rebase(run.d_words, 2048, run.d_table, run.n_alloc, run.d_relocs,
-                                          run.capacity, run.d_count, run.d_new_base, out, run.d_ws,
+                                          run.capacity, run.d_count, run.d_new_base, out, None, run.d_ws,
                                           run.ws_bytes, run.d_status, check=False)
         assert rc == fdy.FDY_ERR_INVALID_ARG
 
@@ -544,6 +612,69 @@ def test_fingerprint_edge_cases(hip, oracle):
     assert np.array_equal(gk, keys) and np.array_equal(gt, tid) and gg is None
     _, _, gg, _ = hip.fingerprint(nd, off, L.FP_ALL)
     assert np.array_equal(gg, tg)
+
+
+def test_fingerprint_many_graphs_and_templates(hip, oracle):
+    """The shape of Section 6.4.1: 512 graphs (batch sizes 1..512) in 22 topology groups; then
+    sizes around and beyond what the grouping table in LDS holds (8,192 graphs; beyond it the
+    table lies in the workspace), with every graph distinct, with few distinct ones, and with
+    templates first met late."""
+    edges = [1, 2, 4, 8, 16, 24, 32, 48, 64, 96, 128, 160, 192, 224, 256, 288, 320, 352, 384, 416, 448]
+    ar = make_config(2, layers=4, batch_sizes=list(range(1, 513)), bucket_edges=edges)
+    assert ar.n_graphs == 512 and ar.n_templates == 22
+    keys, tid, tg = oracle.fingerprint(ar.nodes, ar.node_off, ar.fp_mask)
+    assert np.array_equal(tid, ar.graph_tmpl) and np.array_equal(tg, ar.tmpl_graph)
+    gk, gt, gg, _ = hip.fingerprint(ar.nodes, ar.node_off, ar.fp_mask)
+    assert np.array_equal(gk, keys) and np.array_equal(gt, tid) and np.array_equal(gg, tg)
+    nodes = small(1).nodes
+    rng = np.random.default_rng(9)
+    for G, distinct in ((8191, 8191), (8192, 8192), (8193, 8193), (8192, 37), (20000, 20000), (70000, 1000),
+                        (300000, 3)):
+        say(f"[fingerprint] G={G} distinct={distinct}")
+        # graph i = one node of the archive with its kernel id replaced by the pick
+        pick = rng.integers(0, distinct, G).astype(np.uint64)
+        pick[: min(G, distinct)] = rng.permutation(min(G, distinct)).astype(np.uint64)
+        nd = np.repeat(nodes[:1], G)
+        nd["kernel_id"] = pick + np.uint64(1000)
+        off = np.arange(G + 1, dtype=np.uint64)
+        keys, tid, tg = oracle.fingerprint(nd, off, L.FP_ALL)
+        gk, gt, gg, _ = hip.fingerprint(nd, off, L.FP_ALL)
+        assert np.array_equal(gk, keys) and np.array_equal(gt, tid) and np.array_equal(gg, tg)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3])
+def test_segment_fingerprint_one_launch(hip, oracle, idx):
+    """fdy_segment_fingerprint = fdy_reloc_segment + fdy_fingerprint, with the grouping done by
+    the last block of the launch (a prepared table supplies its counter) or by a second launch
+    (no prepared table); called twice in a row on the same prepared table."""
+    import paper_2604_06664_amd as fdy
+    import torch
+
+    ar = small(idx)
+    relocs, cnt = oracle.scan(ar.words, ar.table)
+    roff = oracle.reloc_segment(relocs, ar.word_off)
+    keys, tid, tg = oracle.fingerprint(ar.nodes, ar.node_off, ar.fp_mask)
+    G = ar.n_graphs
+    srun = hip.ScanRun(ar.words, ar.table, prepared=True)
+    srun.launch()
+    d_word_off, d_nodes, d_node_off = fdy.to_device(ar.word_off), fdy.to_device(ar.nodes), fdy.to_device(ar.node_off)
+    for prepared in (srun.d_prepared, None, srun.d_prepared):
+        d_roff = fdy.device_bytes((G + 1) * 8, fill=0xEE)
+        d_keys, d_tid, d_tg = (fdy.device_bytes(G * 8, fill=0xEE), fdy.device_bytes(G * 4, fill=0xEE),
+                               fdy.device_bytes(G * 4, fill=0xEE))
+        d_nt = torch.full((1,), -1, dtype=torch.int32, device="cuda:0")
+        fdy.fdy_segment_fingerprint(srun.d_relocs, srun.d_count, srun.capacity, d_word_off, d_roff, d_nodes,
+                                    d_node_off, G, ar.fp_mask, d_keys, d_tid, d_tg, d_nt, d_prepared=prepared)
+        torch.cuda.synchronize()
+        nt = int(d_nt.item())
+        assert nt == len(tg)
+        assert np.array_equal(fdy.to_host(d_roff, np.uint64, G + 1), roff)
+        assert np.array_equal(fdy.to_host(d_keys, np.uint64, G), keys)
+        assert np.array_equal(fdy.to_host(d_tid, np.uint32, G), tid)
+        assert np.array_equal(fdy.to_host(d_tg, np.uint32, nt), tg)
+    # the scan still works on the prepared table afterwards
+    got, n, st = (srun.launch(), srun.result())[-1]
+    assert st == 0 and n == cnt and np.array_equal(got, relocs)
 
 
 # ----------------------------------------------------------------------------- materialize

@@ -183,7 +183,7 @@ extern "C" int arena_graph_check(char* msg, int msg_len) {
   CK(hipMemcpy(d_nb, new_base.data(), n_alloc * 8, hipMemcpyHostToDevice));
   CK(hipMemset(d_status, 0, 4));
   FD(fdy_scan_rebase((const uint64_t*)d_words, n_words, (const fdy_alloc*)d_table, n_alloc,
-                     (const uint64_t*)d_nb, (uint64_t*)d_out, (uint64_t*)d_count, d_ws, ws_bytes,
+                     (const uint64_t*)d_nb, (uint64_t*)d_out, (uint64_t*)d_count, nullptr, d_ws, ws_bytes,
                      (uint32_t*)d_status, stream));
   CK(hipStreamSynchronize(stream));
   uint64_t count = 0;

@@ -196,8 +196,8 @@ extern "C" int install_scale_check(uint32_t n_nodes, uint32_t n_graphs, uint32_t
   CK(hipMemset(d_status.p, 0, 4));
   const size_t ws_scan = fdy_scan_workspace_bytes(n_words, n_buf);
   CK(d_ws_scan.alloc(ws_scan));
-  FD(fdy_scan_pointers(d_words.p, n_words, d_table.p, n_buf, d_relocs.p, n_words, d_count.p, d_ws_scan.p,
-                       ws_scan, d_status.p, stream));
+  FD(fdy_scan_pointers(d_words.p, n_words, d_table.p, n_buf, d_relocs.p, n_words, d_count.p, nullptr,
+                       d_ws_scan.p, ws_scan, d_status.p, stream));
   const std::vector<uint64_t> word_off = {0, n_words};
   CK(d_word_off.upload(word_off));
   CK(d_reloc_off.alloc(2));
@@ -209,7 +209,7 @@ extern "C" int install_scale_check(uint32_t n_nodes, uint32_t n_graphs, uint32_t
   CK(d_tmpl_graph.alloc(n_graphs));
   CK(d_n_tmpl.alloc(1));
   FD(fdy_fingerprint(d_recs.p, d_node_off.p, n_graphs, FDY_FP_ALL, d_keys.p, d_graph_tmpl.p, d_tmpl_graph.p,
-                     d_n_tmpl.p, stream));
+                     d_n_tmpl.p, nullptr, 0, stream));
   CK(hipStreamSynchronize(stream));
   uint32_t n_templates = 0, status = 0;
   uint64_t count = 0;

@@ -131,7 +131,7 @@ extern "C" int toy_graph_check(char* msg, int msg_len) {
   const size_t ws_scan = fdy_scan_workspace_bytes(n_words, n_alloc);
   CK(d_ws_scan.alloc(ws_scan));
   FD(fdy_scan_pointers(d_words.p, n_words, d_table.p, n_alloc, d_relocs.p, n_words, d_count.p,
-                       d_ws_scan.p, ws_scan, d_status.p, stream));
+                       nullptr, d_ws_scan.p, ws_scan, d_status.p, stream));
   const uint64_t word_off[2] = {0, n_words}, zeros[2] = {0, 0}, ovr_off[2] = {0, 1};
   CK(d_word_off.alloc(2));
   CK(d_reloc_off.alloc(2));
