@@ -151,6 +151,46 @@ __device__ __forceinline__ u32 lane_lower_bound(KeyFn key, u32 lo, u32 hi, u64 t
   return lo;
 }
 
+// Two per-lane lower bounds at once (A and B: independent lists), four-way: each step loads
+// three keys per list, all six before any is used, so a list of n entries takes log4 n
+// dependent round trips and the shorter search hides behind the longer one.  This kernel's
+// time is its longest chain of dependent loads.
+template <typename KeyA, typename KeyB>
+__device__ __forceinline__ void lane_lower_bound_pair(KeyA key_a, u32 lo_a, u32 hi_a, u64 target_a, KeyB key_b,
+                                                      u32 lo_b, u32 hi_b, u64 target_b, u32& res_a, u32& res_b) {
+  while (lo_a < hi_a || lo_b < hi_b) {
+    const u32 na = hi_a - lo_a, nb = hi_b - lo_b;
+    // probe positions (ascending; equal ones for ranges below four entries are harmless)
+    const u32 a1 = lo_a + na / 4, a2 = lo_a + na / 2, a3 = lo_a + na / 2 + na / 4;
+    const u32 b1 = lo_b + nb / 4, b2 = lo_b + nb / 2, b3 = lo_b + nb / 2 + nb / 4;
+    u64 ka1 = 0, ka2 = 0, ka3 = 0, kb1 = 0, kb2 = 0, kb3 = 0;
+    if (na) {
+      ka1 = key_a(a1);
+      ka2 = key_a(a2);
+      ka3 = key_a(a3);
+    }
+    if (nb) {
+      kb1 = key_b(b1);
+      kb2 = key_b(b2);
+      kb3 = key_b(b3);
+    }
+    if (na) {
+      if (ka3 < target_a) lo_a = a3 + 1;
+      else if (ka2 < target_a) { lo_a = a2 + 1; hi_a = a3; }
+      else if (ka1 < target_a) { lo_a = a1 + 1; hi_a = a2; }
+      else hi_a = a1;
+    }
+    if (nb) {
+      if (kb3 < target_b) lo_b = b3 + 1;
+      else if (kb2 < target_b) { lo_b = b2 + 1; hi_b = b3; }
+      else if (kb1 < target_b) { lo_b = b1 + 1; hi_b = b2; }
+      else hi_b = b1;
+    }
+  }
+  res_a = lo_a;
+  res_b = lo_b;
+}
+
 // The per-graph prefix sums as the tile, patch and dims blocks read them: from the workspace
 // (written by mat_prep_graphs_kernel) or from the block's own LDS copy.
 struct PrepView {
@@ -206,11 +246,11 @@ __device__ __forceinline__ void prep_tiles_block(const MatParams& p, const PrepV
     const fdy_reloc* relocs = d.relocs;
     rl0 = (u32)d.src_reloc_off[q.s];
     rl1 = (u32)d.src_reloc_off[q.s + 1];
-    reloc_lo = lane_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, rl0, rl1, q.src_word);
     const fdy_ovr32* ovr = d.ovr;
     const u32 ov0 = (u32)d.ovr_off[q.g];
     ov1 = (u32)d.ovr_off[q.g + 1];
-    ovr_lo = lane_lower_bound([&](u32 i) { return (u64)ovr[i].byte_off; }, ov0, ov1, q.k0 * 8);
+    lane_lower_bound_pair([&](u32 i) { return (u64)relocs[i].word; }, rl0, rl1, q.src_word,
+                          [&](u32 i) { return (u64)ovr[i].byte_off; }, ov0, ov1, q.k0 * 8, reloc_lo, ovr_lo);
   }
   s_lo[tid] = make_uint2(reloc_lo, ovr_lo);
   __syncthreads();

@@ -177,21 +177,36 @@ __device__ __forceinline__ u64 chunk_exclusive_prefix(const u64* cstate, u32 chu
   u64 excl = 0;
   int pos = (int)chunk - 1;
   u32 spins = 0;
+  // The states of up to 256 predecessors are requested at once and then looked at 64 at a
+  // time, nearest first (the chunks of a small input all finish at about the same moment, and
+  // a walk of one dependent load per 64 of them would be most of such a launch's time).
+  constexpr int kAhead = 4;
   for (;;) {
-    const int idx = pos - (int)l;
-    const u64 v = idx >= 0 ? ld_state(&cstate[idx]) : kFlagInc;  // before chunk 0: prefix 0
-    const u32 flag = (u32)(v >> 62);
-    const u64 inc_mask = ballot(flag == 2);
-    const u64 empty_mask = ballot(flag == 0);
-    const u32 first_inc = inc_mask ? (u32)__ffsll((long long)inc_mask) - 1 : 64;
-    const u64 need = first_inc >= 63 ? ~0ull : ((2ull << first_inc) - 1);  // lanes 0..first_inc
-    if (empty_mask & need) {
-      if (!spin_once(spins, spin_limit, d_status)) break;
-      continue;
+    u64 v[kAhead];
+#pragma unroll
+    for (int j = 0; j < kAhead; ++j) {
+      const int idx = pos - 64 * j - (int)l;
+      v[j] = idx >= 0 ? ld_state(&cstate[idx]) : kFlagInc;  // before chunk 0: prefix 0
     }
-    excl += wave_sum_u64(((need >> l) & 1) ? (v & kValMask) : 0);
-    if (first_inc < 64) break;
-    pos -= 64;
+    bool found = false, wait = false;
+#pragma unroll
+    for (int j = 0; j < kAhead; ++j) {
+      if (found || wait) continue;
+      const u32 flag = (u32)(v[j] >> 62);
+      const u64 inc_mask = ballot(flag == 2);
+      const u64 empty_mask = ballot(flag == 0);
+      const u32 first_inc = inc_mask ? (u32)__ffsll((long long)inc_mask) - 1 : 64;
+      const u64 need = first_inc >= 63 ? ~0ull : ((2ull << first_inc) - 1);  // lanes 0..first_inc
+      if (empty_mask & need) {
+        wait = true;  // what lies before this block of 64 is read again
+      } else {
+        excl += wave_sum_u64(((need >> l) & 1) ? (v[j] & kValMask) : 0);
+        if (first_inc < 64) found = true;
+        else pos -= 64;
+      }
+    }
+    if (found) break;
+    if (wait && !spin_once(spins, spin_limit, d_status)) break;
   }
   return excl;
 }
@@ -1198,9 +1213,13 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       }
     }
     __syncthreads();
+    // this workgroup is through with the shared state: the count goes out before the last
+    // entries are written, so that its round trip runs beside those stores
+    if (p.self_clean && closer) finish_and_reset(p);
     write_round<kGroups, kG, kHalf, kOut>(p, prev, s_excl[db], qi_all, top, span_lo, span_len, shifts, qw, marked);
+  } else if (p.self_clean && closer) {
+    finish_and_reset(p);
   }
-  if (p.self_clean && closer) finish_and_reset(p);
 }
 
 // ---- fused scan + rebase: out[j] = new_base[region] + offset for a hit, words[j] otherwise.
