@@ -14,9 +14,11 @@
  *
  * Conventions that hold for every entry point
  *  - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller owns
- *    every buffer; the library never allocates or frees device memory, copies nothing
- *    between host and device, and keeps no state between calls (the process-wide tuning
- *    and timing switches of the internal fdy_tune.h are not part of this interface).
+ *    every buffer; the library never allocates or frees device memory and copies nothing
+ *    between host and device.  State between calls lives in buffers of the caller's (a
+ *    prepared table, see fdy_scan_table_prepare), with one exception: the process-wide
+ *    tuning knobs and timing records declared in fdy_internal.h (measurement support, off
+ *    and at their defaults unless a caller touches them; not thread-safe).
  *  - Every call that takes a stream only ENQUEUES kernels on it (hipStream_t passed as
  *    void*; NULL = the default stream).  Outputs are valid once the caller has
  *    synchronized that stream.  Calls on one stream may be chained without host syncs:

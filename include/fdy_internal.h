@@ -1,9 +1,16 @@
-/* Internal tuning knobs of libfdy (launch shapes, LDS budget, spin limit).  They exist for
- * measurement sweeps and for tests that force the bounded-wait error path from the host;
- * they are not part of the public interface and may change without notice.  Values are
- * process-wide and read at call time. */
-#ifndef FDY_TUNE_H
-#define FDY_TUNE_H
+/* fdy_internal.h - INTERNAL exports of libfdy: tuning knobs (launch shapes, LDS budget, spin
+ * limit) and per-kernel event timing.  They exist for measurement sweeps, for the bench, and
+ * for tests that force the bounded-wait error path from the host; they are not part of the
+ * public interface (fdy.h) and may change without notice.
+ *
+ * This is the only state the library keeps between calls: a process-wide array of integers
+ * (the knobs) and the timing records.  Every entry point reads the knobs it needs once, at
+ * the start of the call.  Neither is thread-safe: set knobs, and enable or read timing, only
+ * while no other thread is inside a library call.  A knob that changes the layout of the
+ * search hierarchy (FDY_TUNE_SCAN_TOP_LOG2) invalidates prepared tables made before the
+ * change; the scan detects that on the device (FDY_ST_BAD_PREPARED). */
+#ifndef FDY_INTERNAL_H
+#define FDY_INTERNAL_H
 #ifdef __cplusplus
 extern "C" {
 #endif

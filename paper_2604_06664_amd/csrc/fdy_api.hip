@@ -4,7 +4,7 @@
 #include <vector>
 
 #include "fdy_device.hpp"
-#include "fdy_tune.h"
+#include "fdy_internal.h"
 
 namespace {
 int g_tune[FDY_TUNE_COUNT] = {

@@ -16,7 +16,7 @@
 // template and a list of scalars per graph); ordering inside a tile comes from ballots over
 // words in index order, low half before high half.
 #include "fdy_device.hpp"
-#include "fdy_tune.h"
+#include "fdy_internal.h"
 
 namespace fdy {
 namespace {

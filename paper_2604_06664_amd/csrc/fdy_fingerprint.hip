@@ -13,7 +13,7 @@
 // a second, single-workgroup launch; archives of more than 8,192 graphs use a table in the
 // caller's workspace.
 #include "fdy_device.hpp"
-#include "fdy_tune.h"
+#include "fdy_internal.h"
 
 namespace fdy {
 namespace {

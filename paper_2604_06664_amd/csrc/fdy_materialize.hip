@@ -31,7 +31,7 @@
 //                            relocation lists and base maps are re-read per group from L2 /
 //                            Infinity Cache; only the output is compulsory HBM traffic.
 #include "fdy_device.hpp"
-#include "fdy_tune.h"
+#include "fdy_internal.h"
 
 namespace fdy {
 namespace {

@@ -75,7 +75,7 @@
 #include <type_traits>
 
 #include "fdy_device.hpp"
-#include "fdy_tune.h"
+#include "fdy_internal.h"
 
 namespace fdy {
 namespace {

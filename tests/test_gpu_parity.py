@@ -892,9 +892,12 @@ def test_materialize_lists_out_of_order_are_flagged(hip, oracle):
 # ------------------------------------------------------------------- whole path, full sizes
 @pytest.mark.parametrize("idx", [1, 2, 3, 5, 4])
 def test_full_config_whole_path(hip, oracle, idx):
-    """scan -> segment -> fingerprint -> materialize chained on the device (no host round
-    trip between the calls), at the full size of each configuration, every output compared
-    with the oracle element by element."""
+    """The whole path chained on the device (no host round trip between the calls), at the full
+    size of each configuration, every output compared with the oracle element by element.
+    Twice: in the launch configuration that bench.py times (table prepared once, segmentation
+    and fingerprint in one launch, and - where every graph is its own template under one base
+    map, config 4 - the scan writing the materialized output itself), and through the plain
+    calls (fdy_scan_pointers, fdy_reloc_segment, fdy_fingerprint, fdy_materialize)."""
     import paper_2604_06664_amd as fdy
     import torch
 
@@ -906,36 +909,38 @@ def test_full_config_whole_path(hip, oracle, idx):
     keys, tid, tg = oracle.fingerprint(ar.nodes, ar.node_off, ar.fp_mask)
     assert np.array_equal(tid, ar.graph_tmpl) and np.array_equal(tg, ar.tmpl_graph)
     mp = MatProblem.from_archive(ar, relocs, roff, graph_tmpl=tid, tmpl_graph=tg)
-    say(f"[full] config {idx}: gpu W={len(ar.words)} A={ar.n_alloc} G={ar.n_graphs} M={ar.n_maps}")
-    srun = hip.ScanRun(ar.words, ar.table, capacity=cnt + 16)
-    srun.launch()
+    want_dims = len(ar.nodes) > 0
+    ref, rdims = oracle.materialize(mp, want_dims=want_dims)
     G = ar.n_graphs
-    d_word_off = fdy.to_device(ar.word_off)
-    d_roff = fdy.device_bytes((G + 1) * 8, fill=0xEE)
-    fdy.fdy_reloc_segment(srun.d_relocs, srun.d_count, srun.capacity, d_word_off, G + 1, d_roff)
-    gk, gt, gg, fp = hip.fingerprint(ar.nodes, ar.node_off, ar.fp_mask)
-    mrun = hip.MatRun(mp, want_dims=len(ar.nodes) > 0, device_overrides=dict(
-        src_words=srun.d_words, relocs=srun.d_relocs, src_reloc_off=d_roff,
-        graph_tmpl=fp["d_tid"], tmpl_graph=fp["d_tg"]))
-    mrun.launch()
-    got_relocs, got_cnt, st = srun.result()
-    say(f"[full] config {idx}: comparing")
-    assert st == 0 and got_cnt == cnt == len(ar.ptr_word)
-    assert np.array_equal(got_relocs, relocs)
-    assert np.array_equal(fdy.to_host(d_roff, np.uint64, G + 1), roff)
-    assert np.array_equal(gk, keys) and np.array_equal(gt, tid) and np.array_equal(gg, tg)
-    del got_relocs
-    ref, rdims = oracle.materialize(mp, want_dims=len(ar.nodes) > 0)
-    out, dims, st = mrun.result()
-    assert st == 0
-    assert np.array_equal(out, ref)
-    if rdims is not None:
-        assert np.array_equal(dims, rdims)
-    del mrun, srun
-    torch.cuda.empty_cache()
+    for how in ("as benchmarked", "plain calls"):
+        bench_like = how == "as benchmarked"
+        say(f"[full] config {idx}: gpu, {how}: W={len(ar.words)} A={ar.n_alloc} G={G} M={ar.n_maps}")
+        run = hip.PathRun(ar, reloc_capacity=cnt + 16, prepared=bench_like, one_pass=None if bench_like else False)
+        assert run.one_pass == (bench_like and idx == 4)
+        for t in (run.scan.d_relocs, run.mat.d_out):
+            t.fill_(0xEE)
+        run.step()
+        assert run.status() == 0
+        got_cnt = int(run.scan.d_count.item())
+        assert got_cnt == cnt == len(ar.ptr_word)
+        say(f"[full] config {idx}: comparing")
+        assert np.array_equal(fdy.to_host(run.scan.d_relocs, hip.RELOC, cnt), relocs)
+        assert np.array_equal(fdy.to_host(run.d_reloc_off, np.uint64, G + 1), roff)
+        nt = int(run.d_nt.item())
+        assert nt == len(tg)
+        assert np.array_equal(fdy.to_host(run.d_keys, np.uint64, G), keys)
+        assert np.array_equal(fdy.to_host(run.d_tid, np.uint32, G), tid)
+        assert np.array_equal(fdy.to_host(run.d_tg, np.uint32, nt), tg)
+        out = fdy.to_host(run.mat.d_out, np.uint64, mp.M * run.mat.wpm).reshape(mp.M, run.mat.wpm)
+        assert np.array_equal(out, ref)
+        del out
+        if rdims is not None:
+            assert np.array_equal(fdy.to_host(run.mat.d_dims, np.uint32, run.mat.nodes_total * 6).reshape(-1, 6), rdims)
+        del run
+        torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
 def test_repeated_runs_give_identical_bytes(hip, idx):
     """Workgroups draw their chunks in whatever order they start, and hits are placed by a
     look-back over other workgroups' totals: a race there would show as outputs that differ
@@ -951,6 +956,8 @@ def test_repeated_runs_give_identical_bytes(hip, idx):
             run.mat.d_out] + ([run.mat.d_dims] if run.mat.d_dims is not None else [])
     first = None
     for rep in range(4):
+        # outputs and workspaces are poisoned; the prepared table is not (its counters must have
+        # been left zeroed by the run before)
         for t in outs + [run.scan.d_ws, run.mat.d_ws]:
             t.fill_(0x5A + rep)
         run.step()

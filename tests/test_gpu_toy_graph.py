@@ -31,12 +31,15 @@ def test_toy_graph_install_and_replay():
 
 
 def test_install_at_decode_graph_scale():
-    """hipGraph install at the node count of one dense-decode graph (36 layers x 16 kernels):
-    67 graphs x 2 new layouts materialized by the library, installed node by node into the
-    template's executable graph, each replayed and checked against a host simulation.  Prints
-    the install time per graph beside building and instantiating the graph from scratch (the
-    two quantities of Table 2 of the paper; its numbers are for other hardware and real
-    kernels, so they are context, not a bar)."""
+    """hipGraph install at the node count of one dense-decode graph (36 layers x 16 kernels) with
+    three topologies side by side (Section 4.2.1: one template graph per unique topology): 67
+    graphs x 2 new layouts; scan, segmentation, fingerprint, override derivation and
+    materialization by the library; every graph installed node by node - kernel arguments AND
+    launch dimensions - into the executable graph of the template that the fingerprint gave it,
+    replayed, and checked against a host simulation whose result depends on every node's
+    kernel, scalar and gridDim.x.  Prints the install time per graph beside building and
+    instantiating the graph from scratch (the two quantities of Table 2 of the paper; its
+    numbers are for other hardware and real kernels, so they are context, not a bar)."""
     import torch
 
     assert torch.cuda.is_available()
@@ -50,12 +53,14 @@ def test_install_at_decode_graph_scale():
     toy.install_scale_check.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_double),
                                         C.c_char_p, C.c_int]
     msg = C.create_string_buffer(1024)
-    stats = (C.c_double * 9)()
-    print("[install] 576 nodes x 67 graphs x 2 maps", flush=True)
+    stats = (C.c_double * 12)()
+    print("[install] 576 nodes x 67 graphs x 2 maps, 3 topologies", flush=True)
     rc = toy.install_scale_check(576, 67, 2, stats, msg, 1024)
     print("[install]", msg.value.decode(), flush=True)
     assert rc == 0, msg.value.decode()
-    assert stats[5] == 67 * 2 and stats[6] == 2 * 576
+    assert stats[5] == 67 * 2 and stats[6] == 2 * 576 * 67
+    assert stats[9] >= 3 and stats[10] == stats[9]  # three topologies, each executable graph used
+    assert stats[11] > 67  # most installs set a gridDim.x that is not the template's
     out = os.environ.get("FDY_TEST_OUT", "")  # optional folder for the measured figures
     if os.path.isdir(out):
         with open(os.path.join(out, "install_scale.txt"), "w") as f:
