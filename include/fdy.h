@@ -477,6 +477,24 @@ int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words, uint32_t*
                     void* d_workspace, size_t workspace_bytes, uint32_t* d_status,
                     void* hip_stream);
 
+/* ---- fdy_materialize without a workspace ----------------------------------------------
+ * For callers that cannot allocate device memory where they call from: code that runs under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation,
+ * same outputs and status bits as fdy_materialize; the tile table and the other per-call
+ * tables lie in a fixed array of fdy_materialize_static_limit() bytes (4 MiB) inside the
+ * loaded library, one copy per GPU, held until the process ends.  The call allocates and
+ * frees nothing.
+ *   - FDY_ERR_WORKSPACE: the descriptor needs more than the fixed array holds
+ *     (fdy_materialize_workspace_bytes(h_desc) > fdy_materialize_static_limit()); use
+ *     fdy_materialize then.
+ *   - Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU
+ *     (different streams, no ordering between them) race.  Calls on one stream are fine.
+ *   - The first call on each device looks the array's address up (with that device current);
+ *     make it outside graph capture. */
+size_t fdy_materialize_static_limit(void);
+int fdy_materialize_static(const fdy_mat_desc* h_desc, uint64_t* d_out_words, uint32_t* d_out_dims,
+                           uint32_t* d_status, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -110,6 +110,11 @@ def lib():
         L.fdy_materialize.restype = C.c_int
         L.fdy_materialize.argtypes = [C.POINTER(fdy_mat_desc), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_size_t, C.c_void_p, C.c_void_p]
+        L.fdy_materialize_static_limit.restype = C.c_size_t
+        L.fdy_materialize_static_limit.argtypes = []
+        L.fdy_materialize_static.restype = C.c_int
+        L.fdy_materialize_static.argtypes = [C.POINTER(fdy_mat_desc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_void_p]
         L.fdy__tune_get.restype = C.c_int
         L.fdy__tune_get.argtypes = [C.c_int]
         L.fdy__tune_set.restype = C.c_int
@@ -307,6 +312,16 @@ def fdy_materialize(h_desc, d_out_words, d_out_dims, d_workspace, workspace_byte
                                _ptr(d_workspace), int(workspace_bytes), _ptr(d_status),
                                _stream(stream))
     return _check(rc, "fdy_materialize") if check else rc
+
+
+def fdy_materialize_static_limit():
+    return lib().fdy_materialize_static_limit()
+
+
+def fdy_materialize_static(h_desc, d_out_words, d_out_dims, d_status=None, stream=None, check=True):
+    rc = lib().fdy_materialize_static(C.byref(h_desc), _ptr(d_out_words), _ptr(d_out_dims), _ptr(d_status),
+                                      _stream(stream))
+    return _check(rc, "fdy_materialize_static") if check else rc
 
 
 def tune_get(knob):

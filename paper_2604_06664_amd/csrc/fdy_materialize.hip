@@ -30,6 +30,8 @@
 //                            streams the tile out with coalesced stores.  Templates,
 //                            relocation lists and base maps are re-read per group from L2 /
 //                            Infinity Cache; only the output is compulsory HBM traffic.
+#include <mutex>
+
 #include "fdy_device.hpp"
 #include "fdy_internal.h"
 
@@ -666,9 +668,52 @@ extern "C" size_t fdy_materialize_workspace_bytes(const fdy_mat_desc* h_desc) {
   return layout(h_desc, nullptr, nullptr);
 }
 
+// Scratch of the entry point that allocates nothing (fdy_materialize_static): the tile table and
+// the other per-call tables of a materialization, in device memory that belongs to the loaded
+// library.  Each GPU holds its own copy at its own address, found once per device with
+// hipGetSymbolAddress; host code uses that address, never the array's name.
+constexpr size_t kStaticScratchBytes = 4u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static int materialize_launch(const fdy_mat_desc* h_desc, uint64_t* d_out_words, uint32_t* d_out_dims,
+                              void* d_workspace, size_t workspace_bytes, uint32_t* d_status,
+                              void* hip_stream);
+
 extern "C" int fdy_materialize(const fdy_mat_desc* h_desc, uint64_t* d_out_words, uint32_t* d_out_dims,
                                void* d_workspace, size_t workspace_bytes, uint32_t* d_status,
                                void* hip_stream) {
+  return materialize_launch(h_desc, d_out_words, d_out_dims, d_workspace, workspace_bytes, d_status, hip_stream);
+}
+
+extern "C" size_t fdy_materialize_static_limit(void) { return kStaticScratchBytes; }
+
+extern "C" int fdy_materialize_static(const fdy_mat_desc* h_desc, uint64_t* d_out_words, uint32_t* d_out_dims,
+                                      uint32_t* d_status, void* hip_stream) {
+  if (!desc_ok(h_desc)) return FDY_ERR_INVALID_ARG;
+  if (layout(h_desc, nullptr, nullptr) > kStaticScratchBytes) return FDY_ERR_WORKSPACE;  // beyond the fixed scratch
+  constexpr int kMaxDevices = 64;
+  static void* ptr_of_device[kMaxDevices] = {};
+  static std::mutex mu;
+  int dev = 0;
+  FDY_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return FDY_ERR_INVALID_ARG;
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of_device[dev]) {  // first call on this device, which is current
+      void* found = nullptr;
+      FDY_HIP_TRY(hipGetSymbolAddress(&found, HIP_SYMBOL(scratch)));
+      if (!found) return FDY_ERR_HIP;
+      ptr_of_device[dev] = found;
+    }
+    ptr = ptr_of_device[dev];
+  }
+  return materialize_launch(h_desc, d_out_words, d_out_dims, ptr, kStaticScratchBytes, d_status, hip_stream);
+}
+
+static int materialize_launch(const fdy_mat_desc* h_desc, uint64_t* d_out_words, uint32_t* d_out_dims,
+                              void* d_workspace, size_t workspace_bytes, uint32_t* d_status,
+                              void* hip_stream) {
   if (!desc_ok(h_desc)) return FDY_ERR_INVALID_ARG;
   const fdy_mat_desc& d = *h_desc;
   if (d.n_graphs == 0 || d.n_maps == 0) return FDY_OK;
