@@ -335,6 +335,7 @@ __device__ __forceinline__ void stage_tile(u64* buf, const u64* src, u64 src_wor
 // words the previous map's rank patched are given their template values back first.
 constexpr int kMatPre = kMatTile / kMatBlock;
 constexpr int kMatStore = kMatTile / (2 * kMatBlock);  // 16-byte chunks per thread
+constexpr int kMatOvrPre = 2;                          // overrides of the tile a thread keeps in registers
 
 __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
   __shared__ __align__(16) u64 buf[kMatTile];
@@ -396,23 +397,60 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
   }
   const bool has_ovr = ent.ovr_lo < ent.ovr_hi;
   const bool has_patch = d.map_rank != nullptr;
-  __syncthreads();
-  uint2 undo = make_uint2(0, 0);  // the previous map's patch slice
-  for (u32 m = m0; m < m1; ++m) {
-    if (has_patch && m != m0) {
-      // take the previous rank's patches back out: those words get the template's value again
-      // (relocations and overrides that touch them are applied again below, as for every map)
-      for (u32 q = undo.x + tid; q < undo.y; q += kMatBlock) {
-        const u64 k = (u64)d.patch[q].word - ent.k0;
-        if (k < n) buf[k] = src[k];
+  // What repeats per map is kept off the chain of dependent loads as far as it goes: the
+  // tile's overrides (the same for every map) wait in registers, kMatOvrPre per thread; a map's
+  // patch slice is looked up one map ahead; its entries are requested together with the base-map
+  // gathers, one per thread; and a patched word gets back what it held before the patch (the
+  // template's value, or a rebased or overridden one that the next map's c2 / c3 write again
+  // anyway) from a register instead of from the template in memory.  Lists longer than the
+  // registers hold take their surplus from memory, in the same stage.
+  u32 ov_at[kMatOvrPre], ov_val[kMatOvrPre];
+  if (has_ovr) {
+#pragma unroll
+    for (int i = 0; i < kMatOvrPre; ++i) {
+      const u32 q = ent.ovr_lo + tid + (u32)i * kMatBlock;
+      ov_at[i] = 0xffffffffu;
+      ov_val[i] = 0;
+      if (q < ent.ovr_hi) {
+        const fdy_ovr32 o = d.ovr[q];
+        const u64 b = (u64)o.byte_off - (u64)ent.k0 * 8;
+        if ((b >> 3) < n && (b & 3) == 0) {
+          ov_at[i] = (u32)(b >> 2);
+          ov_val[i] = o.value;
+        } else {
+          bad = true;
+        }
       }
-      __syncthreads();
     }
-    // c2: rebase
+  }
+  auto patch_slice = [&](u32 m) {  // the slice of map m's rank inside this tile; empty for a bad rank
+    const u32 rk_m = d.map_rank[m];
+    return rk_m < d.n_ranks ? p.ws.tile_patch[(u64)j * d.n_ranks + rk_m] : make_uint2(0xffffffffu, 0);
+  };
+  // this thread's patch entry of a slice (none: word index all ones)
+  auto patch_entry = [&](uint2 pr) {
+    u64x2 e = u64x2{~0ull, 0};
+    if (pr.x != 0xffffffffu && pr.x + tid < pr.y) e = *reinterpret_cast<const u64x2*>(&d.patch[pr.x + tid]);
+    return e;
+  };
+  uint2 pr_next = has_patch ? patch_slice(m0) : make_uint2(0, 0);
+  u64x2 pe_next = has_patch ? patch_entry(pr_next) : u64x2{~0ull, 0};
+  __syncthreads();
+  for (u32 m = m0; m < m1; ++m) {
+    const uint2 pr = pr_next;
+    const u64x2 pe = pe_next;
+    if (has_patch && m + 1 < m1) {
+      pr_next = patch_slice(m + 1);
+      pe_next = patch_entry(pr_next);
+    }
+    // requests of this map: the base-map gathers (c2); its patch entry (c4) came a map ahead
     const u64* nb = d.new_base + (u64)m * d.n_alloc;
     u64 base[kMatPre];
 #pragma unroll
     for (int i = 0; i < kMatPre; ++i) base[i] = rk[i] != 0xffffffffu ? nb[rr[i]] : 0;
+    const bool my_patch = has_patch && (u32)pe.x != 0xffffffffu;
+    if (has_patch && pr.x == 0xffffffffu) bad = true;
+    // c2: rebase
 #pragma unroll
     for (int i = 0; i < kMatPre; ++i)
       if (rk[i] != 0xffffffffu) buf[rk[i]] = base[i] + ro[i];
@@ -420,30 +458,39 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
     if (has_ovr) {
       __syncthreads();
       u32* buf32 = reinterpret_cast<u32*>(buf);
-      for (u32 q = ent.ovr_lo + tid; q < ent.ovr_hi; q += kMatBlock) {
+#pragma unroll
+      for (int i = 0; i < kMatOvrPre; ++i)
+        if (ov_at[i] != 0xffffffffu) buf32[ov_at[i]] = ov_val[i];
+      for (u32 q = ent.ovr_lo + tid + kMatOvrPre * kMatBlock; q < ent.ovr_hi; q += kMatBlock) {
         const fdy_ovr32 o = d.ovr[q];
         const u64 b = (u64)o.byte_off - (u64)ent.k0 * 8;
         if ((b >> 3) < n && (b & 3) == 0) buf32[b >> 2] = o.value;
         else bad = true;
       }
     }
-    // c4: rank patches
+    // c4: rank patches; what the patched word held goes to a register for the way back
+    u32 undo_at = 0xffffffffu;
+    u64 undo_val = 0;
+    const bool long_slice = has_patch && pr.x != 0xffffffffu && pr.y - pr.x > (u32)kMatBlock;
     if (has_patch) {
       __syncthreads();
-      const u32 rk_m = d.map_rank[m];
-      if (rk_m < d.n_ranks) {
-        const uint2 pr = p.ws.tile_patch[(u64)j * d.n_ranks + rk_m];
-        undo = pr;
-        for (u32 q = pr.x + tid; q < pr.y; q += kMatBlock) {
+      if (my_patch) {
+        const u64 k = (u64)(u32)pe.x - ent.k0;
+        if (k < n) {
+          undo_at = (u32)k;
+          undo_val = buf[k];
+          buf[k] = pe.y;
+        } else {
+          bad = true;
+        }
+      }
+      if (long_slice)
+        for (u32 q = pr.x + tid + kMatBlock; q < pr.y; q += kMatBlock) {
           const u64x2 raw = *reinterpret_cast<const u64x2*>(&d.patch[q]);
           const u64 k = (u64)(u32)raw.x - ent.k0;
           if (k < n) buf[k] = raw.y;
           else bad = true;
         }
-      } else {
-        bad = true;
-        undo = make_uint2(0, 0);
-      }
     }
     __syncthreads();
     // stream the tile out: LDS -> registers, then 16-byte non-temporal stores (the output is
@@ -464,7 +511,20 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
       }
     }
     const u64 first = buf[0], last = buf[n - 1];
-    if (m + 1 < m1) __syncthreads();
+    if (m + 1 < m1) {
+      __syncthreads();
+      if (has_patch) {
+        // the patched words get back what they held (the surplus of a long slice: the template's
+        // value from memory); relocations and overrides that touch them are applied again
+        if (undo_at != 0xffffffffu) buf[undo_at] = undo_val;
+        if (long_slice)
+          for (u32 q = pr.x + tid + kMatBlock; q < pr.y; q += kMatBlock) {
+            const u64 k = (u64)d.patch[q].word - ent.k0;
+            if (k < n) buf[k] = src[k];
+          }
+        __syncthreads();
+      }
+    }
 #pragma unroll
     for (int c = 0; c < kMatStore; ++c) {
       const u32 i = tid + (u32)c * kMatBlock;
