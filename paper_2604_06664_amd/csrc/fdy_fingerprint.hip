@@ -223,7 +223,14 @@ __global__ __launch_bounds__(kFpBlock) void fp_key_kernel(FpArgs a) {
       u64 n = *a.d_count;
       if (n > a.capacity) n = a.capacity;
       const fdy_reloc* relocs = a.relocs;
-      const u32 r = wave_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, 0u, (u32)n, a.word_off[b]);
+      const u64 target = a.word_off[b];
+      // the first boundary is word 0 and the last lies behind every word: both are answered
+      // without the search's dependent round trips
+      u32 r = 0;
+      if (target != 0 && n != 0)
+        r = (u64)relocs[n - 1].word < target
+                ? (u32)n
+                : wave_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, 0u, (u32)n, target);
       if (lane_id() == 0) a.reloc_off[b] = r;
     }
   }

@@ -177,36 +177,21 @@ __device__ __forceinline__ u64 chunk_exclusive_prefix(const u64* cstate, u32 chu
   u64 excl = 0;
   int pos = (int)chunk - 1;
   u32 spins = 0;
-  // The states of up to 256 predecessors are requested at once and then looked at 64 at a
-  // time, nearest first (the chunks of a small input all finish at about the same moment, and
-  // a walk of one dependent load per 64 of them would be most of such a launch's time).
-  constexpr int kAhead = 4;
   for (;;) {
-    u64 v[kAhead];
-#pragma unroll
-    for (int j = 0; j < kAhead; ++j) {
-      const int idx = pos - 64 * j - (int)l;
-      v[j] = idx >= 0 ? ld_state(&cstate[idx]) : kFlagInc;  // before chunk 0: prefix 0
+    const int idx = pos - (int)l;
+    const u64 v = idx >= 0 ? ld_state(&cstate[idx]) : kFlagInc;  // before chunk 0: prefix 0
+    const u32 flag = (u32)(v >> 62);
+    const u64 inc_mask = ballot(flag == 2);
+    const u64 empty_mask = ballot(flag == 0);
+    const u32 first_inc = inc_mask ? (u32)__ffsll((long long)inc_mask) - 1 : 64;
+    const u64 need = first_inc >= 63 ? ~0ull : ((2ull << first_inc) - 1);  // lanes 0..first_inc
+    if (empty_mask & need) {
+      if (!spin_once(spins, spin_limit, d_status)) break;
+      continue;
     }
-    bool found = false, wait = false;
-#pragma unroll
-    for (int j = 0; j < kAhead; ++j) {
-      if (found || wait) continue;
-      const u32 flag = (u32)(v[j] >> 62);
-      const u64 inc_mask = ballot(flag == 2);
-      const u64 empty_mask = ballot(flag == 0);
-      const u32 first_inc = inc_mask ? (u32)__ffsll((long long)inc_mask) - 1 : 64;
-      const u64 need = first_inc >= 63 ? ~0ull : ((2ull << first_inc) - 1);  // lanes 0..first_inc
-      if (empty_mask & need) {
-        wait = true;  // what lies before this block of 64 is read again
-      } else {
-        excl += wave_sum_u64(((need >> l) & 1) ? (v[j] & kValMask) : 0);
-        if (first_inc < 64) found = true;
-        else pos -= 64;
-      }
-    }
-    if (found) break;
-    if (wait && !spin_once(spins, spin_limit, d_status)) break;
+    excl += wave_sum_u64(((need >> l) & 1) ? (v & kValMask) : 0);
+    if (first_inc < 64) break;
+    pos -= 64;
   }
   return excl;
 }
@@ -966,7 +951,7 @@ __device__ __forceinline__ fdy_reloc* stage_of(const ScanParams& p, u32 b, int g
 // A dense group without a staging area is searched a second time here, from the words in
 // memory (scratch: the wave's value queue qw, idle between rounds, and the group's own index
 // queue, which a dense group does not use).
-template <int kGroups, int kG, bool kHalf, bool kK16>
+template <int kGroups, int kG, bool kHalf, bool kK16, bool kStaged>
 __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResults<kGroups, kG>& r,
                                             u64 chunk_excl, unsigned short* qi_all, const void* top, u64 span_lo,
                                             u64 span_len, u32 shifts, u64* qw, u32& marked) {
@@ -988,7 +973,7 @@ __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResu
           store_reloc(p, pos + __popcll(bl & lt), (u32)(wbase + qi[k * 64 + lane_id()]), r.reg[g][k], r.off[g][k]);
         pos += __popcll(bl);
       }
-    } else if (!p.stage) {
+    } else if constexpr (!kStaged) {
       u64 H = 0;
       for (int row = 0; row < kG; ++row) {
         u64 dw[kWpl];
@@ -1021,7 +1006,11 @@ __device__ __forceinline__ void write_round(const ScanParams& p, const RoundResu
 // time: by then the lines have left the L2, and 13 M scattered 8-byte stores into memory cost
 // more than the whole scan.)  The 64 KiB this takes come from the level-0 keys, which such a
 // launch keeps in 16 bits each, and from half of the bucket index.
-template <int kGroups, int kG, bool kHalf, bool kOut>
+// kStaged: the workspace holds a staging area for dense groups.  The other variant searches
+// them twice and carries that second search's code.  (One kernel that chose between the two
+// at run time was measured 3 to 5 % slower than either, on inputs without a single dense
+// group: this kernel's time moves by that much with the size and layout of its code.)
+template <int kGroups, int kG, bool kHalf, bool kOut, bool kStaged>
 __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
   constexpr int kUnits = kGroups * kWaves;  // (group, wave) units of a chunk, in word order
   constexpr int kChunk = kUnits * kG;       // sub-tiles a workgroup draws per ticket
@@ -1134,7 +1123,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       } else {
         // more candidates than the registers keep results for: the hits go to the wave's
         // staging area as complete entries and are copied to their place a round later
-        fdy_reloc* dst = p.stage ? stage_of<kGroups, kG>(p, b, g) : nullptr;
+        fdy_reloc* dst = kStaged ? stage_of<kGroups, kG>(p, b, g) : nullptr;
         for (int r = 0; r < kG; ++r) {
           u64 dw[kWpl];
           Filt t;
@@ -1142,7 +1131,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
           filter_words<kHalf>(dw, t, span_lo, span_len);
           u64* vals = kOut ? qw + r * kSub : qw;
           const u64 wb = (u64)(first_sub + r) * kSub;
-          if (dst) H += dense_pass<kHalf, kOut, kOut, kDenseStage>(p, dw, t, top, span_lo, shifts, vals, qi, wb, dst + H, 0, marked);
+          if constexpr (kStaged) H += dense_pass<kHalf, kOut, kOut, kDenseStage>(p, dw, t, top, span_lo, shifts, vals, qi, wb, dst + H, 0, marked);
           else H += dense_pass<kHalf, kOut, kOut, kDenseCount>(p, dw, t, top, span_lo, shifts, vals, qi, wb, nullptr, 0, marked);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -1188,7 +1177,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
       const u64 total = __shfl(cur.cnt_incl, 63);  // all lanes take part in the shuffle
       if (closer && lane == 0) st_state(&p.cstate[chunk], (chunk == 0 ? kFlagInc : kFlagAgg) | total);
     }
-    if (have_prev) write_round<kGroups, kG, kHalf, kOut>(p, prev, s_excl[b], qi_all, top, span_lo, span_len, shifts, qw, marked);
+    if (have_prev) write_round<kGroups, kG, kHalf, kOut, kStaged>(p, prev, s_excl[b], qi_all, top, span_lo, span_len, shifts, qw, marked);
     prev = cur;
     have_prev = true;
     base = nbase;
@@ -1216,7 +1205,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(ScanParams p) {
     // this workgroup is through with the shared state: the count goes out before the last
     // entries are written, so that its round trip runs beside those stores
     if (p.self_clean && closer) finish_and_reset(p);
-    write_round<kGroups, kG, kHalf, kOut>(p, prev, s_excl[db], qi_all, top, span_lo, span_len, shifts, qw, marked);
+    write_round<kGroups, kG, kHalf, kOut, kStaged>(p, prev, s_excl[db], qi_all, top, span_lo, span_len, shifts, qw, marked);
   } else if (p.self_clean && closer) {
     finish_and_reset(p);
   }
@@ -1913,12 +1902,16 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   // index queues of two chunks
   const size_t lds = lds0 + (size_t)kWaves * rp.g * ((ordered_out ? (size_t)kSub : (size_t)kQcap) * 8 +
                                                       (size_t)kQcap * 2 * 2 * rp.groups);
-  auto kern = rp.g == kGSmall ? (half          ? scan_kernel<kGroupsSmall, kGSmall, true, false>
-                                 : ordered_out ? scan_kernel<kGroupsSmall, kGSmall, false, true>
-                                               : scan_kernel<kGroupsSmall, kGSmall, false, false>)
-                              : (half          ? scan_kernel<kGroupsBig, kGBig, true, false>
-                                 : ordered_out ? scan_kernel<kGroupsBig, kGBig, false, true>
-                                               : scan_kernel<kGroupsBig, kGBig, false, false>);
+  auto pick = [&](auto staged_c) {
+    constexpr bool st = decltype(staged_c)::value;
+    return rp.g == kGSmall ? (half          ? scan_kernel<kGroupsSmall, kGSmall, true, false, st>
+                              : ordered_out ? scan_kernel<kGroupsSmall, kGSmall, false, true, st>
+                                            : scan_kernel<kGroupsSmall, kGSmall, false, false, st>)
+                           : (half          ? scan_kernel<kGroupsBig, kGBig, true, false, st>
+                              : ordered_out ? scan_kernel<kGroupsBig, kGBig, false, true, st>
+                                            : scan_kernel<kGroupsBig, kGBig, false, false, st>);
+  };
+  auto kern = stage ? pick(std::true_type{}) : pick(std::false_type{});
   FDY_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const int slot = ordered_out ? FDY_PROF_SCAN_OUT : FDY_PROF_SCAN_MAIN;
   prof_begin(slot, stream);
