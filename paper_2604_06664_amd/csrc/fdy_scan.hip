@@ -110,6 +110,8 @@ struct ScanParams {
   const uint4* leaf;        // packed table, 64 bytes per 8 entries (null: not built)
   const uint4* cmid;        // compact copy of packed level 1, 32 bytes per node of 8 keys (null: not built)
   const uint4* cleaf;       // compact copy of the table, 32 bytes per 8 entries (null: not built)
+  const uint4* leafmap;     // ordered scan with output: 128 bytes per 8 entries, the compact line and
+                            // behind it the eight regions' new bases (null: not built)
   u64* cstate;     // [n_chunks] per-chunk totals / inclusive prefixes
   u32* done;       // workgroups that have finished (the last one resets the state behind it)
   u64* acc;        // fused scan + rebase: hits so far
@@ -274,6 +276,7 @@ struct Found {
   bool hit;
   u32 region;
   u64 offset;
+  const u64* nb;  // where the region's new base is read from (launches with a base map)
 };
 
 // Level 1's choice (the last key of the node that is not above w: its place, and the key itself in gb)
@@ -536,20 +539,30 @@ __device__ __forceinline__ void search(const ScanParams& p, const void* top_v, u
   // itself; so are all lines of small tables, which stay in L2 anyway.  Either way the whole
   // line is fetched at once.
   u64x2 e[N];
+  const u64* nbl[N];  // base of the new-base array to index with the region: the line's own copy, if any
+#pragma unroll
+  for (int c = 0; c < N; ++c) nbl[c] = nullptr;
   if (p.levels == 0) {
 #pragma unroll
     for (int c = 0; c < N; ++c) e[c] = *reinterpret_cast<const u64x2*>(&p.table[n[c]]);
   } else if (cleaf) {
+    // With a base map the compact line comes from a copy that keeps the eight regions' new
+    // bases in the same 128-byte memory line: the hit's new base, asked for a round trip later,
+    // is then found in the L2 that has just fetched the line (from the base map itself, 8 bytes
+    // at a random place of 8 MiB, three out of four such requests went on to the memory side).
+    const uint4* lm = kK16 ? p.leafmap : nullptr;
     uint4 cq[N][2];
 #pragma unroll
     for (int c = 0; c < N; ++c) {
-      cq[c][0] = cleaf[n[c] * 2];
-      cq[c][1] = cleaf[n[c] * 2 + 1];
+      cq[c][0] = lm ? lm[n[c] * 8] : cleaf[n[c] * 2];
+      cq[c][1] = lm ? lm[n[c] * 8 + 1] : cleaf[n[c] * 2 + 1];
+      nbl[c] = lm ? reinterpret_cast<const u64*>(lm + n[c] * 8 + 2) - n[c] * 8 : nullptr;
     }
     __builtin_amdgcn_sched_barrier(0);  // every chain's line is requested before the first is used
 #pragma unroll
     for (int c = 0; c < N; ++c) {
       const bool packed = pick_cline(cq[c], w[c], gb[c], n[c], e[c]);
+      if (!packed) nbl[c] = nullptr;
       // a marked line: the 64-byte copy, then the table
       if (!packed && !probe_wide_line(p.leaf, w[c], gb[c], n[c], e[c])) probe_line(p, w[c], n[c], e[c]);
       marked += (u32)__popcll(ballot(!packed));
@@ -600,6 +613,7 @@ __device__ __forceinline__ void search(const ScanParams& p, const void* top_v, u
     f[c].offset = w[c] - e[c].x;
     f[c].region = (u32)n[c];
     f[c].hit = f[c].offset < e[c].y;
+    f[c].nb = (nbl[c] ? nbl[c] : p.new_base) + n[c];
   }
 }
 
@@ -863,7 +877,7 @@ __device__ u64 dense_pass(const ScanParams& p, const u64 (&w)[kWpl], const Filt&
         if constexpr (kMode == kDenseStage)
           *reinterpret_cast<uint4*>(&dst[H + __popcll(b & lt)]) = *reinterpret_cast<const uint4*>(&o);
         if constexpr (kMode == kDenseWrite) store_reloc(p, dst_pos + H + __popcll(b & lt), o.word, o.region, o.offset);
-        if constexpr (kStash) qw[qi[q]] = p.new_base[o.region] + o.offset;
+        if constexpr (kStash) qw[qi[q]] = *f[0].nb + o.offset;
       }
       H += __popcll(b);
     }
@@ -902,7 +916,7 @@ __device__ __forceinline__ void run_rounds(const ScanParams& p, const void* top,
     // a hit's word in the LDS copy becomes its rebased value; the copy goes out as a whole later
     u64 nb[N];
 #pragma unroll
-    for (int r = 0; r < N; ++r) nb[r] = reg[R0 + r] != kMiss ? p.new_base[reg[R0 + r]] : 0;
+    for (int r = 0; r < N; ++r) nb[r] = reg[R0 + r] != kMiss ? *f[r].nb : 0;
 #pragma unroll
     for (int r = 0; r < N; ++r)
       if (reg[R0 + r] != kMiss) qw[at[r]] = nb[r] + off[R0 + r];
@@ -1409,6 +1423,23 @@ struct ScanInit {
   PreparedHeader hdr;
 };
 
+// Line i of the compact table copy together with the new bases of its eight regions, in one
+// 128-byte memory line (32 bytes of it unused): built per call of the ordered scan with output,
+// from that call's base map.
+__global__ void scan_leafmap_kernel(const uint4* cleaf, const u64* new_base, u32 n_alloc, u32 lines, uint4* out) {
+  const u32 i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= lines) return;
+  uint4* o = out + (u64)i * 8;
+  o[0] = cleaf[(u64)i * 2];
+  o[1] = cleaf[(u64)i * 2 + 1];
+  u64 nb[8];
+#pragma unroll
+  for (int h = 0; h < 8; ++h) nb[h] = (u64)i * 8 + h < n_alloc ? new_base[(u64)i * 8 + h] : 0;
+#pragma unroll
+  for (int h = 0; h < 4; ++h)
+    o[2 + h] = make_uint4((u32)nb[2 * h], (u32)(nb[2 * h] >> 32), (u32)nb[2 * h + 1], (u32)(nb[2 * h + 1] >> 32));
+}
+
 // Builds the level-0 keys and the packed mid levels, clears the chunk states and counters.
 __global__ void scan_init_kernel(ScanInit a) {
   const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1575,7 +1606,7 @@ struct TablePlan {
   u32 top_n, levels, f0_log2, sampled, bucket_log2, bucket16_log2;
   u32 mid_len[kMaxMid];
   u32 leaf_lines, cmid_nodes;
-  size_t off_top, off_bst, off_top16, off_bst16, off_mid[kMaxMid], off_leaf, off_cleaf, off_cmid, bytes;
+  size_t off_top, off_bst, off_top16, off_bst16, off_mid[kMaxMid], off_leaf, off_cleaf, off_cmid, off_leafmap, bytes;
 };
 
 bool plan_table(u32 n_alloc, TablePlan* pl) {
@@ -1643,6 +1674,9 @@ bool plan_table(u32 n_alloc, TablePlan* pl) {
   off += align256((size_t)pl->leaf_lines * 32);
   pl->off_cmid = off;
   off += align256((size_t)pl->cmid_nodes * 32);
+  // the compact lines with a call's base map beside them (written by every ordered scan with output)
+  pl->off_leafmap = off;
+  off += align256((size_t)pl->leaf_lines * 128);
   pl->bytes = off;
   return true;
 }
@@ -1874,6 +1908,14 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   p.leaf = a.leaf;
   p.cmid = a.cmid;
   p.cleaf = a.cleaf;
+  p.leafmap = nullptr;
+  if (ordered_out && tp.leaf_lines) {
+    uint4* lm = (uint4*)(tb + tp.off_leafmap);
+    hipLaunchKernelGGL(scan_leafmap_kernel, dim3((tp.leaf_lines + 255) / 256), dim3(256), 0, stream,
+                       (const uint4*)a.cleaf, (const u64*)d_new_base, n_alloc, tp.leaf_lines, lm);
+    FDY_HIP_TRY(hipGetLastError());
+    p.leafmap = lm;
+  }
   p.stage = (fdy_reloc*)stage;
   p.n_sub = rp.n_sub;
   p.top_n = tp.top_n;
