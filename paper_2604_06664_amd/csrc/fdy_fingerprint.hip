@@ -148,10 +148,60 @@ __device__ void rank_firsts(u32 G, u32* template_id, u32* tmpl_graph, u32* n_tem
   if (tid == 0) *n_templates = s_carry;
 }
 
+// At most one graph per thread (G <= 1024): keys, firsts and ranks stay in LDS and registers, and
+// the outputs are written once; the only round trips to memory are the load of the keys and the
+// stores of the results.  (The general form below goes through template_id in memory between its
+// steps, which is four more round trips: as long as everything else this launch does.)
+__device__ void group_small(const u64* keys, u32 G, u32* template_id, u32* tmpl_graph, u32* n_templates,
+                            u32* table /* LDS, at least twice the graphs */) {
+  __shared__ u64 s_keys[1024];
+  __shared__ u32 s_rank[1024];
+  __shared__ u32 s_cnt[17];
+  const u32 g = threadIdx.x, l = lane_id(), w = g >> 6;
+  u32 slots = 64;
+  while (slots < 2 * G) slots <<= 1;
+  const u32 mask = slots - 1;
+  for (u32 i = g; i < slots; i += 1024) table[i] = kEmpty;
+  if (g < G) s_keys[g] = __hip_atomic_load(&keys[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  auto key_at = [&](u32 h) { return s_keys[h]; };
+  if (g < G) table_insert(table, mask, key_at, g);
+  __syncthreads();
+  const u32 first = g < G ? table_first(table, mask, key_at, g) : kEmpty;
+  const bool is_first = g < G && first == g;
+  const u64 b = ballot(is_first);
+  if (l == 0) s_cnt[w] = __popcll(b);
+  __syncthreads();
+  if (w == 0) {
+    const u32 x = l < 16 ? s_cnt[l] : 0;
+    u32 xi = x;
+#pragma unroll
+    for (int d = 1; d < 16; d <<= 1) {
+      const u32 o = __shfl_up(xi, d);
+      if (l >= (u32)d) xi += o;
+    }
+    if (l < 16) s_cnt[l] = xi - x;
+    if (l == 15) s_cnt[16] = xi;
+  }
+  __syncthreads();
+  if (is_first) {
+    const u32 rank = s_cnt[w] + __popcll(b & lanemask_lt());
+    s_rank[g] = rank;
+    if (tmpl_graph) tmpl_graph[rank] = g;
+  }
+  __syncthreads();
+  if (g < G) template_id[g] = s_rank[first];
+  if (g == 0) *n_templates = s_cnt[16];
+}
+
 // The whole grouping by one workgroup, table in LDS: up to kLdsGraphs graphs.
 constexpr u32 kLdsGraphs = 8192, kLdsSlots = 2 * kLdsGraphs;
 __device__ void group_in_lds(const u64* keys, u32 G, u32* template_id, u32* tmpl_graph, u32* n_templates,
                              u32* table /* LDS, kLdsSlots */) {
+  if (G <= 1024) {
+    group_small(keys, G, template_id, tmpl_graph, n_templates, table);
+    return;
+  }
   const u32 tid = threadIdx.x;
   u32 slots = 64;  // at least twice the graphs
   while (slots < 2 * G) slots <<= 1;
