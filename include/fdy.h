@@ -207,8 +207,10 @@ int fdy_layout_replay(const fdy_alloc* h_recorded, uint32_t n, uint64_t recorded
  *                    written and FDY_ST_CAPACITY is raised)
  *   d_workspace      device, 256-byte aligned, at least fdy_scan_workspace_bytes() bytes;
  *                    contents on entry are irrelevant, contents on exit are unspecified.
- *                    The size is the search hierarchy built from the table (about 14 bytes
- *                    per allocation beyond 16,384 of them) and 8 bytes per 4,096 words;
+ *                    The size is the search hierarchy built from the table (about 30 bytes
+ *                    per allocation beyond 16,384 of them: packed copies of the table, and
+ *                    room for one new base per allocation beside them, which
+ *                    fdy_scan_pointers_rebase fills per call) and 8 bytes per 4,096 words;
  *                    0 is returned for n_words beyond the limit above.
  *                    Optional staging area: where more than 3 words in 8 lie inside the
  *                    table's span (word-dense inputs), the hits of such a stretch are either

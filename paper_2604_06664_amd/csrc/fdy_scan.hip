@@ -64,6 +64,23 @@
 // the array as 32-bit units and treats every unit index as a position whose value is that
 // unit and the next one; only the loader and the numbering of positions differ.
 //
+// Variant with a rebased output (fdy_scan_pointers_rebase; kOut): the same ordered scan also
+// writes every word, hits rebased, to a second array, so that an archive whose graphs are
+// their own templates needs no second pass over the words (Section 4.2.2: every rank takes the
+// same captured blobs and differs only in its layout).  A wave keeps the sub-tiles of its
+// group in LDS as loaded, queues only the candidates' positions, writes new_base[region] +
+// offset over each hit's copy and streams the copy out with the 16-byte stores a copy would
+// use (scattered 8-byte fix-ups into lines that have left L2 cost a third more time).  The
+// LDS for the copies comes from the level-0 keys, which this variant keeps as 16-bit
+// distances inside their bucket.  A small launch ahead of the scan lays each compact table line
+// and the new bases of its eight regions side by side in one 128-byte record, so that a hit's
+// new base is a second request to the line the search has just fetched.
+//
+// The table's part of all this (hierarchy, packed copies) depends on the table alone and can
+// be built once per archive (fdy_scan_table_prepare); the per-call state (ticket, chunk
+// states, counters) then lives in the same buffer and is zeroed again by the last workgroup
+// to finish, so that a scan is one launch.
+//
 // Tickets are handed out in increasing order and a wave only ever waits for chunks with
 // smaller numbers, which are already owned by resident workgroups; the wait is bounded by a
 // spin limit after which FDY_ST_SPIN is raised and the kernel still terminates.
