@@ -1443,18 +1443,21 @@ struct ScanInit {
 // Line i of the compact table copy together with the new bases of its eight regions, in one
 // 128-byte memory line (32 bytes of it unused): built per call of the ordered scan with output,
 // from that call's base map.
+// One thread per 16-byte piece, so that reads and writes are whole lines.
 __global__ void scan_leafmap_kernel(const uint4* cleaf, const u64* new_base, u32 n_alloc, u32 lines, uint4* out) {
-  const u32 i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= lines) return;
-  uint4* o = out + (u64)i * 8;
-  o[0] = cleaf[(u64)i * 2];
-  o[1] = cleaf[(u64)i * 2 + 1];
-  u64 nb[8];
-#pragma unroll
-  for (int h = 0; h < 8; ++h) nb[h] = (u64)i * 8 + h < n_alloc ? new_base[(u64)i * 8 + h] : 0;
-#pragma unroll
-  for (int h = 0; h < 4; ++h)
-    o[2 + h] = make_uint4((u32)nb[2 * h], (u32)(nb[2 * h] >> 32), (u32)nb[2 * h + 1], (u32)(nb[2 * h + 1] >> 32));
+  const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  const u64 i = t >> 3;
+  const u32 piece = (u32)t & 7;
+  if (i >= lines || piece >= 6) return;
+  uint4 v;
+  if (piece < 2) {
+    v = cleaf[i * 2 + piece];
+  } else {
+    const u64 r = i * 8 + (piece - 2) * 2;  // this piece's two regions
+    const u64 a = r < n_alloc ? new_base[r] : 0, b = r + 1 < n_alloc ? new_base[r + 1] : 0;
+    v = make_uint4((u32)a, (u32)(a >> 32), (u32)b, (u32)(b >> 32));
+  }
+  out[t] = v;
 }
 
 // Builds the level-0 keys and the packed mid levels, clears the chunk states and counters.
@@ -1928,7 +1931,7 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   p.leafmap = nullptr;
   if (ordered_out && tp.leaf_lines) {
     uint4* lm = (uint4*)(tb + tp.off_leafmap);
-    hipLaunchKernelGGL(scan_leafmap_kernel, dim3((tp.leaf_lines + 255) / 256), dim3(256), 0, stream,
+    hipLaunchKernelGGL(scan_leafmap_kernel, dim3((u32)(((u64)tp.leaf_lines * 8 + 255) / 256)), dim3(256), 0, stream,
                        (const uint4*)a.cleaf, (const u64*)d_new_base, n_alloc, tp.leaf_lines, lm);
     FDY_HIP_TRY(hipGetLastError());
     p.leafmap = lm;
