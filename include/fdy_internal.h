@@ -21,6 +21,8 @@ enum {
   FDY_TUNE_SCAN_SPIN_LIMIT = 2, /* polls of a predecessor tile before giving up            */
   FDY_TUNE_MAT_MAP_GROUP = 3,     /* base maps per materialize workgroup, 0 = automatic      */
   FDY_TUNE_SCAN_SMALL_LOG2 = 4, /* inputs below 2^this sub-tiles use the small-chunk scan   */
+  FDY_TUNE_MAT_SELF_WGS = 5,    /* materialize launches of up to this many workgroups       *
+                                 * resolve their tiles themselves (no prep launch); 0: none */
   FDY_TUNE_COUNT = 8
 };
 

@@ -30,6 +30,12 @@
 //                            streams the tile out with coalesced stores.  Templates,
 //                            relocation lists and base maps are re-read per group from L2 /
 //                            Infinity Cache; only the output is compulsory HBM traffic.
+//   small launches           (every workgroup of main resident at once): no prep launch at
+//                            all; each workgroup of main resolves its own tile first, and
+//                            extra blocks of the same launch write the dimensions and check
+//                            the short lists.  Same results, one launch less.
+// The order of every list is verified on the way (FDY_ST_BAD_ORDER): the relocation lists
+// where main reads them, the short lists by blocks of the prep launch (or of main).
 #include <mutex>
 
 #include "fdy_device.hpp"
@@ -78,12 +84,13 @@ struct MatParams {
 
 // Word and node counts of output graph g (those of its template).  False, with zero counts, if
 // its template or the template's source graph is out of range or has 2^32 words or more.
-__device__ __forceinline__ bool graph_sizes(const MatParams& p, u32 g, u64& nw, u64& nn) {
+__device__ __forceinline__ bool graph_sizes(const MatParams& p, u32 g, u64& nw, u64& nn, u32* src_graph = nullptr) {
   const fdy_mat_desc& d = p.d;
   nw = 0;
   nn = 0;
   const u32 t = d.graph_tmpl[g];
   const u32 s = t < d.n_templates ? d.tmpl_graph[t] : 0xffffffffu;
+  if (src_graph) *src_graph = s;
   if (s >= d.n_src_graphs) return false;
   nw = d.src_word_off[s + 1] - d.src_word_off[s];
   if (p.out_dims) nn = d.src_node_off[s + 1] - d.src_node_off[s];
@@ -326,6 +333,77 @@ __device__ __forceinline__ void stage_tile(u64* buf, const u64* src, u64 src_wor
   if (tid == 0 && head + 2 * pairs < n) buf[n - 1] = src[n - 1];
 }
 
+// Order of the short lists (overrides, grid overrides, rank patches): every entry against the
+// one before it, all lists of a kind in one sweep over their concatenation; where the key does
+// not ascend, a new list must begin.  The relocation lists, which are long, are checked where
+// they are read anyway (mat_main_kernel).
+__device__ __forceinline__ void check_lists(const MatParams& p, u32 cb, u32 n_cb) {
+  const fdy_mat_desc& d = p.d;
+  const u64 first = (u64)cb * 256 + threadIdx.x, stride = (u64)n_cb * 256;
+  bool disorder = false;
+  auto sweep = [&](auto key, const u64* off, u32 n_lists) {
+    if (!n_lists) return;
+    const u64 lo = off[0], hi = off[n_lists];
+    for (u64 i = lo + 1 + first; i < hi; i += stride) {
+      if (key(i - 1) < key(i)) continue;
+      u32 a = 0, b = n_lists;  // the last list that begins at or before entry i
+      while (b - a > 1) {
+        const u32 mid = a + (b - a) / 2;
+        if (off[mid] <= i) a = mid;
+        else b = mid;
+      }
+      if (off[a] != i) disorder = true;
+    }
+  };
+  const fdy_ovr32* ovr = d.ovr;
+  sweep([&](u64 i) { return ovr[i].byte_off; }, d.ovr_off, d.n_graphs);
+  if (p.out_dims) {
+    const fdy_grid_ovr* govr = d.govr;
+    sweep([&](u64 i) { return govr[i].node; }, d.govr_off, d.n_graphs);
+  }
+  if (d.map_rank) {
+    const fdy_patch* patch = d.patch;
+    sweep([&](u64 i) { return patch[i].word; }, d.patch_off, d.n_templates * d.n_ranks);
+  }
+  if (disorder) raise_status(p.d_status, FDY_ST_BAD_ORDER);
+}
+
+// Thread i: launch dimensions of output node i.
+__device__ __forceinline__ void write_dims(const MatParams& p, const PrepView& v, u64 i) {
+  const fdy_mat_desc& d = p.d;
+  if (!v.ok) return;
+  if (i >= d.out_nodes_total) return;
+  // largest g with out_node_off[g] <= i
+  const u64* off = v.out_node_off;
+  u32 lo = 0, hi = d.n_graphs;  // answer in [lo, hi)
+  while (hi - lo > 1) {
+    const u32 mid = lo + (hi - lo) / 2;
+    if (off[mid] <= i) lo = mid;
+    else hi = mid;
+  }
+  const u32 g = lo;
+  const u32 n = (u32)(i - off[g]);
+  const u32 s = d.tmpl_graph[d.graph_tmpl[g]];
+  const fdy_node nd = d.src_nodes[d.src_node_off[s] + n];
+  u32 gx = nd.grid[0], gy = nd.grid[1], gz = nd.grid[2];
+  // grid override of this node, if any (list ascending by node)
+  u64 a = d.govr_off[g], b = d.govr_off[g + 1];
+  while (a < b) {
+    const u64 mid = a + (b - a) / 2;
+    if (d.govr[mid].node < n) a = mid + 1;
+    else b = mid;
+  }
+  if (a < d.govr_off[g + 1] && d.govr[a].node == n) {
+    gx = d.govr[a].grid[0];
+    gy = d.govr[a].grid[1];
+    gz = d.govr[a].grid[2];
+  }
+  uint2* o = reinterpret_cast<uint2*>(p.out_dims + i * 6);
+  o[0] = make_uint2(gx, gy);
+  o[1] = make_uint2(gz, nd.block[0]);
+  o[2] = make_uint2(nd.block[1], nd.block[2]);
+}
+
 // One workgroup per (tile, group of consecutive base maps).  What does not depend on the map
 // is fetched once per workgroup: the tile entry, the template tile (LDS) and this thread's
 // share of the tile's relocation entries (registers; the slice holds at most kMatTile
@@ -337,14 +415,176 @@ constexpr int kMatPre = kMatTile / kMatBlock;
 constexpr int kMatStore = kMatTile / (2 * kMatBlock);  // 16-byte chunks per thread
 constexpr int kMatOvrPre = 2;                          // overrides of the tile a thread keeps in registers
 
-__global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
+//
+// kSelf (small launches: every workgroup resident at once, at most kSelfGraphs output graphs):
+// no tile table exists; the workgroup works out its own tile first (per-graph prefix sums in
+// LDS, then its slices of the lists, one cooperative search per wave), and further blocks of
+// the same launch write the launch dimensions and check the order of the short lists.  That
+// is mat_prep_tiles_kernel's work without its launch: the model-shaped archives are bound by
+// launches, and an extra 4 us of prologue in workgroups that all run side by side is less than
+// the 10 us the launch costs.
+constexpr u32 kSelfGraphs = 1000;   // offsets of up to 1,024 graphs fit the tile buffer
+constexpr u32 kSelfMaxGroup = 8;    // most base maps per workgroup in this mode
+
+// Per-graph sums of a kSelf block, in the 16 KiB tile buffer: tile_off u32[1024] | source graph
+// u32[1024] | out_word_off (or, for the blocks that write dimensions, out_node_off) u64[1024].
+// Returns whether the totals match what the caller sized the launch for; `bad` reports an
+// output graph without a valid template.
+struct SelfSums {
+  u32* tile_off;
+  u32* src;
+  u64* off;
+  u32 n_tiles;
+  bool ok, bad;
+};
+__device__ __forceinline__ SelfSums self_sums(const MatParams& p, u64* buf, u64* s_buf, bool nodes) {
+  SelfSums r;
+  r.tile_off = reinterpret_cast<u32*>(buf);
+  r.src = r.tile_off + 1024;
+  r.off = buf + 1024;
+  const u32 G = p.d.n_graphs, tid = threadIdx.x;
+  constexpr u32 kPer = 1024 / kMatBlock;
+  u64 nw[kPer], nn[kPer], sum_w = 0, sum_n = 0, sum_t = 0;
+  u32 from[kPer];
+  bool bad = false;
+#pragma unroll
+  for (u32 i = 0; i < kPer; ++i) {
+    const u32 g = tid * kPer + i;
+    nw[i] = 0;
+    nn[i] = 0;
+    from[i] = 0;
+    if (g < G && !graph_sizes(p, g, nw[i], nn[i], &from[i])) bad = true;
+    sum_w += nw[i];
+    sum_n += nn[i];
+    sum_t += (nw[i] + kMatTile - 1) / kMatTile;
+  }
+  u64 tw, tn, tt;
+  u64 ew = block_excl_scan(sum_w, s_buf, tw);
+  u64 en = block_excl_scan(sum_n, s_buf, tn);
+  u64 et = block_excl_scan(sum_t, s_buf, tt);
+#pragma unroll
+  for (u32 i = 0; i < kPer; ++i) {
+    const u32 g = tid * kPer + i;
+    if (g < G) {
+      r.tile_off[g] = (u32)et;
+      r.src[g] = from[i];
+      r.off[g] = nodes ? en : ew;
+    }
+    ew += nw[i];
+    en += nn[i];
+    et += (nw[i] + kMatTile - 1) / kMatTile;
+  }
+  if (tid == 0) {
+    r.tile_off[G] = (u32)tt;
+    r.off[G] = nodes ? tn : tw;
+  }
+  r.ok = totals_ok(p, tw, tn, tt);
+  r.n_tiles = r.ok ? (u32)tt : 0u;
+  r.bad = __syncthreads_or(bad);
+  return r;
+}
+
+template <bool kSelf>
+__global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p, u32 n_tile_blocks, u32 nb_dims) {
   __shared__ __align__(16) u64 buf[kMatTile];
+  __shared__ u64 s_buf[kSelf ? 17 : 1];
+  __shared__ u32 s_found[kSelf ? 4 + 2 * kSelfMaxGroup : 1];
   typedef u64 v2u64 __attribute__((ext_vector_type(2)));
   const fdy_mat_desc& d = p.d;
   const u32 j = blockIdx.x, tid = threadIdx.x;
   const u32 m0 = blockIdx.y * p.map_group;
   const u32 m1 = min(m0 + p.map_group, d.n_maps);
-  const MatTile ent = p.ws.tiles[j];
+  MatTile ent;
+  if constexpr (kSelf) {
+    if (j >= n_tile_blocks) {  // launch dimensions, then the order of the short lists
+      if (blockIdx.y) return;
+      if (j < n_tile_blocks + nb_dims) {
+        const SelfSums q = self_sums(p, buf, s_buf, true);
+        PrepView v;
+        v.out_word_off = nullptr;
+        v.out_node_off = q.off;
+        v.tile_off = nullptr;
+        v.n_tiles = q.n_tiles;
+        v.ok = q.ok ? 1u : 0u;
+        write_dims(p, v, (u64)(j - n_tile_blocks) * kMatBlock + tid);
+      } else {
+        check_lists(p, j - n_tile_blocks - nb_dims, gridDim.x - n_tile_blocks - nb_dims);
+      }
+      return;
+    }
+    const SelfSums q = self_sums(p, buf, s_buf, false);
+    if (j == 0 && blockIdx.y == 0) {  // what the prep launch reports
+      if (q.bad) raise_status(p.d_status, FDY_ST_BAD_INDEX);
+      if (tid == 0 && !q.ok) raise_status(p.d_status, FDY_ST_BAD_SIZE);
+    }
+    if (j >= q.n_tiles) return;
+    // the tile's graph: the last one whose first tile is not behind tile j
+    u32 glo = 0, ghi = d.n_graphs;  // answer in [glo, ghi)
+    while (ghi - glo > 1) {
+      const u32 mid = glo + (ghi - glo) / 2;
+      if (q.tile_off[mid] <= j) glo = mid;
+      else ghi = mid;
+    }
+    const u32 g = glo, s_graph = q.src[g];
+    const u32 k0 = (j - q.tile_off[g]) * (u32)kMatTile;
+    const u64 out_word = q.off[g] + k0;
+    const u32 nw = (u32)(q.off[g + 1] - q.off[g]);  // a template stays below 2^32 words
+    const u32 n_here = min(nw - k0, (u32)kMatTile);
+    const bool last = k0 + n_here == nw;
+    const u32 t = d.graph_tmpl[g];
+    const u64 src_word = d.src_word_off[s_graph] + k0;
+    const u32 rl0 = (u32)d.src_reloc_off[s_graph], rl1 = (u32)d.src_reloc_off[s_graph + 1];
+    const u32 ov0 = (u32)d.ovr_off[g], ov1 = (u32)d.ovr_off[g + 1];
+    __syncthreads();  // everyone has read the sums; the buffer is free for the tile
+    {
+      // one cooperative search per wave: where the tile's slices of the template's relocation
+      // list and of the graph's override list begin and end; then the patch slices of the
+      // group's maps, two searches each
+      const u32 w = tid >> 6;
+      const fdy_reloc* relocs = d.relocs;
+      const fdy_ovr32* ovr = d.ovr;
+      u32 r = 0;
+      if (w == 0) r = wave_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, rl0, rl1, src_word);
+      if (w == 1) r = last ? rl1 : wave_lower_bound([&](u32 i) { return (u64)relocs[i].word; }, rl0, rl1, src_word + n_here);
+      if (w == 2) r = wave_lower_bound([&](u32 i) { return (u64)ovr[i].byte_off; }, ov0, ov1, (u64)k0 * 8);
+      if (w == 3) r = last ? ov1 : wave_lower_bound([&](u32 i) { return (u64)ovr[i].byte_off; }, ov0, ov1, ((u64)k0 + n_here) * 8);
+      if (lane_id() == 0) s_found[w] = r;
+      if (d.map_rank) {
+        const fdy_patch* patch = d.patch;
+        for (u32 e = w; e < 2 * (m1 - m0); e += kMatBlock / 64) {
+          const u32 rank = d.map_rank[m0 + (e >> 1)];
+          u32 f = (e & 1) ? 0u : 0xffffffffu;  // a bad rank: the slice that mat_main takes for "none, and flag it"
+          if (rank < d.n_ranks) {
+            const u64 row = (u64)t * d.n_ranks + rank;
+            const u32 p0 = (u32)d.patch_off[row], p1 = (u32)d.patch_off[row + 1];
+            f = wave_lower_bound([&](u32 i) { return (u64)patch[i].word; }, p0, p1, (u64)k0 + ((e & 1) ? n_here : 0u));
+          }
+          if (lane_id() == 0) s_found[4 + e] = f;
+        }
+      }
+    }
+    __syncthreads();
+    ent.src_word = src_word;
+    ent.out_word = out_word;
+    ent.n_words = n_here;
+    ent.g = g;
+    ent.tmpl = t;
+    ent.k0 = k0;
+    ent.reloc_lo = s_found[0];
+    ent.reloc_hi = s_found[1];
+    ent.ovr_lo = s_found[2];
+    ent.ovr_hi = s_found[3];
+    ent.reloc_seg = rl0;
+    if (ent.reloc_hi < ent.reloc_lo) ent.reloc_hi = ent.reloc_lo;  // (a list out of order can cross them)
+    if (ent.ovr_hi < ent.ovr_lo) ent.ovr_hi = ent.ovr_lo;
+    if (ent.reloc_hi - ent.reloc_lo > n_here) {  // strictly ascending: at most one entry per word
+      ent.reloc_hi = ent.reloc_lo + n_here;
+      if (blockIdx.y == 0) raise_status(p.d_status, FDY_ST_BAD_ORDER);
+    }
+    if (k0 == 0 && ent.reloc_lo != rl0 && blockIdx.y == 0) raise_status(p.d_status, FDY_ST_BAD_INDEX);
+  } else {
+    ent = p.ws.tiles[j];
+  }
   const u32 n = ent.n_words;
   if (n == 0) return;
   const u64* src = d.src_words + ent.src_word;
@@ -352,7 +592,7 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
   // too large to stay in the L2s anyway (4,096 tiles = 64 MiB), are loaded non-temporally, so
   // that the base map keeps its place in L2 for the gathers (config 4: 0.51 -> 0.47 ms); small
   // archives stay cached for whoever reads them next.
-  const bool once = gridDim.y == 1 && gridDim.x >= 4096;
+  const bool once = gridDim.y == 1 && n_tile_blocks >= 4096;
   stage_tile(buf, src, ent.src_word, n, tid, once);  // c1
   bool bad = false, disorder = false;
   u32 rk[kMatPre], rr[kMatPre];
@@ -424,8 +664,13 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
     }
   }
   auto patch_slice = [&](u32 m) {  // the slice of map m's rank inside this tile; empty for a bad rank
-    const u32 rk_m = d.map_rank[m];
-    return rk_m < d.n_ranks ? p.ws.tile_patch[(u64)j * d.n_ranks + rk_m] : make_uint2(0xffffffffu, 0);
+    if constexpr (kSelf) {
+      const u32 lo = s_found[4 + 2 * (m - m0)], hi = s_found[5 + 2 * (m - m0)];
+      return make_uint2(lo, lo == 0xffffffffu ? 0u : max(hi, lo));
+    } else {
+      const u32 rk_m = d.map_rank[m];
+      return rk_m < d.n_ranks ? p.ws.tile_patch[(u64)j * d.n_ranks + rk_m] : make_uint2(0xffffffffu, 0);
+    }
   };
   // this thread's patch entry of a slice (none: word index all ones)
   auto patch_entry = [&](uint2 pr) {
@@ -535,77 +780,6 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p) {
   }
   if (bad) raise_status(p.d_status, FDY_ST_BAD_INDEX);
   if (disorder) raise_status(p.d_status, FDY_ST_BAD_ORDER);
-}
-
-// Order of the short lists (overrides, grid overrides, rank patches): every entry against the
-// one before it, all lists of a kind in one sweep over their concatenation; where the key does
-// not ascend, a new list must begin.  The relocation lists, which are long, are checked where
-// they are read anyway (mat_main_kernel).
-__device__ __forceinline__ void check_lists(const MatParams& p, u32 cb, u32 n_cb) {
-  const fdy_mat_desc& d = p.d;
-  const u64 first = (u64)cb * 256 + threadIdx.x, stride = (u64)n_cb * 256;
-  bool disorder = false;
-  auto sweep = [&](auto key, const u64* off, u32 n_lists) {
-    if (!n_lists) return;
-    const u64 lo = off[0], hi = off[n_lists];
-    for (u64 i = lo + 1 + first; i < hi; i += stride) {
-      if (key(i - 1) < key(i)) continue;
-      u32 a = 0, b = n_lists;  // the last list that begins at or before entry i
-      while (b - a > 1) {
-        const u32 mid = a + (b - a) / 2;
-        if (off[mid] <= i) a = mid;
-        else b = mid;
-      }
-      if (off[a] != i) disorder = true;
-    }
-  };
-  const fdy_ovr32* ovr = d.ovr;
-  sweep([&](u64 i) { return ovr[i].byte_off; }, d.ovr_off, d.n_graphs);
-  if (p.out_dims) {
-    const fdy_grid_ovr* govr = d.govr;
-    sweep([&](u64 i) { return govr[i].node; }, d.govr_off, d.n_graphs);
-  }
-  if (d.map_rank) {
-    const fdy_patch* patch = d.patch;
-    sweep([&](u64 i) { return patch[i].word; }, d.patch_off, d.n_templates * d.n_ranks);
-  }
-  if (disorder) raise_status(p.d_status, FDY_ST_BAD_ORDER);
-}
-
-// Thread i: launch dimensions of output node i.
-__device__ __forceinline__ void write_dims(const MatParams& p, const PrepView& v, u64 i) {
-  const fdy_mat_desc& d = p.d;
-  if (!v.ok) return;
-  if (i >= d.out_nodes_total) return;
-  // largest g with out_node_off[g] <= i
-  const u64* off = v.out_node_off;
-  u32 lo = 0, hi = d.n_graphs;  // answer in [lo, hi)
-  while (hi - lo > 1) {
-    const u32 mid = lo + (hi - lo) / 2;
-    if (off[mid] <= i) lo = mid;
-    else hi = mid;
-  }
-  const u32 g = lo;
-  const u32 n = (u32)(i - off[g]);
-  const u32 s = d.tmpl_graph[d.graph_tmpl[g]];
-  const fdy_node nd = d.src_nodes[d.src_node_off[s] + n];
-  u32 gx = nd.grid[0], gy = nd.grid[1], gz = nd.grid[2];
-  // grid override of this node, if any (list ascending by node)
-  u64 a = d.govr_off[g], b = d.govr_off[g + 1];
-  while (a < b) {
-    const u64 mid = a + (b - a) / 2;
-    if (d.govr[mid].node < n) a = mid + 1;
-    else b = mid;
-  }
-  if (a < d.govr_off[g + 1] && d.govr[a].node == n) {
-    gx = d.govr[a].grid[0];
-    gy = d.govr[a].grid[1];
-    gz = d.govr[a].grid[2];
-  }
-  uint2* o = reinterpret_cast<uint2*>(p.out_dims + i * 6);
-  o[0] = make_uint2(gx, gy);
-  o[1] = make_uint2(gz, nd.block[0]);
-  o[2] = make_uint2(nd.block[1], nd.block[2]);
 }
 
 // Everything that only needs the per-graph prefix sums, in one launch (these are small and
@@ -802,6 +976,25 @@ static int materialize_launch(const fdy_mat_desc* h_desc, uint64_t* d_out_words,
   hipStream_t stream = (hipStream_t)hip_stream;
   (void)hipGetLastError();  // drop any stale error left by earlier, unrelated runtime calls
 
+  // Base maps per workgroup.  Measured on MI355X, groups above 2 (4 with rank patches) lose
+  // more to the coarser tail of the launch than they save in repeated loads.
+  u32 mg = (u32)fdy__tune_get(FDY_TUNE_MAT_MAP_GROUP);
+  if (mg == 0) mg = d.map_rank ? 4 : 2;
+  p.map_group = mg < d.n_maps ? mg : d.n_maps;
+  const u32 n_groups = (d.n_maps + p.map_group - 1) / p.map_group;
+  const u32 nb_dims_all = (d_out_dims && d.out_nodes_total) ? (u32)((d.out_nodes_total + 255) / 256) : 0;
+  // A launch small enough that all its workgroups run side by side resolves its tiles itself.
+  const u64 self_limit = (u64)fdy__tune_get(FDY_TUNE_MAT_SELF_WGS);
+  if (d.n_graphs <= kSelfGraphs && p.map_group <= kSelfMaxGroup && p.ws.max_tiles &&
+      (u64)p.ws.max_tiles * n_groups <= self_limit) {
+    prof_begin(FDY_PROF_MAT_MAIN, stream);
+    hipLaunchKernelGGL(mat_main_kernel<true>, dim3(p.ws.max_tiles + nb_dims_all + kCheckBlocks, n_groups),
+                       dim3(kMatBlock), 0, stream, p, p.ws.max_tiles, nb_dims_all);
+    prof_end(FDY_PROF_MAT_MAIN, stream);
+    FDY_HIP_TRY(hipGetLastError());
+    return FDY_OK;
+  }
+
   const bool own_sums = d.n_graphs <= kOwnSumsMax;
   if (!own_sums) {
     prof_begin(FDY_PROF_MAT_PREP_GRAPHS, stream);
@@ -825,13 +1018,8 @@ static int materialize_launch(const fdy_mat_desc* h_desc, uint64_t* d_out_words,
   }
   if (p.ws.max_tiles) {
     prof_begin(FDY_PROF_MAT_MAIN, stream);
-    // Base maps per workgroup.  Measured on MI355X, groups above 2 (4 with rank patches) lose
-    // more to the coarser tail of the launch than they save in repeated loads.
-    u32 mg = (u32)fdy__tune_get(FDY_TUNE_MAT_MAP_GROUP);
-    if (mg == 0) mg = d.map_rank ? 4 : 2;
-    p.map_group = mg < d.n_maps ? mg : d.n_maps;
-    const u32 n_groups = (d.n_maps + p.map_group - 1) / p.map_group;
-    hipLaunchKernelGGL(mat_main_kernel, dim3(p.ws.max_tiles, n_groups), dim3(kMatBlock), 0, stream, p);
+    hipLaunchKernelGGL(mat_main_kernel<false>, dim3(p.ws.max_tiles, n_groups), dim3(kMatBlock), 0, stream, p,
+                       p.ws.max_tiles, 0u);
     prof_end(FDY_PROF_MAT_MAIN, stream);
     FDY_HIP_TRY(hipGetLastError());
   }
