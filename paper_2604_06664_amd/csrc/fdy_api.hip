@@ -13,7 +13,7 @@ int g_tune[FDY_TUNE_COUNT] = {
     /* SCAN_SPIN_LIMIT */ 1 << 20,
     /* MAT_MAP_GROUP     */ 0,
     /* SCAN_SMALL_LOG2 */ 12,
-    /* MAT_SELF_WGS    */ 1280,
+    /* MAT_SELF_WGS    */ 1024,
     0, 0};
 const int g_tune_lo[FDY_TUNE_COUNT] = {1, 1, 0, 0, 0, 0, 0, 0};
 const int g_tune_hi[FDY_TUNE_COUNT] = {14, 16, 1 << 30, 64, 31, 1 << 30, 0, 0};

@@ -333,6 +333,50 @@ __device__ __forceinline__ void stage_tile(u64* buf, const u64* src, u64 src_wor
   if (tid == 0 && head + 2 * pairs < n) buf[n - 1] = src[n - 1];
 }
 
+// The same in two steps, so that other work can sit between the loads and their use (the
+// self-resolving form of the main kernel searches its slices meanwhile).
+constexpr int kTileChunks = kMatTile / (2 * kMatBlock);
+struct TileRegs {
+  u64x2 v[kTileChunks];
+  u64 first, last;
+};
+__device__ __forceinline__ void tile_load(TileRegs& r, const u64* src, u64 src_word, u32 n, u32 tid, bool once) {
+  typedef u64 v2u64 __attribute__((ext_vector_type(2)));
+  const u32 head = (u32)(src_word & 1);  // words before 16-byte alignment (n >= 1 here)
+  const u32 pairs = (n - head) >> 1;
+  r.first = r.last = 0;
+  if (tid == 0 && head) r.first = src[0];
+#pragma unroll
+  for (int c = 0; c < kTileChunks; ++c) {
+    const u32 i = tid + (u32)c * kMatBlock;
+    r.v[c] = u64x2{0, 0};
+    if (i < pairs) {
+      if (once) {
+        const v2u64 v = __builtin_nontemporal_load(reinterpret_cast<const v2u64*>(src + head + 2 * i));
+        r.v[c].x = v.x;
+        r.v[c].y = v.y;
+      } else {
+        r.v[c] = *reinterpret_cast<const u64x2*>(src + head + 2 * i);
+      }
+    }
+  }
+  if (tid == 0 && head + 2 * pairs < n) r.last = src[n - 1];
+}
+__device__ __forceinline__ void tile_store(u64* buf, const TileRegs& r, u64 src_word, u32 n, u32 tid) {
+  const u32 head = (u32)(src_word & 1);
+  const u32 pairs = (n - head) >> 1;
+  if (tid == 0 && head) buf[0] = r.first;
+#pragma unroll
+  for (int c = 0; c < kTileChunks; ++c) {
+    const u32 i = tid + (u32)c * kMatBlock;
+    if (i < pairs) {
+      buf[head + 2 * i] = r.v[c].x;
+      buf[head + 2 * i + 1] = r.v[c].y;
+    }
+  }
+  if (tid == 0 && head + 2 * pairs < n) buf[n - 1] = r.last;
+}
+
 // Order of the short lists (overrides, grid overrides, rank patches): every entry against the
 // one before it, all lists of a kind in one sweep over their concatenation; where the key does
 // not ascend, a new list must begin.  The relocation lists, which are long, are checked where
@@ -494,6 +538,11 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p, u32 n_
   const u32 j = blockIdx.x, tid = threadIdx.x;
   const u32 m0 = blockIdx.y * p.map_group;
   const u32 m1 = min(m0 + p.map_group, d.n_maps);
+  // Template words and relocation entries that no other map group reads again, in an archive
+  // too large to stay in the L2s anyway (4,096 tiles = 64 MiB), are loaded non-temporally, so
+  // that the base map keeps its place in L2 for the gathers (config 4: 0.51 -> 0.47 ms); small
+  // archives stay cached for whoever reads them next.
+  const bool once = gridDim.y == 1 && n_tile_blocks >= 4096;
   MatTile ent;
   if constexpr (kSelf) {
     if (j >= n_tile_blocks) {  // launch dimensions, then the order of the short lists
@@ -536,6 +585,8 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p, u32 n_
     const u32 rl0 = (u32)d.src_reloc_off[s_graph], rl1 = (u32)d.src_reloc_off[s_graph + 1];
     const u32 ov0 = (u32)d.ovr_off[g], ov1 = (u32)d.ovr_off[g + 1];
     __syncthreads();  // everyone has read the sums; the buffer is free for the tile
+    TileRegs tile;
+    tile_load(tile, d.src_words + src_word, src_word, n_here, tid, once);  // in flight during the searches
     {
       // one cooperative search per wave: where the tile's slices of the template's relocation
       // list and of the graph's override list begin and end; then the patch slices of the
@@ -563,6 +614,7 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p, u32 n_
         }
       }
     }
+    tile_store(buf, tile, src_word, n_here, tid);  // c1
     __syncthreads();
     ent.src_word = src_word;
     ent.out_word = out_word;
@@ -588,12 +640,7 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p, u32 n_
   const u32 n = ent.n_words;
   if (n == 0) return;
   const u64* src = d.src_words + ent.src_word;
-  // Template words and relocation entries that no other map group reads again, in an archive
-  // too large to stay in the L2s anyway (4,096 tiles = 64 MiB), are loaded non-temporally, so
-  // that the base map keeps its place in L2 for the gathers (config 4: 0.51 -> 0.47 ms); small
-  // archives stay cached for whoever reads them next.
-  const bool once = gridDim.y == 1 && n_tile_blocks >= 4096;
-  stage_tile(buf, src, ent.src_word, n, tid, once);  // c1
+  if constexpr (!kSelf) stage_tile(buf, src, ent.src_word, n, tid, once);  // c1
   bool bad = false, disorder = false;
   u32 rk[kMatPre], rr[kMatPre];
   u64 ro[kMatPre];
