@@ -46,7 +46,8 @@ enum {
   FDY_PROF_MAT_MAIN = 7,
   FDY_PROF_SCAN_OUT = 8,
   FDY_PROF_SCAN_REBASE = 9,
-  FDY_PROF_SLOTS = 10
+  FDY_PROF_SCAN_RECORDS = 10, /* the launch ahead of the scan with output (scan_leafmap_kernel) */
+  FDY_PROF_SLOTS = 11
 };
 int fdy__prof_enable(int n_records);
 void fdy__prof_mask(unsigned slot_mask); /* which slots record; default all */

@@ -333,7 +333,7 @@ def tune_set(knob, value):
     return lib().fdy__tune_set(knob, value)
 
 
-PROF_SLOTS = 10
+PROF_SLOTS = 11
 
 
 PROF_SCAN_MAIN, PROF_MAT_MAIN, PROF_SCAN_OUT, PROF_SCAN_REBASE = 0, 7, 8, 9

@@ -178,6 +178,6 @@ extern "C" const char* fdy__prof_name(int slot) {
   static const char* names[FDY_PROF_SLOTS] = {
       "scan_kernel", "scan_init_kernel", "reloc_segment_kernel", "fp_key_kernel", "fp_group_kernel",
       "mat_prep_graphs_kernel", "mat_prep_tiles_kernel", "mat_main_kernel", "scan_out_kernel",
-      "scan_rebase_kernel"};
+      "scan_rebase_kernel", "scan_leafmap_kernel"};
   return slot >= 0 && slot < FDY_PROF_SLOTS ? names[slot] : "?";
 }

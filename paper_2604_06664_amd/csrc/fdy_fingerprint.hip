@@ -19,7 +19,12 @@ namespace fdy {
 namespace {
 
 constexpr u64 kP = 0x9e3779b97f4a7c15ull;
-constexpr int kFpBlock = 1024;
+// Threads per graph.  Measured on MI355X: the launch of a small kernel costs per wave (about
+// 2.6 ns each before the last one starts), so 1,024 threads for graphs of a few hundred nodes
+// are mostly launch; 256 are faster still for 576-node graphs (8.8 against 10.3 us for 67 of
+// them) but slower for 2,632-node ones (13.5 against 11.5), and the host does not know the
+// node counts.  512 is at least as fast as 1,024 on every shape tried.
+constexpr int kFpBlock = 512;
 
 __device__ __forceinline__ u64 mix(u64 x) {
   x ^= x >> 30;
@@ -100,30 +105,32 @@ __device__ __forceinline__ u32 table_first(const u32* table, u32 mask, KeyAt key
 }
 
 // Given first[g] in template_id[g]: ranks the firsts (chunked exclusive scan over the graphs, in
-// order), writes tmpl_graph and replaces template_id by the dense ids.  One workgroup of 1024.
+// order), writes tmpl_graph and replaces template_id by the dense ids.  One workgroup of T threads.
+template <int T>
 __device__ void rank_firsts(u32 G, u32* template_id, u32* tmpl_graph, u32* n_templates) {
-  __shared__ u32 s_w[17];
+  constexpr int kW = T / 64;
+  __shared__ u32 s_w[kW + 1];
   __shared__ u32 s_carry;
   const u32 tid = threadIdx.x, l = lane_id(), w = tid >> 6;
   constexpr u32 kMark = 0x80000000u;
   if (tid == 0) s_carry = 0;
   __syncthreads();
-  for (u32 g0 = 0; g0 < G; g0 += 1024) {
+  for (u32 g0 = 0; g0 < G; g0 += T) {
     const u32 g = g0 + tid;
     const bool first = g < G && template_id[g] == g;
     const u64 b = ballot(first);
     if (l == 0) s_w[w] = __popcll(b);
     __syncthreads();
     if (w == 0) {
-      const u32 x = l < 16 ? s_w[l] : 0;
+      const u32 x = l < (u32)kW ? s_w[l] : 0;
       u32 xi = x;
 #pragma unroll
-      for (int d = 1; d < 16; d <<= 1) {
+      for (int d = 1; d < kW; d <<= 1) {
         const u32 o = __shfl_up(xi, d);
         if (l >= (u32)d) xi += o;
       }
-      if (l < 16) s_w[l] = xi - x;
-      if (l == 15) s_w[16] = xi;
+      if (l < (u32)kW) s_w[l] = xi - x;
+      if (l == (u32)kW - 1) s_w[kW] = xi;
     }
     __syncthreads();
     if (first) {
@@ -132,88 +139,116 @@ __device__ void rank_firsts(u32 G, u32* template_id, u32* tmpl_graph, u32* n_tem
       if (tmpl_graph) tmpl_graph[rank] = g;
     }
     __syncthreads();
-    if (tid == 0) s_carry += s_w[16];
+    if (tid == 0) s_carry += s_w[kW];
     __syncthreads();
   }
   // everyone else copies the rank of its first; then the marks come off
-  for (u32 g = tid; g < G; g += 1024) {
+  for (u32 g = tid; g < G; g += T) {
     const u32 v = template_id[g];
     if (!(v & kMark)) template_id[g] = template_id[v] & ~kMark;
   }
   __syncthreads();
-  for (u32 g = tid; g < G; g += 1024) {
+  for (u32 g = tid; g < G; g += T) {
     const u32 v = template_id[g];
     if (v & kMark) template_id[g] = v & ~kMark;
   }
   if (tid == 0) *n_templates = s_carry;
 }
 
-// At most one graph per thread (G <= 1024): keys, firsts and ranks stay in LDS and registers, and
-// the outputs are written once; the only round trips to memory are the load of the keys and the
-// stores of the results.  (The general form below goes through template_id in memory between its
-// steps, which is four more round trips: as long as everything else this launch does.)
+// Up to kSmallGraphs graphs: keys, firsts and ranks stay in LDS and registers, and the outputs
+// are written once; the only round trips to memory are the load of the keys and the stores of
+// the results.  (The general form below goes through template_id in memory between its steps,
+// which is four more round trips: as long as everything else this launch does.)
+constexpr u32 kSmallGraphs = 1024;
+template <int T>
 __device__ void group_small(const u64* keys, u32 G, u32* template_id, u32* tmpl_graph, u32* n_templates,
                             u32* table /* LDS, at least twice the graphs */) {
-  __shared__ u64 s_keys[1024];
-  __shared__ u32 s_rank[1024];
-  __shared__ u32 s_cnt[17];
-  const u32 g = threadIdx.x, l = lane_id(), w = g >> 6;
+  constexpr int kW = T / 64, kPer = kSmallGraphs / T;
+  __shared__ u64 s_keys[kSmallGraphs];
+  __shared__ u32 s_rank[kSmallGraphs];
+  __shared__ u32 s_cnt[kW + 1];
+  const u32 tid = threadIdx.x, l = lane_id(), w = tid >> 6;
   u32 slots = 64;
   while (slots < 2 * G) slots <<= 1;
   const u32 mask = slots - 1;
-  for (u32 i = g; i < slots; i += 1024) table[i] = kEmpty;
-  if (g < G) s_keys[g] = __hip_atomic_load(&keys[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (u32 i = tid; i < slots; i += T) table[i] = kEmpty;
+#pragma unroll
+  for (int c = 0; c < kPer; ++c) {
+    const u32 g = (u32)c * T + tid;
+    if (g < G) s_keys[g] = __hip_atomic_load(&keys[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   __syncthreads();
   auto key_at = [&](u32 h) { return s_keys[h]; };
-  if (g < G) table_insert(table, mask, key_at, g);
-  __syncthreads();
-  const u32 first = g < G ? table_first(table, mask, key_at, g) : kEmpty;
-  const bool is_first = g < G && first == g;
-  const u64 b = ballot(is_first);
-  if (l == 0) s_cnt[w] = __popcll(b);
-  __syncthreads();
-  if (w == 0) {
-    const u32 x = l < 16 ? s_cnt[l] : 0;
-    u32 xi = x;
 #pragma unroll
-    for (int d = 1; d < 16; d <<= 1) {
-      const u32 o = __shfl_up(xi, d);
-      if (l >= (u32)d) xi += o;
+  for (int c = 0; c < kPer; ++c) {
+    const u32 g = (u32)c * T + tid;
+    if (g < G) table_insert(table, mask, key_at, g);
+  }
+  __syncthreads();
+  u32 first[kPer];
+#pragma unroll
+  for (int c = 0; c < kPer; ++c) {
+    const u32 g = (u32)c * T + tid;
+    first[c] = g < G ? table_first(table, mask, key_at, g) : kEmpty;
+  }
+  u32 carry = 0;  // firsts in the chunks before this one (the same in every thread)
+#pragma unroll
+  for (int c = 0; c < kPer; ++c) {
+    if ((u32)c * T >= G) break;  // uniform
+    const u32 g = (u32)c * T + tid;
+    const bool is_first = g < G && first[c] == g;
+    const u64 b = ballot(is_first);
+    if (l == 0) s_cnt[w] = __popcll(b);
+    __syncthreads();
+    if (w == 0) {
+      const u32 x = l < (u32)kW ? s_cnt[l] : 0;
+      u32 xi = x;
+#pragma unroll
+      for (int d = 1; d < kW; d <<= 1) {
+        const u32 o = __shfl_up(xi, d);
+        if (l >= (u32)d) xi += o;
+      }
+      if (l < (u32)kW) s_cnt[l] = xi - x;
+      if (l == (u32)kW - 1) s_cnt[kW] = xi;
     }
-    if (l < 16) s_cnt[l] = xi - x;
-    if (l == 15) s_cnt[16] = xi;
+    __syncthreads();
+    if (is_first) {
+      const u32 rank = carry + s_cnt[w] + __popcll(b & lanemask_lt());
+      s_rank[g] = rank;
+      if (tmpl_graph) tmpl_graph[rank] = g;
+    }
+    carry += s_cnt[kW];
+    __syncthreads();
   }
-  __syncthreads();
-  if (is_first) {
-    const u32 rank = s_cnt[w] + __popcll(b & lanemask_lt());
-    s_rank[g] = rank;
-    if (tmpl_graph) tmpl_graph[rank] = g;
+#pragma unroll
+  for (int c = 0; c < kPer; ++c) {
+    const u32 g = (u32)c * T + tid;
+    if (g < G) template_id[g] = s_rank[first[c]];
   }
-  __syncthreads();
-  if (g < G) template_id[g] = s_rank[first];
-  if (g == 0) *n_templates = s_cnt[16];
+  if (tid == 0) *n_templates = carry;
 }
 
-// The whole grouping by one workgroup, table in LDS: up to kLdsGraphs graphs.
+// The whole grouping by one workgroup of T threads, table in LDS: up to kLdsGraphs graphs.
 constexpr u32 kLdsGraphs = 8192, kLdsSlots = 2 * kLdsGraphs;
+template <int T>
 __device__ void group_in_lds(const u64* keys, u32 G, u32* template_id, u32* tmpl_graph, u32* n_templates,
                              u32* table /* LDS, kLdsSlots */) {
-  if (G <= 1024) {
-    group_small(keys, G, template_id, tmpl_graph, n_templates, table);
+  if (G <= kSmallGraphs) {
+    group_small<T>(keys, G, template_id, tmpl_graph, n_templates, table);
     return;
   }
   const u32 tid = threadIdx.x;
   u32 slots = 64;  // at least twice the graphs
   while (slots < 2 * G) slots <<= 1;
   const u32 mask = slots - 1;
-  for (u32 i = tid; i < slots; i += 1024) table[i] = kEmpty;
+  for (u32 i = tid; i < slots; i += T) table[i] = kEmpty;
   __syncthreads();
   auto key_at = [&](u32 g) { return __hip_atomic_load(&keys[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
-  for (u32 g = tid; g < G; g += 1024) table_insert(table, mask, key_at, g);
+  for (u32 g = tid; g < G; g += T) table_insert(table, mask, key_at, g);
   __syncthreads();
-  for (u32 g = tid; g < G; g += 1024) template_id[g] = table_first(table, mask, key_at, g);
+  for (u32 g = tid; g < G; g += T) template_id[g] = table_first(table, mask, key_at, g);
   __syncthreads();
-  rank_firsts(G, template_id, tmpl_graph, n_templates);
+  rank_firsts<T>(G, template_id, tmpl_graph, n_templates);
 }
 
 struct FpArgs {
@@ -250,7 +285,14 @@ __global__ __launch_bounds__(kFpBlock) void fp_key_kernel(FpArgs a) {
   if (lo > N) lo = N;
   if (hi > N) hi = N;
   Seg s{0, 1};
-  for (u64 i = lo; i < hi; ++i) {
+  u64 i = lo;
+  for (; i + 4 <= hi; i += 4) {  // four nodes' loads and mixes side by side, folded in order
+    const u64 h0 = node_hash(a.nodes + n0 + i, a.mask), h1 = node_hash(a.nodes + n0 + i + 1, a.mask);
+    const u64 h2 = node_hash(a.nodes + n0 + i + 2, a.mask), h3 = node_hash(a.nodes + n0 + i + 3, a.mask);
+    s.v = (((s.v * kP + h0) * kP + h1) * kP + h2) * kP + h3;
+    s.p *= kP * kP * kP * kP;
+  }
+  for (; i < hi; ++i) {
     s.v = s.v * kP + node_hash(a.nodes + n0 + i, a.mask);
     s.p *= kP;
   }
@@ -307,14 +349,14 @@ __global__ __launch_bounds__(kFpBlock) void fp_key_kernel(FpArgs a) {
   __syncthreads();
   if (!s_last) return;
   if (tid == 0) __hip_atomic_store(a.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  group_in_lds(a.keys, G, a.template_id, a.tmpl_graph, a.n_templates, s_table);
+  group_in_lds<kFpBlock>(a.keys, G, a.template_id, a.tmpl_graph, a.n_templates, s_table);
 }
 
 // Grouping as a launch of its own: one workgroup, table in LDS.
 __global__ __launch_bounds__(1024) void fp_group_kernel(const u64* keys, u32 G, u32* template_id,
                                                         u32* tmpl_graph, u32* n_templates) {
   extern __shared__ __align__(16) u32 s_table[];
-  group_in_lds(keys, G, template_id, tmpl_graph, n_templates, s_table);
+  group_in_lds<1024>(keys, G, template_id, tmpl_graph, n_templates, s_table);
 }
 
 // More graphs than the LDS table holds: the table lies in the caller's workspace and the steps
@@ -332,7 +374,7 @@ __global__ void fp_table_first_kernel(const u64* keys, u32 G, const u32* table, 
   if (g < G) template_id[g] = table_first(table, mask, [&](u32 h) { return keys[h]; }, g);
 }
 __global__ __launch_bounds__(1024) void fp_rank_kernel(u32 G, u32* template_id, u32* tmpl_graph, u32* n_templates) {
-  rank_firsts(G, template_id, tmpl_graph, n_templates);
+  rank_firsts<1024>(G, template_id, tmpl_graph, n_templates);
 }
 
 u32 table_slots(u32 G) {

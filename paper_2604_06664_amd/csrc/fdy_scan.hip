@@ -1931,8 +1931,10 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   p.leafmap = nullptr;
   if (ordered_out && tp.leaf_lines) {
     uint4* lm = (uint4*)(tb + tp.off_leafmap);
+    prof_begin(FDY_PROF_SCAN_RECORDS, stream);
     hipLaunchKernelGGL(scan_leafmap_kernel, dim3((u32)(((u64)tp.leaf_lines * 8 + 255) / 256)), dim3(256), 0, stream,
                        (const uint4*)a.cleaf, (const u64*)d_new_base, n_alloc, tp.leaf_lines, lm);
+    prof_end(FDY_PROF_SCAN_RECORDS, stream);
     FDY_HIP_TRY(hipGetLastError());
     p.leafmap = lm;
   }
