@@ -13,15 +13,31 @@ from tests.cases import small
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("idx", [2, 3])
-def test_captured_step_replays_like_eager(idx):
+@pytest.mark.parametrize("idx,own_tiles", [(2, True), (3, True), (3, False)])
+def test_captured_step_replays_like_eager(idx, own_tiles):
+    """own_tiles False: the materialization is captured in its form with a prep launch (which
+    inputs this small would not take by themselves)."""
     import torch
 
     assert torch.cuda.is_available()
     import paper_2604_06664_amd as fdy
-    from tests.support import session
 
     fdy.lib()
+    default_limit = fdy.tune_get(fdy.TUNE_MAT_SELF_WGS)
+    if not own_tiles:
+        fdy.tune_set(fdy.TUNE_MAT_SELF_WGS, 0)
+    try:
+        _capture_and_replay(idx)
+    finally:
+        fdy.tune_set(fdy.TUNE_MAT_SELF_WGS, default_limit)
+
+
+def _capture_and_replay(idx):
+    import torch
+
+    import paper_2604_06664_amd as fdy
+    from tests.support import session
+
     ar = small(idx)
     run = session.PathRun(ar, reloc_capacity=len(ar.ptr_word) + 64)
     fused = session.ScanRebaseRun(ar.words, ar.table, ar.new_base[0])
