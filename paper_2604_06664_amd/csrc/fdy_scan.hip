@@ -414,7 +414,7 @@ constexpr u32 kUseCmid = 1u << 16, kUseCleaf = 1u << 17;  // flags that travel w
 // Interval search for N candidates per lane at once (each w lies inside the table's span).
 // The N chains are independent; writing every step for all of them lets their LDS and
 // global round trips overlap, which is what the dependent steps of one chain cannot do.
-template <int N, bool kK16 = false>
+template <int N, bool kK16 = false, bool kRecords = kK16>
 __device__ __forceinline__ void search(const ScanParams& p, const void* top_v, u64 span_lo, u32 shifts,
                                        const u64 (&w)[N], Found (&f)[N], u32& marked) {
   typedef typename std::conditional<kK16, unsigned short, u32>::type key_t;
@@ -567,7 +567,7 @@ __device__ __forceinline__ void search(const ScanParams& p, const void* top_v, u
     // bases in the same 128-byte memory line: the hit's new base, asked for a round trip later,
     // is then found in the L2 that has just fetched the line (from the base map itself, 8 bytes
     // at a random place of 8 MiB, three out of four such requests went on to the memory side).
-    const uint4* lm = kK16 ? p.leafmap : nullptr;
+    const uint4* lm = kRecords ? p.leafmap : nullptr;
     uint4 cq[N][2];
 #pragma unroll
     for (int c = 0; c < N; ++c) {
@@ -1264,10 +1264,10 @@ __device__ __forceinline__ void rebase_rounds(const ScanParams& p, const u32* to
     valid[r] = (r0 + r) * 64 + lane < Q;
     wv[r] = valid[r] ? qw[(r0 + r) * 64 + lane] : span_lo;
   }
-  search<N>(p, top, span_lo, shifts, wv, f, marked);
+  search<N, false, true>(p, top, span_lo, shifts, wv, f, marked);
   u64 nb[N];
 #pragma unroll
-  for (int r = 0; r < N; ++r) nb[r] = valid[r] && f[r].hit ? p.new_base[f[r].region] : 0;
+  for (int r = 0; r < N; ++r) nb[r] = valid[r] && f[r].hit ? *f[r].nb : 0;
 #pragma unroll
   for (int r = 0; r < N; ++r) {
     const bool hit = valid[r] && f[r].hit;
@@ -1929,7 +1929,7 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   p.cmid = a.cmid;
   p.cleaf = a.cleaf;
   p.leafmap = nullptr;
-  if (ordered_out && tp.leaf_lines) {
+  if ((ordered_out || fused) && tp.leaf_lines) {
     uint4* lm = (uint4*)(tb + tp.off_leafmap);
     prof_begin(FDY_PROF_SCAN_RECORDS, stream);
     hipLaunchKernelGGL(scan_leafmap_kernel, dim3((u32)(((u64)tp.leaf_lines * 8 + 255) / 256)), dim3(256), 0, stream,
