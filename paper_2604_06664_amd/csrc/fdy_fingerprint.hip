@@ -19,11 +19,10 @@ namespace fdy {
 namespace {
 
 constexpr u64 kP = 0x9e3779b97f4a7c15ull;
-// Threads per graph.  Measured on MI355X: the launch of a small kernel costs per wave (about
-// 2.6 ns each before the last one starts), so 1,024 threads for graphs of a few hundred nodes
-// are mostly launch; 256 are faster still for 576-node graphs (8.8 against 10.3 us for 67 of
-// them) but slower for 2,632-node ones (13.5 against 11.5), and the host does not know the
-// node counts.  512 is at least as fast as 1,024 on every shape tried.
+// Threads per graph.  Measured on MI355X: 1,024 threads are more than graphs of a few hundred
+// nodes can use; 256 are faster still for 576-node graphs (8.8 against 10.3 us for 67 of them)
+// but slower for 2,632-node ones (13.5 against 11.5), and the host does not know the node
+// counts.  512 is at least as fast as 1,024 on every shape tried.
 constexpr int kFpBlock = 512;
 
 __device__ __forceinline__ u64 mix(u64 x) {
