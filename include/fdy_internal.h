@@ -58,9 +58,15 @@ const char* fdy__prof_name(int slot);
 }
 
 namespace fdy {
-/* internal: bracket one launch; no-ops unless profiling is enabled */
+/* internal: bracket a group of launches with two event records; no-ops unless profiling is
+ * enabled */
 void prof_begin(int slot, void* stream);
 void prof_end(int slot, void* stream);
+/* internal: the next pair of events of a slot for ONE launch that carries them itself (the
+ * events then hold the kernel's own begin and end on the device, as a kernel trace reports
+ * them; two records around a launch add the dispatch on either side, 2-6 us).  False: this
+ * launch is not timed. */
+bool prof_take(int slot, void** start_event, void** stop_event);
 }  // namespace fdy
 #endif
 #endif

@@ -130,6 +130,16 @@ void fdy::prof_end(int slot, void* stream) {
   ++s.used;
 }
 
+bool fdy::prof_take(int slot, void** start_event, void** stop_event) {
+  if (!g_prof_n || !((g_prof_mask >> slot) & 1u)) return false;
+  ProfSlot& s = g_prof[slot];
+  if (s.used >= g_prof_n) return false;
+  *start_event = (void*)s.a[s.used];
+  *stop_event = (void*)s.b[s.used];
+  ++s.used;
+  return true;
+}
+
 extern "C" int fdy__prof_enable(int n_records) {
   for (auto& s : g_prof) {
     for (auto e : s.a) (void)hipEventDestroy(e);

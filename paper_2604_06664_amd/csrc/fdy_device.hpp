@@ -1,9 +1,11 @@
 // Internal helpers shared by the HIP kernels of libfdy (gfx950, wave64).  Not installed.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "fdy.h"
+#include "fdy_internal.h"
 
 #define FDY_WAVE 64
 
@@ -95,6 +97,20 @@ __device__ inline u64 block_excl_scan(u64 v, u64* s_buf, u64& total) {
   total = s_buf[16];
   __syncthreads();
   return r;
+}
+
+// One kernel launch on the caller's stream; when the bench has switched timing on for `slot`,
+// the launch carries a pair of events that receive the kernel's own begin and end.
+template <typename... KArgs, typename... Args>
+inline void launch(int slot, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                   Args&&... args) {
+  static_assert(sizeof...(KArgs) == sizeof...(Args), "one argument per kernel parameter");
+  void *a = nullptr, *b = nullptr;
+  if (prof_take(slot, &a, &b))
+    hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, stream, (hipEvent_t)a, (hipEvent_t)b, 0u,
+                          static_cast<KArgs>(args)...);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, lds, stream, static_cast<KArgs>(args)...);
 }
 
 }  // namespace fdy

@@ -407,9 +407,7 @@ static int fingerprint_launch(FpArgs a, uint32_t n_graphs, uint32_t n_boundaries
     if (lds > 32768)
       FDY_HIP_TRY(hipFuncSetAttribute((const void*)fp_key_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                       (int)(kLdsSlots * 4)));
-    prof_begin(FDY_PROF_FP_KEYS, stream);
-    hipLaunchKernelGGL(fp_key_kernel, dim3(n_graphs), dim3(kFpBlock), lds, stream, a);
-    prof_end(FDY_PROF_FP_KEYS, stream);
+    launch(FDY_PROF_FP_KEYS, fp_key_kernel, dim3(n_graphs), dim3(kFpBlock), lds, stream, a);
     FDY_HIP_TRY(hipGetLastError());
     if (n_graphs == 1 || a.counter) return FDY_OK;  // the key kernel has written the grouping too
   }
@@ -417,10 +415,8 @@ static int fingerprint_launch(FpArgs a, uint32_t n_graphs, uint32_t n_boundaries
     if (lds_table > 32768)
       FDY_HIP_TRY(hipFuncSetAttribute((const void*)fp_group_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                       (int)(kLdsSlots * 4)));
-    prof_begin(FDY_PROF_FP_GROUP, stream);
-    hipLaunchKernelGGL(fp_group_kernel, dim3(1), dim3(1024), lds_table, stream,
-                       (const u64*)a.keys, n_graphs, a.template_id, a.tmpl_graph, a.n_templates);
-    prof_end(FDY_PROF_FP_GROUP, stream);
+    launch(FDY_PROF_FP_GROUP, fp_group_kernel, dim3(1), dim3(1024), lds_table, stream, (const u64*)a.keys, n_graphs,
+           a.template_id, a.tmpl_graph, a.n_templates);
     FDY_HIP_TRY(hipGetLastError());
     return FDY_OK;
   }

@@ -1034,19 +1034,15 @@ static int materialize_launch(const fdy_mat_desc* h_desc, uint64_t* d_out_words,
   const u64 self_limit = (u64)fdy__tune_get(FDY_TUNE_MAT_SELF_WGS);
   if (d.n_graphs <= kSelfGraphs && p.map_group <= kSelfMaxGroup && p.ws.max_tiles &&
       (u64)p.ws.max_tiles * n_groups <= self_limit) {
-    prof_begin(FDY_PROF_MAT_MAIN, stream);
-    hipLaunchKernelGGL(mat_main_kernel<true>, dim3(p.ws.max_tiles + nb_dims_all + kCheckBlocks, n_groups),
-                       dim3(kMatBlock), 0, stream, p, p.ws.max_tiles, nb_dims_all);
-    prof_end(FDY_PROF_MAT_MAIN, stream);
+    launch(FDY_PROF_MAT_MAIN, mat_main_kernel<true>, dim3(p.ws.max_tiles + nb_dims_all + kCheckBlocks, n_groups),
+           dim3(kMatBlock), 0, stream, p, p.ws.max_tiles, nb_dims_all);
     FDY_HIP_TRY(hipGetLastError());
     return FDY_OK;
   }
 
   const bool own_sums = d.n_graphs <= kOwnSumsMax;
   if (!own_sums) {
-    prof_begin(FDY_PROF_MAT_PREP_GRAPHS, stream);
-    hipLaunchKernelGGL(mat_prep_graphs_kernel, dim3(1), dim3(1024), 0, stream, p);
-    prof_end(FDY_PROF_MAT_PREP_GRAPHS, stream);
+    launch(FDY_PROF_MAT_PREP_GRAPHS, mat_prep_graphs_kernel, dim3(1), dim3(1024), 0, stream, p);
     FDY_HIP_TRY(hipGetLastError());
   }
   u32 nb_tiles = (p.ws.max_tiles + kPrepTiles - 1) / kPrepTiles;
@@ -1054,20 +1050,14 @@ static int materialize_launch(const fdy_mat_desc* h_desc, uint64_t* d_out_words,
   const u32 nb_dims = (d_out_dims && d.out_nodes_total) ? (u32)((d.out_nodes_total + 255) / 256) : 0;
   if (own_sums && nb_tiles + nb_patch + nb_dims == 0) nb_tiles = 1;  // someone has to verify the totals
   if (nb_tiles + nb_patch + nb_dims) {
-    prof_begin(FDY_PROF_MAT_PREP_TILES, stream);
     const u32 nb = nb_tiles + nb_patch + nb_dims + kCheckBlocks;
-    if (own_sums)
-      hipLaunchKernelGGL(mat_prep_tiles_kernel<true>, dim3(nb), dim3(256), 0, stream, p, nb_tiles, nb_patch);
-    else
-      hipLaunchKernelGGL(mat_prep_tiles_kernel<false>, dim3(nb), dim3(256), 0, stream, p, nb_tiles, nb_patch);
-    prof_end(FDY_PROF_MAT_PREP_TILES, stream);
+    launch(FDY_PROF_MAT_PREP_TILES, own_sums ? mat_prep_tiles_kernel<true> : mat_prep_tiles_kernel<false>, dim3(nb),
+           dim3(256), 0, stream, p, nb_tiles, nb_patch);
     FDY_HIP_TRY(hipGetLastError());
   }
   if (p.ws.max_tiles) {
-    prof_begin(FDY_PROF_MAT_MAIN, stream);
-    hipLaunchKernelGGL(mat_main_kernel<false>, dim3(p.ws.max_tiles, n_groups), dim3(kMatBlock), 0, stream, p,
-                       p.ws.max_tiles, 0u);
-    prof_end(FDY_PROF_MAT_MAIN, stream);
+    launch(FDY_PROF_MAT_MAIN, mat_main_kernel<false>, dim3(p.ws.max_tiles, n_groups), dim3(kMatBlock), 0, stream, p,
+           p.ws.max_tiles, 0u);
     FDY_HIP_TRY(hipGetLastError());
   }
   return FDY_OK;

@@ -1822,9 +1822,7 @@ extern "C" int fdy_scan_table_prepare(const fdy_alloc* d_table, uint32_t n_alloc
   a.n_chunks = (u32)((state_bytes(max_words) - kStateHeader) / 8);
   a.d_count = nullptr;
   const u32 n_init = init_threads(tp, a.n_chunks);
-  prof_begin(FDY_PROF_SCAN_INIT, stream);
-  hipLaunchKernelGGL(scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream, a);
-  prof_end(FDY_PROF_SCAN_INIT, stream);
+  launch(FDY_PROF_SCAN_INIT, scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream, a);
   FDY_HIP_TRY(hipGetLastError());
   return FDY_OK;
 }
@@ -1890,9 +1888,7 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
     a.n_chunks = rp.n_chunks;
     a.d_count = nothing ? (u64*)d_count : nullptr;
     const u32 n_init = init_threads(tp, rp.n_chunks);
-    prof_begin(FDY_PROF_SCAN_INIT, stream);
-    hipLaunchKernelGGL(scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream, a);
-    prof_end(FDY_PROF_SCAN_INIT, stream);
+    launch(FDY_PROF_SCAN_INIT, scan_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, stream, a);
     FDY_HIP_TRY(hipGetLastError());
   }
   if (rp.n_sub == 0) return FDY_OK;
@@ -1931,10 +1927,8 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   p.leafmap = nullptr;
   if ((ordered_out || fused) && tp.leaf_lines) {
     uint4* lm = (uint4*)(tb + tp.off_leafmap);
-    prof_begin(FDY_PROF_SCAN_RECORDS, stream);
-    hipLaunchKernelGGL(scan_leafmap_kernel, dim3((u32)(((u64)tp.leaf_lines * 8 + 255) / 256)), dim3(256), 0, stream,
-                       (const uint4*)a.cleaf, (const u64*)d_new_base, n_alloc, tp.leaf_lines, lm);
-    prof_end(FDY_PROF_SCAN_RECORDS, stream);
+    launch(FDY_PROF_SCAN_RECORDS, scan_leafmap_kernel, dim3((u32)(((u64)tp.leaf_lines * 8 + 255) / 256)), dim3(256),
+           0, stream, (const uint4*)a.cleaf, (const u64*)d_new_base, n_alloc, tp.leaf_lines, lm);
     FDY_HIP_TRY(hipGetLastError());
     p.leafmap = lm;
   }
@@ -1956,9 +1950,7 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
     if (fgrid > (n_groups + kWaves - 1) / kWaves) fgrid = (n_groups + kWaves - 1) / kWaves;
     FDY_HIP_TRY(hipFuncSetAttribute((const void*)scan_rebase_kernel,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    prof_begin(FDY_PROF_SCAN_REBASE, stream);
-    hipLaunchKernelGGL(scan_rebase_kernel, dim3(fgrid), dim3(kBlock), lds, stream, p);
-    prof_end(FDY_PROF_SCAN_REBASE, stream);
+    launch(FDY_PROF_SCAN_REBASE, scan_rebase_kernel, dim3(fgrid), dim3(kBlock), lds, stream, p);
     FDY_HIP_TRY(hipGetLastError());
     return FDY_OK;
   }
@@ -1978,9 +1970,7 @@ static int scan_launch(const uint64_t* d_words, uint64_t n_words, const fdy_allo
   auto kern = stage ? pick(std::true_type{}) : pick(std::false_type{});
   FDY_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const int slot = ordered_out ? FDY_PROF_SCAN_OUT : FDY_PROF_SCAN_MAIN;
-  prof_begin(slot, stream);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), lds, stream, p);
-  prof_end(slot, stream);
+  launch(slot, kern, dim3(grid), dim3(kBlock), lds, stream, p);
   FDY_HIP_TRY(hipGetLastError());
   return FDY_OK;
 }
@@ -2050,11 +2040,8 @@ extern "C" int fdy_reloc_segment(const fdy_reloc* d_relocs, const uint64_t* d_co
   if (!d_count || !d_word_off || !d_reloc_off) return FDY_ERR_INVALID_ARG;
   if (reloc_capacity && !d_relocs) return FDY_ERR_INVALID_ARG;
   (void)hipGetLastError();
-  prof_begin(FDY_PROF_SEGMENT, hip_stream);
-  hipLaunchKernelGGL(reloc_segment_kernel, dim3((n_off + 3) / 4), dim3(256), 0,
-                     (hipStream_t)hip_stream, d_relocs, (const u64*)d_count, reloc_capacity,
-                     (const u64*)d_word_off, n_off, (u64*)d_reloc_off);
-  prof_end(FDY_PROF_SEGMENT, hip_stream);
+  launch(FDY_PROF_SEGMENT, reloc_segment_kernel, dim3((n_off + 3) / 4), dim3(256), 0, (hipStream_t)hip_stream,
+         d_relocs, (const u64*)d_count, reloc_capacity, (const u64*)d_word_off, n_off, (u64*)d_reloc_off);
   FDY_HIP_TRY(hipGetLastError());
   return FDY_OK;
 }
