@@ -30,11 +30,13 @@ int fdy__tune_get(int knob);
 /* returns the previous value, or -1 for an unknown knob / value out of range */
 int fdy__tune_set(int knob, int value);
 
-/* Per-kernel timing for the bench: when enabled with a record count n > 0, each launch of
- * an instrumented kernel is bracketed by a hipEvent pair on the caller's stream (at most n
- * launches per slot are recorded, later ones are not).  fdy__prof_read synchronizes the
- * recorded events and returns, per slot, the number of records and their total elapsed
- * milliseconds; fdy__prof_enable(0) destroys the events.  Not thread-safe; off by default. */
+/* Per-kernel timing for the bench: when enabled with a record count n > 0, each launch of an
+ * instrumented kernel carries a hipEvent pair (hipExtLaunchKernelGGL) that receives the kernel's
+ * begin and end on the caller's stream (at most n launches per slot are recorded, later ones are
+ * not; a group of launches that shares a slot is bracketed by two event records instead).
+ * fdy__prof_read synchronizes the recorded events and returns, per slot, the number of records
+ * and their total elapsed milliseconds; fdy__prof_enable(0) destroys the events.  Not
+ * thread-safe; off by default. */
 enum {
   FDY_PROF_SCAN_MAIN = 0,
   FDY_PROF_SCAN_INIT = 1,
