@@ -400,6 +400,7 @@ def main():
                    "maps": main_res["maps"], "relocs": main_res["relocs"],
                    "step": main_res["step"]},
         "graphs_materialized_per_s": round(main_res["graphs_per_s"], 1),
+        "launches_per_step": main_res["launches_per_step"],
         "algorithmic_bytes_per_step": main_res["algorithmic_bytes_per_step"],
         "frac_hbm_peak_step": main_res["frac_hbm_peak_step"],
         "two_call_path": main_res.get("two_call_path"),
