@@ -23,6 +23,8 @@ enum {
   FDY_TUNE_SCAN_SMALL_LOG2 = 4, /* inputs below 2^this sub-tiles use the small-chunk scan   */
   FDY_TUNE_MAT_SELF_WGS = 5,    /* materialize launches of up to this many workgroups       *
                                  * resolve their tiles themselves (no prep launch); 0: none */
+  FDY_TUNE_MAT_ONCE_TILES = 6,  /* a materialization of one map group over at least this many   *
+                                 * tiles streams templates and relocation lists past the L2s  */
   FDY_TUNE_COUNT = 8
 };
 

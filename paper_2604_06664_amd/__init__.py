@@ -27,6 +27,7 @@ FDY_ERR_HIP, FDY_ERR_WORKSPACE, FDY_ERR_ORDER = -4, -5, -6
 TUNE_SCAN_TOP_LOG2, TUNE_SCAN_WG_PER_CU, TUNE_SCAN_SPIN_LIMIT, TUNE_MAT_MAP_GROUP = 0, 1, 2, 3
 TUNE_SCAN_SMALL_LOG2 = 4
 TUNE_MAT_SELF_WGS = 5
+TUNE_MAT_ONCE_TILES = 6
 
 
 class FdyError(RuntimeError):

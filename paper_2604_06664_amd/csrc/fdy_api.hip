@@ -14,9 +14,10 @@ int g_tune[FDY_TUNE_COUNT] = {
     /* MAT_MAP_GROUP     */ 0,
     /* SCAN_SMALL_LOG2 */ 12,
     /* MAT_SELF_WGS    */ 1024,
-    0, 0};
-const int g_tune_lo[FDY_TUNE_COUNT] = {1, 1, 0, 0, 0, 0, 0, 0};
-const int g_tune_hi[FDY_TUNE_COUNT] = {14, 16, 1 << 30, 64, 31, 1 << 30, 0, 0};
+    /* MAT_ONCE_TILES  */ 4096,
+    0};
+const int g_tune_lo[FDY_TUNE_COUNT] = {1, 1, 0, 0, 0, 0, 1, 0};
+const int g_tune_hi[FDY_TUNE_COUNT] = {14, 16, 1 << 30, 64, 31, 1 << 30, 1 << 30, 0};
 }  // namespace
 
 extern "C" int fdy__tune_get(int knob) {

@@ -80,6 +80,7 @@ struct MatParams {
   u32* out_dims;
   u32* d_status;
   u32 map_group;  // consecutive base maps handled by one workgroup of the main kernel
+  u32 stream_once;  // templates and relocation lists are read once and too large to stay cached
 };
 
 // Word and node counts of output graph g (those of its template).  False, with zero counts, if
@@ -539,10 +540,11 @@ __global__ __launch_bounds__(kMatBlock) void mat_main_kernel(MatParams p, u32 n_
   const u32 m0 = blockIdx.y * p.map_group;
   const u32 m1 = min(m0 + p.map_group, d.n_maps);
   // Template words and relocation entries that no other map group reads again, in an archive
-  // too large to stay in the L2s anyway (4,096 tiles = 64 MiB), are loaded non-temporally, so
-  // that the base map keeps its place in L2 for the gathers (config 4: 0.51 -> 0.47 ms); small
-  // archives stay cached for whoever reads them next.
-  const bool once = gridDim.y == 1 && n_tile_blocks >= 4096;
+  // too large to stay in the L2s anyway (the host decides: one map group, and from 4,096 tiles
+  // = 64 MiB on, twice the chip's L2s), are loaded non-temporally, so that the base map keeps
+  // its place in L2 for the gathers (config 4: 0.51 -> 0.47 ms); small archives stay cached for
+  // whoever reads them next.
+  const bool once = p.stream_once != 0;
   MatTile ent;
   if constexpr (kSelf) {
     if (j >= n_tile_blocks) {  // launch dimensions, then the order of the short lists
@@ -1029,6 +1031,7 @@ static int materialize_launch(const fdy_mat_desc* h_desc, uint64_t* d_out_words,
   if (mg == 0) mg = d.map_rank ? 4 : 2;
   p.map_group = mg < d.n_maps ? mg : d.n_maps;
   const u32 n_groups = (d.n_maps + p.map_group - 1) / p.map_group;
+  p.stream_once = n_groups == 1 && p.ws.max_tiles >= (u32)fdy__tune_get(FDY_TUNE_MAT_ONCE_TILES) ? 1u : 0u;
   const u32 nb_dims_all = (d_out_dims && d.out_nodes_total) ? (u32)((d.out_nodes_total + 255) / 256) : 0;
   // A launch small enough that all its workgroups run side by side resolves its tiles itself.
   const u64 self_limit = (u64)fdy__tune_get(FDY_TUNE_MAT_SELF_WGS);
